@@ -1,0 +1,137 @@
+"""Channel-aligned homomorphic convolution (CAConv) on the oracle.  TEST INFRASTRUCTURE ONLY.
+
+Follows the paper's order of operations: Slide_f (the f^2 rotations of the input,
+Algorithm 1 first subroutine), MulFilter&Sum_f (Algorithm 1 second subroutine) once per
+output ciphertext, Rescale (one level per SISO, Section 3.4), then rotate-and-sum over the
+outermost channel dimension C_a (Section 2.2 "RaS", Section 3.1 "CAConv"), which leaves the
+sum replicated in every C_a block because rotation is cyclic.
+
+Data format pi_CA = {C_a, H, W, R_g} with C_g = 1 (Section 3):
+    slot(c, h, w, r) = ((c*H + h)*W + w)*R + r,   C_a*H*W*R = N/2,
+every replica r holding the same input value x[c, h, w].
+Output ciphertext o, replica r carries output channel co = (o*R + r) mod c_out.
+"""
+import numpy as np
+
+from .ckks_client import encode
+from .he_oracle import Oracle
+
+
+class ConvGeometry:
+    def __init__(self, N, C_a, H, W, c_out, f=3, stride=1):
+        assert f % 2 == 1
+        self.N, self.C_a, self.H, self.W, self.c_out, self.f, self.stride = N, C_a, H, W, c_out, f, stride
+        slots = N // 2
+        assert slots % (C_a * H * W) == 0
+        self.R = slots // (C_a * H * W)
+        self.n_out = -(-c_out // self.R)
+        half = (f - 1) // 2
+        # Slide_f amounts (Algorithm 1: r = w_i*(j1-(f-1)/2) + (j2-(f-1)/2)), times the inner stride R
+        self.taps = [(dy, dx) for dy in range(-half, half + 1) for dx in range(-half, half + 1)]
+        self.tap_steps = [((dy * W + dx) * self.R) % slots for dy, dx in self.taps]
+        # RaS over C_a: strides H*W*R * 2^t
+        self.ras_steps = [H * W * self.R * (1 << t) for t in range(int(np.log2(C_a)))]
+        assert (1 << len(self.ras_steps)) == C_a
+
+    def slot(self, c, h, w, r):
+        return ((c * self.H + h) * self.W + w) * self.R + r
+
+    def out_channel(self, o, r):
+        return (o * self.R + r) % self.c_out
+
+    def pack_input(self, x):
+        """x[C_a][H][W] -> slot vector [N/2], each value replicated R times."""
+        assert x.shape == (self.C_a, self.H, self.W)
+        return np.repeat(x.reshape(-1), self.R).astype(np.float64)
+
+    def weight_slots(self, wt, o, tap):
+        """Slot vector of the filter plaintext for output ciphertext o and tap (dy,dx):
+        Wt[co(o,r), c, dy+half, dx+half] where the tap reads inside the image, else 0
+        (zero padding by masking); for stride s only output pixels with h,w multiples of s
+        are kept."""
+        dy, dx = self.taps[tap]
+        half = (self.f - 1) // 2
+        v = np.zeros((self.C_a, self.H, self.W, self.R), dtype=np.float64)
+        for r in range(self.R):
+            co = self.out_channel(o, r)
+            for h in range(0, self.H):
+                if not (0 <= h + dy < self.H) or h % self.stride:
+                    continue
+                for w in range(0, self.W):
+                    if not (0 <= w + dx < self.W) or w % self.stride:
+                        continue
+                    v[:, h, w, r] = wt[co, :, dy + half, dx + half]
+        return v.reshape(-1)
+
+    def unpack_output(self, z_list):
+        """Decoded slot vectors of the n_out outputs -> (out[c_out][H][W] from block c'=0,
+        max spread over the C_a replicated blocks)."""
+        out = np.zeros((self.c_out, self.H, self.W), dtype=np.float64)
+        spread = 0.0
+        for o, z in enumerate(z_list):
+            v = np.asarray(z).real.reshape(self.C_a, self.H, self.W, self.R)
+            spread = max(spread, float(np.max(np.abs(v - v[0:1]))))
+            for r in range(self.R):
+                out[self.out_channel(o, r)] = v[0, :, :, r]
+        return out, spread
+
+
+def encode_weights(orc: Oracle, geo: ConvGeometry, wt, level, pt_scale):
+    """All n_out*f^2 filter plaintexts at `level`, NTT form: uint64 [n_out][f^2][level+1][N]."""
+    mods = list(range(level + 1))
+    pts = np.empty((geo.n_out, len(geo.taps), level + 1, orc.N), dtype=np.uint64)
+    for o in range(geo.n_out):
+        for t in range(len(geo.taps)):
+            m = encode(geo.weight_slots(wt, o, t).astype(np.complex128), orc.N, pt_scale)
+            pts[o, t] = orc.ntt(orc.reduce_signed(m, mods), mods)
+    return pts
+
+
+def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False):
+    """ct [2][level+1][N] -> list of n_out ciphertexts [2][level][N].
+
+    evks: dict slot-step -> evaluation key of the Galois element 5^step.
+    With keep=True also returns every intermediate (for limb-by-limb parity checks)."""
+    inter = {"slide": [], "mac": [], "rescaled": [], "ras": []}
+    # Slide_f: all rotations of the one input share a single ModUp of c1 (same bits as
+    # separate rotations by construction)
+    raised = orc.modup(ct[1], level)
+    slid = []
+    for step in geo.tap_steps:
+        if step == 0:
+            slid.append(ct.copy())
+        else:
+            slid.append(orc.rotate_from_raised(ct, raised, level, orc.galois_elt(step), evks[step]))
+    inter["slide"] = slid
+    outs = []
+    for o in range(geo.n_out):
+        acc = None
+        for t in range(len(geo.taps)):
+            acc = orc.ptct_mac(acc, slid[t], pts[o, t], level, init=(t == 0))
+        inter["mac"].append(acc)
+        cur = orc.rescale(acc, level)
+        inter["rescaled"].append(cur)
+        steps_out = []
+        for step in geo.ras_steps:
+            rot = orc.rotate(cur, level - 1, orc.galois_elt(step), evks[step])
+            cur = orc.add(cur, rot, level - 1)
+            steps_out.append(cur)
+        inter["ras"].append(steps_out)
+        outs.append(cur)
+    return (outs, inter) if keep else outs
+
+
+def conv2d_float(x, wt, stride=1):
+    """Direct float64 cross-correlation with zero 'same' padding (the plaintext reference)."""
+    c_out, c_in, f, _ = wt.shape
+    _, H, W = x.shape
+    half = (f - 1) // 2
+    out = np.zeros((c_out, H, W), dtype=np.float64)
+    for co in range(c_out):
+        for c in range(c_in):
+            for dy in range(-half, half + 1):
+                for dx in range(-half, half + 1):
+                    h0, h1 = max(0, -dy), min(H, H - dy)
+                    w0, w1 = max(0, -dx), min(W, W - dx)
+                    out[co, h0:h1, w0:w1] += wt[co, c, dy + half, dx + half] * x[c, h0 + dy:h1 + dy, w0 + dx:w1 + dx]
+    return out[:, ::stride, ::stride] if stride > 1 else out
