@@ -1,0 +1,161 @@
+/*
+ * he_mi355x.h - C ABI of the MI355X (gfx950) library for the homomorphic convolution layer
+ * over RNS-CKKS ciphertexts: slot rotations (Galois automorphism + hybrid key switching),
+ * plaintext-ciphertext multiply-accumulate and rescale, all resting on batched negacyclic
+ * NTT/iNTT over 64-bit RNS limbs.
+ *
+ * The paper (HyPHEN, arXiv 2302.02407) states the problem as sequences of RNS-CKKS
+ * operations - CRot, MulPt, AddCt, Rescale (Section 2.1, Table 1), assembled into SISO
+ * convolution (Algorithm 1), rotate-and-sum (Section 2.2) and channel-aligned convolution
+ * CAConv (Section 3.1) - and takes the operations themselves from an RNS-CKKS library with
+ * hybrid key switching (decomposition number dnum; Appendix, parameter sets).  Each entry
+ * point below is one of those operations or one stage inside CRot.
+ *
+ * Conventions (all entry points)
+ *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every
+ *    buffer it passes; the context owns only its precomputed tables and its workspace.
+ *  - A polynomial limb is N = 2^logN uint64 residues in [0, m) of one modulus m.  Buffers are
+ *    limb-major: [poly][limb][N].  A ciphertext at level l is [2][l+1][N] (c0 then c1) over
+ *    q_0..q_l.
+ *  - "NTT form": position j holds the evaluation at psi^(2*bitrev(j)+1), psi the primitive
+ *    2N-th root of the modulus given by he_ctx_psi.  Ciphertexts, plaintexts and keys are in
+ *    NTT form unless a call says otherwise.
+ *  - Modulus index space: 0..nq-1 = q_0..q_L (ciphertext primes), nq..nq+np-1 = special primes.
+ *  - Every call returns HE_OK (0) or a negative he_status; he_last_error() gives the text.
+ *    Calls never abort and never throw.  Work is enqueued on the context's HIP stream and is
+ *    NOT synchronised on return unless stated.
+ *  - A context is not thread-safe; calls on one context must not overlap (they share its
+ *    workspace).
+ */
+#ifndef HE_MI355X_H
+#define HE_MI355X_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct he_ctx he_ctx;
+
+typedef enum {
+    HE_OK = 0,
+    HE_ERR_BADARG = -1, /* null pointer, size or index out of range, even Galois element ... */
+    HE_ERR_LEVEL = -2,  /* level outside 0..L (or 1..L for rescale) */
+    HE_ERR_NOKEY = -3,  /* no evaluation key registered for the Galois element */
+    HE_ERR_ALLOC = -4,  /* device or host allocation failed */
+    HE_ERR_HIP = -5     /* a HIP runtime call or kernel launch failed */
+} he_status;
+
+/* Operation counts since creation / last reset (paper: cost table of the convolutions counts
+ * rotations per stage; these let a caller check CAConv issues f^2-1 Slide + n_o*log2(C_a) RaS
+ * key switches and no other). */
+typedef struct {
+    uint64_t keyswitch;   /* inner product + ModDown pairs executed */
+    uint64_t modup;       /* digit decompositions (ModUp of one polynomial) */
+    uint64_t ntt_limbs;   /* forward limb transforms */
+    uint64_t intt_limbs;  /* inverse limb transforms */
+    uint64_t mac;         /* plaintext-ciphertext products accumulated */
+    uint64_t rescale;     /* ciphertext rescales */
+    uint64_t automorph;   /* limb permutations (explicit calls and c0 of rotations) */
+} he_counters_t;
+
+/* Geometry and operands of one channel-aligned convolution (paper Section 3.1, CAConv on the
+ * data format pi_CA = {C_a, H, W, R_g}; slot(c,h,w,r) = ((c*H+h)*W+w)*R + r, C_a*H*W*R = N/2).
+ * d_weights[o*f*f + t] is the filter plaintext of output ciphertext o and tap t (row-major
+ * taps, dy outer, dx inner, both from -(f-1)/2), NTT form at `level`, [level+1][N]. */
+typedef struct {
+    uint32_t C_a, H, W, R;       /* slot layout of the input ciphertext */
+    uint32_t f;                  /* odd filter width (1, 3, 5, ...) */
+    uint32_t n_out;              /* number of output ciphertexts */
+    uint32_t level;              /* level of the input; outputs are at level-1 */
+    const uint64_t* const* h_d_weights; /* host array of n_out*f*f device pointers */
+} he_conv_plan;
+
+/* Create a context: ring degree 2^logN (8 <= logN <= 17), ciphertext primes q[0..nq),
+ * special primes p[0..np) (np may be 0 if no key switching is used), decomposition number
+ * dnum (alpha = ceil(nq/dnum) limbs per digit, needs np >= 1 for key switching).  Every
+ * modulus must be a prime = 1 mod 2N, 2^20 < m < 2^60, pairwise distinct.  Builds the root
+ * tables (psi = c^((m-1)/2N), c the smallest quadratic non-residue of m), conversion
+ * constants and a device workspace sized for level L.  hip_stream is a hipStream_t (NULL =
+ * the default stream) on which all work of this context is enqueued.  Synchronises once. */
+int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t nq,
+                      const uint64_t* h_p, uint32_t np, uint32_t dnum, void* hip_stream);
+int32_t he_ctx_destroy(he_ctx* ctx);
+/* Text of the last error on this context (ctx may be NULL: last creation error). */
+const char* he_last_error(const he_ctx* ctx);
+/* psi of modulus `mod_idx` (tests compare the root choice against their own). */
+int32_t he_ctx_psi(const he_ctx* ctx, uint32_t mod_idx, uint64_t* h_psi_out);
+int32_t he_counters(const he_ctx* ctx, he_counters_t* h_out);
+int32_t he_counters_reset(he_ctx* ctx);
+/* Block until everything enqueued on the context's stream has finished. */
+int32_t he_sync(he_ctx* ctx);
+
+/* Forward / inverse negacyclic NTT of n_limbs limbs in place (ring of Section 2.1).
+ * d_data: [n_limbs][N]; h_mod_idx[i] = modulus index of limb i.  he_ntt: coefficient form in,
+ * NTT form out; he_intt the inverse (including the factor N^-1).  Inputs must be canonical;
+ * outputs are canonical. */
+int32_t he_ntt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_t n_limbs);
+int32_t he_intt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_t n_limbs);
+
+/* Galois automorphism a(X) -> a(X^g) on every limb (the slot permutation inside CRot,
+ * Section 2.1): g odd, 0 < g < 2N; g = 5^r mod 2N rotates slots left by r, g = 2N-1
+ * conjugates.  ntt_form != 0: pure index permutation of NTT-form limbs; ntt_form == 0:
+ * signed index map on coefficient-form limbs.  d_out must not overlap d_in. */
+int32_t he_automorph(he_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, const uint32_t* h_mod_idx,
+                     uint32_t n_limbs, uint32_t galois_elt, int32_t ntt_form);
+
+/* Register the evaluation key that switches sigma_g(s) -> s (galois_elt = g) or s^2 -> s
+ * (galois_elt = 0).  d_evk: [dnum][2][nq+np][N] NTT form, component 0 = b, 1 = a, limb order
+ * q_0..q_L, p_0..p_{k-1}; digit j carries P*s' on the q-limbs j*alpha..(j+1)*alpha-1.  The
+ * caller keeps the buffer alive and unchanged while it is registered; registering again
+ * replaces the pointer. */
+int32_t he_evk_register(he_ctx* ctx, uint32_t galois_elt, const uint64_t* d_evk);
+
+/* Hybrid key switching of one polynomial (the inner step of CRot and of relinearisation;
+ * paper Appendix, evaluation keys and dnum): d_in [level+1][N] NTT form;
+ * (d_out0, d_out1), each [level+1][N], satisfy out0 + out1*s = in*s' + small error for the
+ * key registered under galois_elt_of_key.  Steps: ModUp of each digit (iNTT, fast basis
+ * conversion without overflow correction, NTT), inner product with the key over
+ * q_0..q_level,p_*, ModDown (conversion of the p-part without rounding term, times P^-1).
+ * No automorphism is applied. */
+int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t galois_elt_of_key,
+                     uint64_t* d_out0, uint64_t* d_out1);
+
+/* Rotations of one ciphertext by several slot amounts sharing a single ModUp of c1 (what
+ * Slide_f of Algorithm 1 needs: all f^2 rotations of one input).  d_ct [2][level+1][N];
+ * h_steps[i] = left-rotation amount (negative = right; reduced mod N/2; 0 = plain copy, no
+ * key needed); h_d_out[i] = device buffer [2][level+1][N] for rotation i (must not overlap
+ * d_ct or each other).  Per step with g = 5^step: acc = sum_j sigma_g(raised_j) * evk_g,j;
+ * (ks0, ks1) = ModDown(acc); out = (sigma_g(c0) + ks0, ks1). */
+int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const int32_t* h_steps,
+                          uint32_t n_steps, uint64_t* const* h_d_out);
+/* CRot(ct; step): identical bits to he_rotate_hoisted with n_steps = 1. */
+int32_t he_rotate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, int32_t step, uint64_t* d_out);
+/* Slot-wise complex conjugation (Galois element 2N-1, key registered under 2N-1). */
+int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out);
+
+/* MulPt + AddCt (MulFilter&Sum_f of Algorithm 1, one tap): acc.c0 (+)= ct.c0*pt,
+ * acc.c1 (+)= ct.c1*pt, slot-wise per limb.  d_acc, d_ct [2][level+1][N]; d_pt [level+1][N];
+ * init != 0 overwrites d_acc instead of accumulating.  d_acc may not overlap d_ct / d_pt. */
+int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const uint64_t* d_pt,
+                    uint32_t level, int32_t init);
+/* AddCt: d_out = d_a + d_b on [2][level+1][N]; d_out may alias d_a or d_b. */
+int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out);
+
+/* Rescale (Section 2.1): divide by q_level with exact rounding (half up) per coefficient and
+ * drop that limb: d_ct [2][level+1][N] -> d_out [2][level][N], 1 <= level <= L. */
+int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out);
+
+/* Channel-aligned convolution CAConv (Section 3.1; Algorithm 1 for Slide_f and
+ * MulFilter&Sum_f): Slide_f = hoisted rotations by (dy*W+dx)*R for the f^2 taps; for each
+ * output o: sum over taps of rotated input * weight plaintext, Rescale, then rotate-and-sum
+ * over C_a with amounts H*W*R*2^t, t < log2(C_a).  d_ct_in [2][level+1][N];
+ * h_d_ct_out[o] = device buffer [2][level][N].  Needs keys for every non-zero tap amount and
+ * every rotate-and-sum amount.  Grows the context workspace on first use (allocates). */
+int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64_t* d_ct_in, uint64_t* const* h_d_ct_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HE_MI355X_H */

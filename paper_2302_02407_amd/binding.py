@@ -1,0 +1,237 @@
+"""ctypes binding of libhe_mi355x.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA tensors of dtype uint64 (or int64 holding the same bits), contiguous,
+limb-major [poly][limb][N].  Every step of the path runs in the library's HIP kernels; there
+is no CPU fallback: if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
+
+HE_OK = 0
+_STATUS = {0: "HE_OK", -1: "HE_ERR_BADARG", -2: "HE_ERR_LEVEL", -3: "HE_ERR_NOKEY", -4: "HE_ERR_ALLOC", -5: "HE_ERR_HIP"}
+
+EXPORTS = [
+    "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync",
+    "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate",
+    "he_conjugate", "he_ptct_mac", "he_add", "he_rescale", "he_conv2d",
+]
+
+
+class HEError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("%s (%d): %s" % (_STATUS.get(code, "?"), code, msg))
+        self.code = code
+
+
+class Counters(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("keyswitch", "modup", "ntt_limbs", "intt_limbs", "mac", "rescale", "automorph")]
+
+
+class ConvPlan(C.Structure):
+    _fields_ = [("C_a", C.c_uint32), ("H", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32),
+                ("n_out", C.c_uint32), ("level", C.c_uint32), ("h_d_weights", C.POINTER(C.c_void_p))]
+
+
+_lib = None
+
+
+def load():
+    """Load the built library; raises if it is absent (build with __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libhe_mi355x.so is not built: run `python -m paper_2302_02407_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, u32, i32 = C.c_void_p, C.c_uint32, C.c_int32
+    u64p, u32p, i32p = C.POINTER(C.c_uint64), C.POINTER(C.c_uint32), C.POINTER(C.c_int32)
+    sig = {
+        "he_ctx_create": [C.POINTER(vp), u32, u64p, u32, u64p, u32, u32, vp],
+        "he_ctx_destroy": [vp],
+        "he_ctx_psi": [vp, u32, u64p],
+        "he_counters": [vp, C.POINTER(Counters)],
+        "he_counters_reset": [vp],
+        "he_sync": [vp],
+        "he_ntt": [vp, vp, u32p, u32],
+        "he_intt": [vp, vp, u32p, u32],
+        "he_automorph": [vp, vp, vp, u32p, u32, u32, i32],
+        "he_evk_register": [vp, u32, vp],
+        "he_keyswitch": [vp, vp, u32, u32, vp, vp],
+        "he_rotate_hoisted": [vp, vp, u32, i32p, u32, C.POINTER(vp)],
+        "he_rotate": [vp, vp, u32, i32, vp],
+        "he_conjugate": [vp, vp, u32, vp],
+        "he_ptct_mac": [vp, vp, vp, vp, u32, i32],
+        "he_add": [vp, vp, vp, u32, vp],
+        "he_rescale": [vp, vp, u32, vp],
+        "he_conv2d": [vp, C.POINTER(ConvPlan), vp, C.POINTER(vp)],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = i32
+    lib.he_last_error.argtypes = [vp]
+    lib.he_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _dev(t, what="tensor"):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a CUDA tensor" % what)
+    if t.dtype not in (torch.uint64, torch.int64):
+        raise TypeError("%s must be uint64/int64" % what)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % what)
+    return C.c_void_p(t.data_ptr())
+
+
+def _u32arr(xs):
+    xs = [int(x) for x in xs]
+    return (C.c_uint32 * max(1, len(xs)))(*xs), len(xs)
+
+
+class HEContext:
+    """One parameter set on the current device; all work goes to torch's current stream at creation."""
+
+    def __init__(self, logN, q, p, dnum, stream=None):
+        self._lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the HIP path has no CPU fallback")
+        self.logN, self.N = int(logN), 1 << int(logN)
+        self.q, self.p, self.dnum = [int(x) for x in q], [int(x) for x in p], int(dnum)
+        self.nq, self.np_ = len(self.q), len(self.p)
+        self.stream = torch.cuda.current_stream() if stream is None else stream
+        qa = (C.c_uint64 * self.nq)(*self.q)
+        pa = (C.c_uint64 * max(1, self.np_))(*(self.p or [0]))
+        h = C.c_void_p()
+        rc = self._lib.he_ctx_create(C.byref(h), self.logN, qa, self.nq, pa, self.np_, self.dnum,
+                                     C.c_void_p(self.stream.cuda_stream))
+        if rc != HE_OK:
+            raise HEError(rc, self._lib.he_last_error(None).decode())
+        self._h = h
+        self._keys = {}   # keeps registered key tensors alive
+
+    @classmethod
+    def from_params(cls, prm, stream=None):
+        return cls(prm.logN, prm.q, prm.p, prm.dnum, stream)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.he_ctx_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _ck(self, rc):
+        if rc != HE_OK:
+            raise HEError(rc, self._lib.he_last_error(self._h).decode())
+
+    # ---- parameters / bookkeeping
+    def he_ctx_psi(self, mod_idx):
+        v = C.c_uint64()
+        self._ck(self._lib.he_ctx_psi(self._h, mod_idx, C.byref(v)))
+        return v.value
+
+    def he_counters(self):
+        c = Counters()
+        self._ck(self._lib.he_counters(self._h, C.byref(c)))
+        return {n: getattr(c, n) for n, _ in Counters._fields_}
+
+    def he_counters_reset(self):
+        self._ck(self._lib.he_counters_reset(self._h))
+
+    def he_sync(self):
+        self._ck(self._lib.he_sync(self._h))
+
+    def galois_elt(self, step):
+        return pow(5, step % (self.N // 2), 2 * self.N)
+
+    # ---- transforms
+    def he_ntt(self, data, mod_idx):
+        arr, n = _u32arr(mod_idx)
+        assert data.numel() == n * self.N
+        self._ck(self._lib.he_ntt(self._h, _dev(data), arr, n))
+        return data
+
+    def he_intt(self, data, mod_idx):
+        arr, n = _u32arr(mod_idx)
+        assert data.numel() == n * self.N
+        self._ck(self._lib.he_intt(self._h, _dev(data), arr, n))
+        return data
+
+    def he_automorph(self, src, dst, mod_idx, galois_elt, ntt_form=True):
+        arr, n = _u32arr(mod_idx)
+        assert src.numel() == n * self.N and dst.numel() == n * self.N
+        self._ck(self._lib.he_automorph(self._h, _dev(src), _dev(dst), arr, n, galois_elt, 1 if ntt_form else 0))
+        return dst
+
+    # ---- key switching
+    def he_evk_register(self, galois_elt, evk):
+        assert evk.numel() == self.dnum * 2 * (self.nq + self.np_) * self.N
+        self._ck(self._lib.he_evk_register(self._h, galois_elt, _dev(evk)))
+        self._keys[galois_elt] = evk
+
+    def he_keyswitch(self, poly, level, galois_elt_of_key, out0, out1):
+        assert poly.numel() == (level + 1) * self.N == out0.numel() == out1.numel()
+        self._ck(self._lib.he_keyswitch(self._h, _dev(poly), level, galois_elt_of_key, _dev(out0), _dev(out1)))
+        return out0, out1
+
+    def he_rotate_hoisted(self, ct, level, steps, outs):
+        steps = [int(s) for s in steps]
+        assert len(outs) == len(steps) and ct.numel() == 2 * (level + 1) * self.N
+        for o in outs:
+            assert o.numel() == ct.numel()
+        sa = (C.c_int32 * max(1, len(steps)))(*steps)
+        pa = (C.c_void_p * max(1, len(outs)))(*[_dev(o).value for o in outs])
+        self._ck(self._lib.he_rotate_hoisted(self._h, _dev(ct), level, sa, len(steps), pa))
+        return outs
+
+    def he_rotate(self, ct, level, step, out):
+        assert ct.numel() == 2 * (level + 1) * self.N == out.numel()
+        self._ck(self._lib.he_rotate(self._h, _dev(ct), level, int(step), _dev(out)))
+        return out
+
+    def he_conjugate(self, ct, level, out):
+        assert ct.numel() == 2 * (level + 1) * self.N == out.numel()
+        self._ck(self._lib.he_conjugate(self._h, _dev(ct), level, _dev(out)))
+        return out
+
+    # ---- MulPt accumulate / add / rescale
+    def he_ptct_mac(self, acc, ct, pt, level, init):
+        assert acc.numel() == ct.numel() == 2 * (level + 1) * self.N and pt.numel() == (level + 1) * self.N
+        self._ck(self._lib.he_ptct_mac(self._h, _dev(acc), _dev(ct), _dev(pt), level, 1 if init else 0))
+        return acc
+
+    def he_add(self, a, b, level, out):
+        assert a.numel() == b.numel() == out.numel() == 2 * (level + 1) * self.N
+        self._ck(self._lib.he_add(self._h, _dev(a), _dev(b), level, _dev(out)))
+        return out
+
+    def he_rescale(self, ct, level, out):
+        assert ct.numel() == 2 * (level + 1) * self.N and out.numel() == 2 * level * self.N
+        self._ck(self._lib.he_rescale(self._h, _dev(ct), level, _dev(out)))
+        return out
+
+    # ---- convolution
+    def he_conv2d(self, C_a, H, W, R, f, level, weights, ct_in, outs):
+        """weights: list of n_out*f*f device tensors [level+1][N]; outs: n_out tensors [2][level][N]."""
+        n_out = len(outs)
+        assert len(weights) == n_out * f * f and ct_in.numel() == 2 * (level + 1) * self.N
+        for w in weights:
+            assert w.numel() == (level + 1) * self.N
+        for o in outs:
+            assert o.numel() == 2 * level * self.N
+        wa = (C.c_void_p * len(weights))(*[_dev(w).value for w in weights])
+        oa = (C.c_void_p * n_out)(*[_dev(o).value for o in outs])
+        plan = ConvPlan(C_a, H, W, R, f, n_out, level, C.cast(wa, C.POINTER(C.c_void_p)))
+        self._ck(self._lib.he_conv2d(self._h, C.byref(plan), _dev(ct_in), oa))
+        return outs

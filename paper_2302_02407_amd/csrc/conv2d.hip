@@ -1,0 +1,135 @@
+// Channel-aligned convolution CAConv (paper Section 3.1) assembled from Slide_f and
+// MulFilter&Sum_f (Algorithm 1), Rescale (Section 2.1) and rotate-and-sum over C_a
+// (Section 2.2), all enqueued on the context's stream with no host synchronisation.
+#include "modarith.cuh"
+
+#define CV_THREADS 256
+#define CV_MAX_TAPS 49
+
+struct MacTaps {
+    const u64* ct[CV_MAX_TAPS]; // rotated inputs [2][L1][N]
+    const u64* pt[CV_MAX_TAPS]; // filter plaintexts [L1][N]
+    uint32_t n;
+};
+
+// MulFilter&Sum_f for one output ciphertext: acc_c[limb] = sum_t ct_t,c[limb] * pt_t[limb].
+// Products are summed in 128 bits and reduced once per 8 taps.  grid: (N/256, L1).
+__global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTaps taps, u64* __restrict__ acc, const ModConst* mc,
+                                                              uint32_t logN, uint32_t L1) {
+    const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
+    const uint32_t limb = blockIdx.y;
+    const ModConst m = mc[limb];
+    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n;
+    u128 a0 = 0, a1 = 0;
+    for (uint32_t t = 0; t < taps.n; t++) {
+        if (t && (t & 7) == 0) {
+            a0 = barrett128(a0, m.q, m.mu, m.bits);
+            a1 = barrett128(a1, m.q, m.mu, m.bits);
+        }
+        u64 p = taps.pt[t][o0];
+        a0 += (u128)taps.ct[t][o0] * p;
+        a1 += (u128)taps.ct[t][o1] * p;
+    }
+    acc[o0] = barrett128(a0, m.q, m.mu, m.bits);
+    acc[o1] = barrett128(a1, m.q, m.mu, m.bits);
+}
+
+__global__ __launch_bounds__(CV_THREADS) void add_inplace_kernel(u64* __restrict__ a, const u64* __restrict__ b,
+                                                                 const ModConst* mc, uint32_t logN, uint32_t n_limbs) {
+    uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
+    u64 q = mc[blockIdx.y % n_limbs].q;
+    size_t o = ((size_t)blockIdx.y << logN) + n;
+    a[o] = addmod(a[o], b[o], q);
+}
+
+extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64_t* d_ct_in, uint64_t* const* h_d_ct_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!plan || !d_ct_in || !h_d_ct_out || !plan->h_d_weights) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: null argument");
+    const uint32_t N = ctx->N, slots = N / 2, level = plan->level, f = plan->f, taps = f * f;
+    if (ctx->np == 0) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: context has no special primes");
+    if (level == 0 || level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_conv2d: level %u outside 1..%u", level, ctx->nq - 1);
+    if ((f & 1u) == 0 || taps > CV_MAX_TAPS) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: filter width %u must be odd and at most 7", f);
+    if (plan->C_a == 0 || (plan->C_a & (plan->C_a - 1))) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: C_a must be a power of two");
+    if ((u64)plan->C_a * plan->H * plan->W * plan->R != slots) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: C_a*H*W*R must equal N/2");
+    if (plan->n_out == 0) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: n_out is zero");
+    const uint32_t L1 = level + 1;
+    // rotation amounts: Slide_f taps (dy outer, dx inner) and rotate-and-sum over C_a
+    std::vector<uint32_t> tap_g(taps), ras_g;
+    std::vector<const u64*> tap_key(taps, nullptr), ras_key;
+    const int32_t half = (int32_t)(f - 1) / 2;
+    for (uint32_t t = 0; t < taps; t++) {
+        int32_t dy = (int32_t)(t / f) - half, dx = (int32_t)(t % f) - half;
+        int64_t step = ((int64_t)dy * plan->W + dx) * plan->R;
+        step = ((step % (int64_t)slots) + slots) % slots;
+        tap_g[t] = h_galois_of_step(ctx, (int32_t)step);
+        if (tap_g[t] != 1) {
+            auto it = ctx->evk.find(tap_g[t]);
+            if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_conv2d: no key for tap rotation %lld", (long long)step);
+            tap_key[t] = it->second;
+        }
+    }
+    for (uint32_t s = 1; s < plan->C_a; s <<= 1) {
+        uint32_t step = plan->H * plan->W * plan->R * s;
+        uint32_t g = h_galois_of_step(ctx, (int32_t)step);
+        auto it = ctx->evk.find(g);
+        if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_conv2d: no key for rotate-and-sum amount %u", step);
+        ras_g.push_back(g);
+        ras_key.push_back(it->second);
+    }
+    for (uint32_t i = 0; i < plan->n_out * taps; i++)
+        if (!plan->h_d_weights[i]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: weight plaintext %u is null", i);
+    for (uint32_t o = 0; o < plan->n_out; o++)
+        if (!h_d_ct_out[o]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: output %u is null", o);
+    // workspace: [key-switch region at `level`][rescale scratch][taps-1 rotated inputs][acc][rot]
+    const size_t ct_e = (size_t)2 * L1 * N;
+    const size_t ks_e = ks_raised_elems(ctx, level) + ks_scratch_elems(ctx, level);
+    const size_t rs_e = rescale_ws_elems(ctx, level);
+    const size_t total = ks_e + rs_e + (size_t)(taps + 1) * ct_e;
+    int32_t rc = he_ensure_ws(ctx, total * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    u64* raised = ctx->d_ws;
+    u64* scratch = raised + ks_raised_elems(ctx, level);
+    u64* rs_ws = ctx->d_ws + ks_e;
+    u64* slid = rs_ws + rs_e;
+    u64* acc = slid + (size_t)(taps - 1) * ct_e;
+    u64* rot = acc + ct_e;
+    const u64* ct_in = (const u64*)d_ct_in;
+
+    // Slide_f: one ModUp of c1 shared by all taps
+    rc = modup_impl(ctx, ct_in + (size_t)L1 * N, level, raised, scratch);
+    if (rc != HE_OK) return rc;
+    MacTaps mt;
+    mt.n = taps;
+    uint32_t nb = 0;
+    for (uint32_t t = 0; t < taps; t++) {
+        if (tap_g[t] == 1) { mt.ct[t] = ct_in; continue; }
+        u64* out = slid + (size_t)nb++ * ct_e;
+        rc = ks_inner_moddown(ctx, raised, level, tap_g[t], tap_key[t], ct_in, out, out + (size_t)L1 * N, scratch);
+        if (rc != HE_OK) return rc;
+        mt.ct[t] = out;
+    }
+    const uint32_t lo = level - 1; // level after the rescale
+    u64* raised_lo = ctx->d_ws;
+    u64* scratch_lo = raised_lo + ks_raised_elems(ctx, lo);
+    for (uint32_t o = 0; o < plan->n_out; o++) {
+        for (uint32_t t = 0; t < taps; t++) mt.pt[t] = (const u64*)plan->h_d_weights[(size_t)o * taps + t];
+        dim3 grid(N / CV_THREADS, L1), block(CV_THREADS);
+        hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc, ctx->d_mc, ctx->logN, L1);
+        HE_HIP(ctx, hipGetLastError());
+        ctx->cnt.mac += taps;
+        u64* out = (u64*)h_d_ct_out[o];
+        rc = rescale_impl(ctx, acc, level, out, rs_ws);
+        if (rc != HE_OK) return rc;
+        // rotate-and-sum over the outermost channel dimension
+        for (size_t s = 0; s < ras_g.size(); s++) {
+            rc = modup_impl(ctx, out + (size_t)level * N, lo, raised_lo, scratch_lo);
+            if (rc != HE_OK) return rc;
+            rc = ks_inner_moddown(ctx, raised_lo, lo, ras_g[s], ras_key[s], out, rot, rot + (size_t)level * N, scratch_lo);
+            if (rc != HE_OK) return rc;
+            dim3 g2(N / CV_THREADS, 2 * level);
+            hipLaunchKernelGGL(add_inplace_kernel, g2, block, 0, ctx->stream, out, rot, ctx->d_mc, ctx->logN, level);
+            HE_HIP(ctx, hipGetLastError());
+        }
+    }
+    return HE_OK;
+}

@@ -1,0 +1,236 @@
+// Context: parameter validation, root/twiddle tables, device constants, workspace, errors.
+#include <stdarg.h>
+#include <new>
+#include <stdio.h>
+#include <string.h>
+
+#include "he_internal.h"
+
+static std::string g_create_err;
+
+int32_t he_fail(he_ctx* ctx, int32_t code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf; else g_create_err = buf;
+    return code;
+}
+
+u64 h_mulmod(u64 a, u64 b, u64 m) { return (u64)((u128)a * b % m); }
+u64 h_powmod(u64 a, u64 e, u64 m) {
+    u64 r = 1 % m;
+    a %= m;
+    for (; e; e >>= 1) {
+        if (e & 1) r = h_mulmod(r, a, m);
+        a = h_mulmod(a, a, m);
+    }
+    return r;
+}
+u64 h_invmod(u64 a, u64 m) { return h_powmod(a % m, m - 2, m); }
+u64 h_shoup(u64 w, u64 m) { return (u64)(((u128)w << 64) / m); }
+
+static bool h_is_prime(u64 n) {
+    if (n < 2) return false;
+    static const u64 bases[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    for (u64 b : bases) {
+        if (n % b == 0) return n == b;
+    }
+    u64 d = n - 1;
+    int r = 0;
+    while ((d & 1) == 0) { d >>= 1; r++; }
+    for (u64 a : bases) {
+        u64 x = h_powmod(a, d, n);
+        if (x == 1 || x == n - 1) continue;
+        bool comp = true;
+        for (int i = 1; i < r; i++) {
+            x = h_mulmod(x, x, n);
+            if (x == n - 1) { comp = false; break; }
+        }
+        if (comp) return false;
+    }
+    return true;
+}
+
+static uint32_t bitrev(uint32_t x, uint32_t bits) {
+    uint32_t r = 0;
+    for (uint32_t i = 0; i < bits; i++) r |= ((x >> i) & 1u) << (bits - 1 - i);
+    return r;
+}
+
+uint32_t h_galois_of_step(const he_ctx* ctx, int32_t step) {
+    int64_t half = ctx->N / 2;
+    int64_t s = ((int64_t)step % half + half) % half;
+    return (uint32_t)h_powmod(5, (u64)s, 2 * (u64)ctx->N);
+}
+
+int32_t he_ensure_ws(he_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return HE_OK;
+    if (ctx->d_ws) {
+        HE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        HE_HIP(ctx, hipFree(ctx->d_ws));
+        ctx->d_ws = nullptr;
+        ctx->ws_bytes = 0;
+    }
+    if (hipMalloc(&ctx->d_ws, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return he_fail(ctx, HE_ERR_ALLOC, "workspace allocation of %zu bytes failed", bytes);
+    }
+    ctx->ws_bytes = bytes;
+    return HE_OK;
+}
+
+extern "C" {
+
+const char* he_last_error(const he_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t nq, const uint64_t* h_p,
+                      uint32_t np, uint32_t dnum, void* hip_stream) {
+    if (!out) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: out is null");
+    *out = nullptr;
+    if (logN < 8 || logN > 17) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: logN %u outside 8..17", logN);
+    if (!h_q || nq == 0 || (np && !h_p)) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: missing prime list");
+    if (nq + np > HE_MAX_MODULI) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: more than %d moduli", HE_MAX_MODULI);
+    if (dnum == 0 || dnum > nq) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: dnum %u outside 1..nq", dnum);
+    uint32_t N = 1u << logN, M = nq + np;
+    for (uint32_t i = 0; i < M; i++) {
+        u64 m = i < nq ? h_q[i] : h_p[i - nq];
+        if (m <= (1ull << 20) || m >= (1ull << 60)) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: modulus %u out of range (2^20, 2^60)", i);
+        if (m % (2ull * N) != 1) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: modulus %u is not 1 mod 2N", i);
+        if (!h_is_prime(m)) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: modulus %u is not prime", i);
+        for (uint32_t k = 0; k < i; k++) {
+            u64 mk = k < nq ? h_q[k] : h_p[k - nq];
+            if (mk == m) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: modulus %u repeats modulus %u", i, k);
+        }
+    }
+    he_ctx* c = new (std::nothrow) he_ctx();
+    if (!c) return he_fail(nullptr, HE_ERR_ALLOC, "he_ctx_create: host allocation failed");
+    c->logN = logN; c->N = N; c->nq = nq; c->np = np; c->dnum = dnum; c->M = M;
+    c->alpha = (nq + dnum - 1) / dnum;
+    c->stream = (hipStream_t)hip_stream;
+    c->d_mc = nullptr; c->d_tw = c->d_tw_sh = c->d_itw = c->d_itw_sh = nullptr;
+    c->d_ws = nullptr; c->ws_bytes = 0;
+    c->d_up_hat = c->d_dn_hat = c->d_pinv = c->d_pinv_sh = c->d_qlinv = c->d_qlinv_sh = nullptr;
+    memset(&c->cnt, 0, sizeof(c->cnt));
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        delete c;
+        return he_fail(nullptr, HE_ERR_HIP, "he_ctx_create: no HIP device");
+    }
+    // tables on the host
+    std::vector<u64> tw((size_t)M * N), tw_sh((size_t)M * N), itw((size_t)M * N), itw_sh((size_t)M * N);
+    for (uint32_t i = 0; i < M; i++) {
+        u64 m = i < nq ? h_q[i] : h_p[i - nq];
+        c->mod[i] = m;
+        u64 g = 2;
+        while (h_powmod(g, (m - 1) / 2, m) != m - 1) g++;       // smallest quadratic non-residue
+        u64 psi = h_powmod(g, (m - 1) / (2ull * N), m);
+        c->psi[i] = psi;
+        u64 ipsi = h_invmod(psi, m);
+        u64 pw = 1, ipw = 1;
+        u64* t = &tw[(size_t)i * N]; u64* ts = &tw_sh[(size_t)i * N];
+        u64* it = &itw[(size_t)i * N]; u64* its = &itw_sh[(size_t)i * N];
+        for (uint32_t e = 0; e < N; e++) {                      // psi^e stored at bitrev(e)
+            uint32_t pos = bitrev(e, logN);
+            t[pos] = pw; ts[pos] = h_shoup(pw, m);
+            it[pos] = ipw; its[pos] = h_shoup(ipw, m);
+            pw = h_mulmod(pw, psi, m);
+            ipw = h_mulmod(ipw, ipsi, m);
+        }
+        ModConst& mc = c->h_mc[i];
+        mc.q = m; mc.q2 = 2 * m;
+        mc.bits = 64 - __builtin_clzll(m);
+        mc.mu = (u64)(((u128)1 << (mc.bits + 63)) / m);
+        mc.ninv = h_invmod(N % m, m);
+        mc.ninv_sh = h_shoup(mc.ninv, m);
+        mc.pad = 0;
+    }
+    size_t tb = (size_t)M * N * sizeof(u64);
+    hipError_t e = hipSuccess;
+    if (e == hipSuccess) e = hipMalloc(&c->d_mc, sizeof(ModConst) * M);
+    if (e == hipSuccess) e = hipMalloc(&c->d_tw, tb);
+    if (e == hipSuccess) e = hipMalloc(&c->d_tw_sh, tb);
+    if (e == hipSuccess) e = hipMalloc(&c->d_itw, tb);
+    if (e == hipSuccess) e = hipMalloc(&c->d_itw_sh, tb);
+    if (e == hipSuccess) e = hipMemcpy(c->d_mc, c->h_mc, sizeof(ModConst) * M, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_tw, tw.data(), tb, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_tw_sh, tw_sh.data(), tb, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_itw, itw.data(), tb, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_itw_sh, itw_sh.data(), tb, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        he_fail(nullptr, e == hipErrorOutOfMemory ? HE_ERR_ALLOC : HE_ERR_HIP, "he_ctx_create: %s", hipGetErrorString(e));
+        he_ctx_destroy(c);
+        return e == hipErrorOutOfMemory ? HE_ERR_ALLOC : HE_ERR_HIP;
+    }
+    {
+        int32_t rc = ks_init_tables(c);
+        if (rc != HE_OK) {
+            g_create_err = c->err;
+            he_ctx_destroy(c);
+            return rc;
+        }
+    }
+    // workspace for one key switch at the top level (raised digits + accumulators + temporaries)
+    if (np > 0) {
+        size_t elems = ks_raised_elems(c, nq - 1) + ks_scratch_elems(c, nq - 1);
+        int32_t rc = he_ensure_ws(c, elems * sizeof(u64));
+        if (rc != HE_OK) {
+            g_create_err = c->err;
+            he_ctx_destroy(c);
+            return rc;
+        }
+    }
+    *out = c;
+    return HE_OK;
+}
+
+int32_t he_ctx_destroy(he_ctx* c) {
+    if (!c) return HE_OK;
+    (void)hipStreamSynchronize(c->stream);
+    if (c->d_mc) (void)hipFree(c->d_mc);
+    if (c->d_tw) (void)hipFree(c->d_tw);
+    if (c->d_tw_sh) (void)hipFree(c->d_tw_sh);
+    if (c->d_itw) (void)hipFree(c->d_itw);
+    if (c->d_itw_sh) (void)hipFree(c->d_itw_sh);
+    if (c->d_ws) (void)hipFree(c->d_ws);
+    ks_free_tables(c);
+    delete c;
+    return HE_OK;
+}
+
+int32_t he_ctx_psi(const he_ctx* ctx, uint32_t mod_idx, uint64_t* h_psi_out) {
+    if (!ctx || !h_psi_out || mod_idx >= ctx->M) return HE_ERR_BADARG;
+    *h_psi_out = ctx->psi[mod_idx];
+    return HE_OK;
+}
+
+int32_t he_counters(const he_ctx* ctx, he_counters_t* h_out) {
+    if (!ctx || !h_out) return HE_ERR_BADARG;
+    *h_out = ctx->cnt;
+    return HE_OK;
+}
+
+int32_t he_counters_reset(he_ctx* ctx) {
+    if (!ctx) return HE_ERR_BADARG;
+    memset(&ctx->cnt, 0, sizeof(ctx->cnt));
+    return HE_OK;
+}
+
+int32_t he_sync(he_ctx* ctx) {
+    if (!ctx) return HE_ERR_BADARG;
+    HE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return HE_OK;
+}
+
+int32_t he_evk_register(he_ctx* ctx, uint32_t galois_elt, const uint64_t* d_evk) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_evk) return he_fail(ctx, HE_ERR_BADARG, "he_evk_register: null key");
+    if (galois_elt != 0 && ((galois_elt & 1u) == 0 || galois_elt >= 2 * ctx->N))
+        return he_fail(ctx, HE_ERR_BADARG, "he_evk_register: Galois element %u is not odd and below 2N", galois_elt);
+    if (ctx->np == 0) return he_fail(ctx, HE_ERR_BADARG, "he_evk_register: context has no special primes");
+    ctx->evk[galois_elt] = (const u64*)d_evk;
+    return HE_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,138 @@
+// Coefficient-wise kernels: Galois permutation, MulPt-accumulate, AddCt, and their entry points.
+#include "modarith.cuh"
+
+#define EW_THREADS 256
+
+// Source position of output position j under sigma_g on NTT-form limbs: position j holds the
+// evaluation at psi^(2k+1), k = bitrev(j); sigma_g(a) there equals a at exponent
+// (2k+1)*g mod 2N, i.e. natural index k' = g*k + (g-1)/2 mod N, stored at bitrev(k').
+// Aligned blocks of positions map to aligned blocks, so a wave's 64 loads stay inside one
+// 512-byte span.
+__device__ __forceinline__ uint32_t galois_src(uint32_t j, uint32_t g, uint32_t logN) {
+    uint32_t k = __brev(j) >> (32 - logN);
+    uint32_t kp = (g * k + ((g - 1) >> 1)) & ((1u << logN) - 1);
+    return __brev(kp) >> (32 - logN);
+}
+
+__global__ __launch_bounds__(EW_THREADS) void automorph_ntt_kernel(const u64* __restrict__ in, u64* __restrict__ out,
+                                                                   uint32_t logN, uint32_t g) {
+    uint32_t j = blockIdx.x * EW_THREADS + threadIdx.x;
+    size_t limb = blockIdx.y;
+    out[(limb << logN) + j] = in[(limb << logN) + galois_src(j, g, logN)];
+}
+
+// Coefficient form: out[t] = +-in[i] with i*g = t (mod 2N) up to the sign from X^N = -1.
+__global__ __launch_bounds__(EW_THREADS) void automorph_coef_kernel(const u64* __restrict__ in, u64* __restrict__ out,
+                                                                    const ModConst* mc, LimbList ll, uint32_t logN,
+                                                                    uint32_t ginv) {
+    uint32_t t = blockIdx.x * EW_THREADS + threadIdx.x;
+    size_t limb = blockIdx.y;
+    u64 q = mc[ll.mod[limb]].q;
+    uint32_t N = 1u << logN;
+    uint32_t u = (uint32_t)(((u64)t * ginv) & (2ull * N - 1));
+    u64 v = in[(limb << logN) + (u & (N - 1))];
+    if (u >= N) v = v ? q - v : 0;
+    out[(limb << logN) + t] = v;
+}
+
+// acc (+)= ct * pt on both components; limb index = blockIdx.y in [0, level+1).
+__global__ __launch_bounds__(EW_THREADS) void ptct_mac_kernel(u64* __restrict__ acc, const u64* __restrict__ ct,
+                                                              const u64* __restrict__ pt, const ModConst* mc,
+                                                              uint32_t logN, uint32_t n_limbs, int init) {
+    uint32_t n = blockIdx.x * EW_THREADS + threadIdx.x;
+    uint32_t limb = blockIdx.y;
+    const ModConst m = mc[limb];
+    size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + n_limbs) << logN) + n;
+    u64 p = pt[o0];
+    u64 r0 = mulmod(ct[o0], p, m), r1 = mulmod(ct[o1], p, m);
+    if (!init) {
+        r0 = addmod(r0, acc[o0], m.q);
+        r1 = addmod(r1, acc[o1], m.q);
+    }
+    acc[o0] = r0;
+    acc[o1] = r1;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void add_kernel(const u64* a, const u64* b, u64* out, const ModConst* mc,
+                                                         uint32_t logN, uint32_t n_limbs) {
+    uint32_t n = blockIdx.x * EW_THREADS + threadIdx.x;
+    uint32_t limb = blockIdx.y % n_limbs;
+    u64 q = mc[limb].q;
+    size_t o = ((size_t)blockIdx.y << logN) + n;
+    out[o] = addmod(a[o], b[o], q);
+}
+
+int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g) {
+    if (n_limbs == 0) return HE_OK;
+    dim3 grid(ctx->N / EW_THREADS, n_limbs), block(EW_THREADS);
+    hipLaunchKernelGGL(automorph_ntt_kernel, grid, block, 0, ctx->stream, in, out, ctx->logN, g);
+    HE_HIP(ctx, hipGetLastError());
+    ctx->cnt.automorph += n_limbs;
+    return HE_OK;
+}
+
+int32_t launch_automorph_coef(he_ctx* ctx, const u64* in, u64* out, const uint32_t* mod_idx, uint32_t n, uint32_t g) {
+    if (n == 0) return HE_OK;
+    LimbList ll;
+    for (uint32_t i = 0; i < n; i++) ll.mod[i] = (uint8_t)mod_idx[i];
+    // inverse of g modulo 2N (g odd): g^(N-1) since the unit group of Z_2N has exponent N/2 | N
+    uint32_t twoN = 2 * ctx->N;
+    u64 ginv = 1, b = g;
+    for (uint32_t e = ctx->N - 1; e; e >>= 1) {
+        if (e & 1) ginv = ginv * b % twoN;
+        b = b * b % twoN;
+    }
+    dim3 grid(ctx->N / EW_THREADS, n), block(EW_THREADS);
+    hipLaunchKernelGGL(automorph_coef_kernel, grid, block, 0, ctx->stream, in, out, ctx->d_mc, ll, ctx->logN, (uint32_t)ginv);
+    HE_HIP(ctx, hipGetLastError());
+    ctx->cnt.automorph += n;
+    return HE_OK;
+}
+
+extern "C" {
+
+int32_t he_automorph(he_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, const uint32_t* h_mod_idx,
+                     uint32_t n_limbs, uint32_t galois_elt, int32_t ntt_form) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_in || !d_out || !h_mod_idx) return he_fail(ctx, HE_ERR_BADARG, "he_automorph: null argument");
+    if ((galois_elt & 1u) == 0 || galois_elt >= 2 * ctx->N) return he_fail(ctx, HE_ERR_BADARG, "he_automorph: Galois element %u is not odd and below 2N", galois_elt);
+    size_t bytes = (size_t)n_limbs * ctx->N * sizeof(u64);
+    const char *a = (const char*)d_in, *b = (const char*)d_out;
+    if (a < b + bytes && b < a + bytes) return he_fail(ctx, HE_ERR_BADARG, "he_automorph: input and output overlap");
+    for (uint32_t i = 0; i < n_limbs; i++)
+        if (h_mod_idx[i] >= ctx->M) return he_fail(ctx, HE_ERR_BADARG, "he_automorph: modulus index out of range");
+    for (uint32_t o = 0; o < n_limbs; o += HE_MAX_LAUNCH_LIMBS) {
+        uint32_t n = n_limbs - o < HE_MAX_LAUNCH_LIMBS ? n_limbs - o : HE_MAX_LAUNCH_LIMBS;
+        const u64* in = (const u64*)d_in + (size_t)o * ctx->N;
+        u64* out = (u64*)d_out + (size_t)o * ctx->N;
+        int32_t rc = ntt_form ? launch_automorph_ntt(ctx, in, out, n, galois_elt)
+                              : launch_automorph_coef(ctx, in, out, h_mod_idx + o, n, galois_elt);
+        if (rc != HE_OK) return rc;
+    }
+    return HE_OK;
+}
+
+int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const uint64_t* d_pt, uint32_t level, int32_t init) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_acc || !d_ct || !d_pt) return he_fail(ctx, HE_ERR_BADARG, "he_ptct_mac: null argument");
+    if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_ptct_mac: level %u above L=%u", level, ctx->nq - 1);
+    dim3 grid(ctx->N / EW_THREADS, level + 1), block(EW_THREADS);
+    hipLaunchKernelGGL(ptct_mac_kernel, grid, block, 0, ctx->stream, (u64*)d_acc, (const u64*)d_ct, (const u64*)d_pt,
+                       ctx->d_mc, ctx->logN, level + 1, init);
+    HE_HIP(ctx, hipGetLastError());
+    ctx->cnt.mac += 1;
+    return HE_OK;
+}
+
+int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_a || !d_b || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_add: null argument");
+    if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_add: level %u above L=%u", level, ctx->nq - 1);
+    dim3 grid(ctx->N / EW_THREADS, 2 * (level + 1)), block(EW_THREADS);
+    hipLaunchKernelGGL(add_kernel, grid, block, 0, ctx->stream, (const u64*)d_a, (const u64*)d_b, (u64*)d_out, ctx->d_mc,
+                       ctx->logN, level + 1);
+    HE_HIP(ctx, hipGetLastError());
+    return HE_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,104 @@
+// Internal declarations shared by the translation units of the library (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/he_mi355x.h"
+
+typedef unsigned long long u64;
+typedef unsigned __int128 u128;
+
+#define HE_MAX_MODULI 64        // nq + np
+#define HE_MAX_LAUNCH_LIMBS 512 // limbs described by one kernel-argument list
+
+// Per-modulus constants, resident on the device (array indexed by modulus index).
+struct ModConst {
+    u64 q;          // the prime
+    u64 q2;         // 2q
+    u64 mu;         // floor(2^(bits+63) / q): Barrett constant for inputs < 2^(bits+63)
+    u64 ninv;       // N^-1 mod q
+    u64 ninv_sh;    // Shoup companion floor(ninv * 2^64 / q)
+    uint32_t bits;  // bit length of q
+    uint32_t pad;
+};
+
+// Modulus index of each limb of a launch, passed by value in the kernel arguments.
+struct LimbList {
+    uint8_t mod[HE_MAX_LAUNCH_LIMBS];
+};
+
+// Optional per-limb output scaling of an inverse transform (replaces the plain N^-1).
+struct ScaleList {
+    u64 s[HE_MAX_MODULI];
+    u64 s_sh[HE_MAX_MODULI];
+};
+
+struct he_ctx {
+    uint32_t logN, N, nq, np, dnum, alpha, M; // M = nq + np
+    hipStream_t stream;
+    int device;
+    u64 mod[HE_MAX_MODULI];
+    u64 psi[HE_MAX_MODULI];
+    ModConst h_mc[HE_MAX_MODULI];
+    // device tables
+    ModConst* d_mc;    // [M]
+    u64* d_tw;         // [M][N]  psi^bitrev(i)
+    u64* d_tw_sh;      // [M][N]  Shoup companions
+    u64* d_itw;        // [M][N]  psi^-bitrev(i)
+    u64* d_itw_sh;     // [M][N]
+    // basis-conversion tables (keyswitch.hip); present when np > 0
+    u64* d_up_hat;     // [dnum][alpha][alpha][M]: (Q_j/q_i) mod m for digit j holding sz limbs, [j][sz-1][i][m]
+    std::vector<u64> h_up_invhat; // [dnum][alpha][alpha]: ((Q_j/q_i)^-1 mod q_i), [j][sz-1][i]
+    u64* d_dn_hat;     // [np][M]: (P/p_t) mod m  (only m < nq used)
+    std::vector<u64> h_dn_invhat; // [np]: (P/p_t)^-1 mod p_t
+    u64* d_pinv;       // [nq] P^-1 mod q_r
+    u64* d_pinv_sh;    // [nq] Shoup companions
+    // rescale tables: q_l^-1 mod q_r for r < l, [nq][nq]
+    u64* d_qlinv;
+    u64* d_qlinv_sh;
+    // workspace (grown on demand)
+    u64* d_ws;
+    size_t ws_bytes;
+    std::map<uint32_t, const u64*> evk; // Galois element -> device key
+    he_counters_t cnt;
+    std::string err;
+};
+
+// ---- host helpers (ctx.hip)
+int32_t he_fail(he_ctx* ctx, int32_t code, const char* fmt, ...);
+int32_t he_ensure_ws(he_ctx* ctx, size_t bytes);
+u64 h_mulmod(u64 a, u64 b, u64 m);
+u64 h_powmod(u64 a, u64 e, u64 m);
+u64 h_invmod(u64 a, u64 m);
+u64 h_shoup(u64 w, u64 m);
+uint32_t h_galois_of_step(const he_ctx* ctx, int32_t step);
+
+#define HE_HIP(ctx, call)                                                                            \
+    do {                                                                                             \
+        hipError_t e__ = (call);                                                                     \
+        if (e__ != hipSuccess) return he_fail(ctx, HE_ERR_HIP, "%s: %s", #call, hipGetErrorString(e__)); \
+    } while (0)
+
+// ---- internal device-work launchers (all enqueue on ctx->stream, none synchronises)
+// Transforms of n limbs (n <= HE_MAX_LAUNCH_LIMBS) whose modulus indices are mod_idx[0..n).
+// scale == nullptr: inverse multiplies by N^-1; else limb i is multiplied by scale->s[i]
+// (which must already include N^-1).
+int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n);
+int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale);
+int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g);
+int32_t launch_automorph_coef(he_ctx* ctx, const u64* in, u64* out, const uint32_t* mod_idx, uint32_t n, uint32_t g);
+
+// key switching internals (keyswitch.hip)
+int32_t ks_init_tables(he_ctx* ctx);
+void ks_free_tables(he_ctx* ctx);
+int32_t ks_modup(he_ctx* ctx, const u64* d_poly, uint32_t level, u64* d_raised);
+int32_t ks_inner_moddown(he_ctx* ctx, const u64* d_raised, uint32_t level, uint32_t g_perm, const u64* d_evk,
+                         const u64* d_c0, u64* d_out0, u64* d_out1, u64* d_scratch);
+int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, u64* d_tmp);
+size_t rescale_ws_elems(const he_ctx* c, uint32_t level);
+int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u64* ws);
+size_t ks_raised_elems(const he_ctx* ctx, uint32_t level);
+size_t ks_scratch_elems(const he_ctx* ctx, uint32_t level);

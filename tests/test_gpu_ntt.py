@@ -1,0 +1,128 @@
+"""GPU parity: he_ntt / he_intt / he_automorph vs the CPU oracle, bit-exact."""
+import numpy as np
+import pytest
+
+from he_inputs import sampling as S
+from he_inputs.params import config_params, ntt_primes, toy_params
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mods():
+    from oracle.he_oracle import Oracle
+    from paper_2302_02407_amd.binding import HEContext
+    return Oracle, HEContext
+
+
+@pytest.mark.parametrize("logN", [8, 9, 10, 11, 12, 13, 14])
+def test_ntt_small_rings_all_limbs(mods, logN):
+    from gpu_util import dev, host
+    Oracle, HEContext = mods
+    two_n = 2 << logN
+    q = ntt_primes(30, two_n, 2) + ntt_primes(54, two_n, 2)
+    p = ntt_primes(60, two_n, 1)
+    orc, ctx = Oracle(logN, q, p, 2), HEContext(logN, q, p, 2)
+    N = 1 << logN
+    for i in range(5):
+        assert ctx.he_ctx_psi(i) == orc.psi(i)
+    rng = S.make_rng(logN)
+    idx = [0, 1, 2, 3, 4, 4, 2, 0, 3]          # repeated and unordered moduli, ragged count
+    a = np.stack([S.uniform_limbs(rng, [(q + p)[i]], N)[0][0] for i in idx])
+    # edge values: zeros, q-1 everywhere, single monomials
+    a[0, :] = 0
+    a[1, :] = q[1] - 1
+    a[2, :] = 0
+    a[2, N - 1] = 1
+    d = dev(a)
+    ctx.he_ntt(d, idx)
+    A = host(d)
+    assert (A == orc.ntt(a, idx)).all()
+    ctx.he_intt(d, idx)
+    assert (host(d) == a).all()
+    # inverse alone against the oracle on arbitrary NTT-form data
+    b = np.stack([S.uniform_limbs(rng, [(q + p)[i]], N)[0][0] for i in idx])
+    d = dev(b)
+    ctx.he_intt(d, idx)
+    assert (host(d) == orc.intt(b, idx)).all()
+
+
+def test_ntt_config0_batch(mods):
+    from gpu_util import dev, host
+    Oracle, HEContext = mods
+    prm = config_params(0)
+    orc, ctx = Oracle.from_params(prm), HEContext.from_params(prm)
+    rng = S.make_rng(0)
+    a = S.uniform_limbs(rng, prm.moduli, prm.N, 5)        # [5][4][N]
+    idx = list(range(4)) * 5
+    d = dev(a)
+    ctx.he_ntt(d, idx)
+    assert (host(d).reshape(20, prm.N) == orc.ntt(a.reshape(20, prm.N), idx)).all()
+
+
+def test_ntt_n65536_sampled_limbs_and_full_roundtrip(mods):
+    """Workload 1 at full size (16 polys x 24 limbs of 54-bit primes, N=2^16): every limb round-trips,
+    and a sample of limbs (first, last, middle of the batch) matches the oracle's forward transform."""
+    import torch
+    from gpu_util import dev, host
+    Oracle, HEContext = mods
+    prm = config_params(1)
+    orc, ctx = Oracle.from_params(prm), HEContext.from_params(prm)
+    rng = S.make_rng(prm.seed)
+    a = S.uniform_limbs(rng, prm.q, prm.N, 16)            # [16][24][N]
+    idx = list(range(24)) * 16
+    d = dev(a)
+    ctx.he_ntt(d, idx)
+    A = host(d).reshape(384, prm.N)
+    sample = [0, 1, 23, 24, 100, 200, 383]
+    want = orc.ntt(a.reshape(384, prm.N)[sample], [idx[i] for i in sample])
+    for k, i in enumerate(sample):
+        assert (A[i] == want[k]).all(), i
+    ctx.he_intt(d, idx)
+    assert torch.equal(d.cpu(), torch.from_numpy(a))
+    # special (60-bit) primes too
+    pm = [24, 31]
+    b = S.uniform_limbs(rng, [prm.moduli[i] for i in pm], prm.N)[0]
+    d = dev(b)
+    ctx.he_ntt(d, pm)
+    assert (host(d) == orc.ntt(b, pm)).all()
+    ctx.he_intt(d, pm)
+    assert (host(d) == b).all()
+
+
+@pytest.mark.parametrize("cfg", [0, 2])
+def test_automorph_both_forms(mods, cfg):
+    from gpu_util import dev, host, zeros
+    Oracle, HEContext = mods
+    prm = config_params(cfg)
+    orc, ctx = Oracle.from_params(prm), HEContext.from_params(prm)
+    rng = S.make_rng(50 + cfg)
+    idx = [0, len(prm.q) - 1, len(prm.q)]
+    a = S.uniform_limbs(rng, [prm.moduli[i] for i in idx], prm.N)[0]
+    a[0, :3] = 0                                            # negation of zero stays zero
+    for g in (orc.galois_elt(1), orc.galois_elt(prm.N // 2 - 7), orc.galois_conj, 1, 3):
+        out = zeros(3, prm.N)
+        ctx.he_automorph(dev(a), out, idx, g, ntt_form=True)
+        assert (host(out) == orc.automorph_ntt(a, g)).all()
+        ctx.he_automorph(dev(a), out, idx, g, ntt_form=False)
+        assert (host(out) == orc.automorph_coef(a, idx, g)).all()
+
+
+def test_bad_arguments_are_errors_not_faults(mods):
+    from gpu_util import zeros
+    from paper_2302_02407_amd.binding import HEError
+    Oracle, HEContext = mods
+    prm = config_params(0)
+    ctx = HEContext.from_params(prm)
+    d = zeros(2, prm.N)
+    with pytest.raises(HEError):
+        ctx.he_ntt(d, [0, 99])                   # modulus index out of range
+    with pytest.raises(HEError):
+        ctx.he_automorph(d, zeros(2, prm.N), [0, 1], 4)       # even Galois element
+    with pytest.raises(HEError):
+        ctx.he_automorph(d, d, [0, 1], 5)        # in-place not allowed
+    with pytest.raises(HEError):
+        HEContext(12, [17], [], 1)               # not 1 mod 2N / too small
+    with pytest.raises(HEError):
+        HEContext(12, [prm.q[0], prm.q[0]], [], 1)   # repeated modulus
+    ctx.he_ntt(d, [])                            # empty batch is a no-op
