@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X homomorphic-convolution hot path (one GPU).
+
+Primary workload (BASELINE configs[2]): rotation / key-switch benchmark at N = 2^16, 24 ciphertext
+limbs of 54 bits + 8 special primes of 60 bits, dnum = 3.  One step = a batch of ciphertexts, each
+rotated by all 15 power-of-two steps 2^0..2^14, once singly (own ModUp per rotation) and once
+hoisted (one shared ModUp): 30 key switches per ciphertext per step.  value = key switches / s.
+The same run also reports the NTT round-trip rate of configs[1] and the he_conv2d latency of
+configs[3] as extra fields, the roofline of the dominant kernel (the NTT tile kernel) from HIP
+events around each of its launches, and the CPU oracle timed on a bounded sample.
+
+All inputs are synthetic and seeded; ciphertexts, keys and plaintexts are uniform residues (what
+real ones look like limb by limb), generated on the device, so the timed region starts with
+everything resident in HBM.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def uniform_dev(torch, gen, moduli, N, lead=()):
+    """uint64 device tensor [*lead][len(moduli)][N], limb i uniform in [0, moduli[i])."""
+    cols = [torch.randint(0, int(m), tuple(lead) + (1, N), dtype=torch.int64, device="cuda", generator=gen)
+            for m in moduli]
+    return torch.cat(cols, dim=len(lead)).contiguous().view(torch.uint64)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--batch", type=int, default=16, help="ciphertexts per step (configs[2] names 64; value is a rate)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-extras", action="store_true", help="skip the NTT and conv2d extra measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from he_inputs.params import config_params
+    from paper_2302_02407_amd.binding import HEContext
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    prm = config_params(2)
+    N, L1, k = prm.N, len(prm.q), len(prm.p)
+    level = L1 - 1
+    ctx = HEContext.from_params(prm)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(prm.seed)
+
+    steps15 = [1 << i for i in range(15)]
+    keys = {}
+    for s in steps15:
+        keys[s] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+        ctx.he_evk_register(ctx.galois_elt(s), keys[s])
+    B = args.batch
+    cts = [uniform_dev(torch, gen, prm.q, N, lead=(2,)) for _ in range(B)]
+    outs = [torch.empty((2, L1, N), dtype=torch.uint64, device="cuda") for _ in steps15]
+
+    def step():
+        for ct in cts:
+            for i, s in enumerate(steps15):          # singly: every rotation does its own ModUp
+                ctx.he_rotate(ct, level, s, outs[i])
+            ctx.he_rotate_hoisted(ct, level, steps15, outs)   # hoisted: one ModUp for the 15 steps
+
+    ks_per_step = B * 30
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = ks_per_step * args.steps / dt
+
+    # single vs hoisted rates, one ciphertext each, HIP events on the context's stream
+    def timed(fn, reps=3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def single_pass():
+        for i, s in enumerate(steps15):
+            ctx.he_rotate(cts[0], level, s, outs[i])
+
+    ms_single = timed(single_pass)
+    ms_hoisted = timed(lambda: ctx.he_rotate_hoisted(cts[0], level, steps15, outs))
+
+    # roofline of the dominant kernel: one more, identical step with an event pair around every
+    # transform launch (kept out of the timed steps so the events do not perturb `value`)
+    ctx.he_profile_begin()
+    step()
+    prof = ctx.he_profile_end()
+    passes_per_transform = 2 if prm.logN > 11 else 1
+    # algorithmic bytes: a limb transform must read and write the limb once (2*N*8 B); each of
+    # its launches is credited an equal share
+    alg_bytes = prof["transform_limb_passes"] * (2.0 * N * 8) / passes_per_transform
+    achieved = alg_bytes / (prof["transform_ms"] * 1e-3) / 1e9
+    roofline = {
+        "kernel": "ntt_tile_kernel",
+        "bound": "hbm",
+        "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": None,
+        "launches": prof["transform_launches"],
+        "avg_launch_us": round(prof["transform_ms"] * 1e3 / max(1, prof["transform_launches"]), 2),
+        "share_of_step": round(prof["transform_ms"] / ms_per_step, 3),
+    }
+
+    extras = {
+        "single_keyswitch_per_s": round(15 / (ms_single * 1e-3), 1),
+        "hoisted_keyswitch_per_s": round(15 / (ms_hoisted * 1e-3), 1),
+    }
+    if not args.no_extras:
+        # configs[1]: NTT + iNTT round trip of 16 polys x 24 limbs; limb-GB/s counts the limb read and
+        # written once per transform
+        idx = list(range(L1)) * 16
+        data = uniform_dev(torch, gen, prm.q, N, lead=(16,))
+
+        def roundtrip():
+            ctx.he_ntt(data, idx)
+            ctx.he_intt(data, idx)
+
+        ms_rt = timed(roundtrip, reps=10)
+        extras["ntt_roundtrip_ms"] = round(ms_rt, 4)
+        extras["ntt_limb_GBps"] = round(384 * N * 8 * 2 * 2 / (ms_rt * 1e-3) / 1e9, 1)
+        del data
+        # configs[3]: ResNet-20-shaped CAConv, 16 -> 16 channels on 32x32, R = 2, level 23
+        conv_steps = sorted(set(((dy * 32 + dx) * 2) % (N // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0}
+                            | {2048, 4096, 8192, 16384})
+        for s in conv_steps:
+            if s not in keys:
+                keys[s] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+                ctx.he_evk_register(ctx.galois_elt(s), keys[s])
+        weights = [uniform_dev(torch, gen, prm.q, N) for _ in range(8 * 9)]
+        conv_out = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
+        ms_conv = timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, cts[0], conv_out), reps=2)
+        extras["conv2d_ms"] = round(ms_conv, 3)
+
+    cpu = None
+    if not args.no_cpu:
+        # the oracle as it stands, on the host cores, on a bounded sample of the same workload:
+        # one ciphertext, the first `n_cpu` of the 15 steps, singly and hoisted
+        import numpy as np
+        from oracle.he_oracle import Oracle, num_threads
+        orc = Oracle.from_params(prm)
+        n_cpu = 3
+        ct_h = cts[0].cpu().numpy()
+        keys_h = [keys[s].cpu().numpy() for s in steps15[:n_cpu]]
+        t0 = time.perf_counter()
+        for i in range(n_cpu):
+            orc.rotate(ct_h, level, orc.galois_elt(steps15[i]), keys_h[i])
+        raised = orc.modup(ct_h[1], level)
+        for i in range(n_cpu):
+            orc.rotate_from_raised(ct_h, raised, level, orc.galois_elt(steps15[i]), keys_h[i])
+        dt_cpu = time.perf_counter() - t0
+        cpu = {"value": round(2 * n_cpu / dt_cpu, 3), "unit": "keyswitch/s", "cores": num_threads(), "kind": "oracle",
+               "sample": "1 ciphertext x %d steps, singly + hoisted (%d key switches, %.1f s)" % (n_cpu, 2 * n_cpu, dt_cpu)}
+
+    out = {
+        "metric": "HRot keyswitches/s", "value": round(value, 1), "unit": "keyswitch/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "configs[2] rotation/key-switch: N=2^16, 24x54-bit + 8x60-bit primes, dnum=3, "
+                               "%d ciphertexts x 15 steps, singly and hoisted" % B,
+                   "batch": B, "keyswitches_per_step": ks_per_step},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    out.update(extras)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -88,6 +88,17 @@ const char* he_last_error(const he_ctx* ctx);
 int32_t he_ctx_psi(const he_ctx* ctx, uint32_t mod_idx, uint64_t* h_psi_out);
 int32_t he_counters(const he_ctx* ctx, he_counters_t* h_out);
 int32_t he_counters_reset(he_ctx* ctx);
+/* Timing of the transform kernels (the dominant kernels of every entry point) with a HIP event
+ * pair around each launch on the context's stream.  he_profile_begin starts collecting;
+ * he_profile_end synchronises the stream, sums the spans and stops.  transform_limb_passes
+ * counts limbs per launch (a full NTT of one limb at N > 2^11 is two launches = two passes). */
+typedef struct {
+    uint64_t transform_launches;
+    uint64_t transform_limb_passes;
+    double transform_ms;
+} he_profile_t;
+int32_t he_profile_begin(he_ctx* ctx);
+int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out);
 /* Block until everything enqueued on the context's stream has finished. */
 int32_t he_sync(he_ctx* ctx);
 

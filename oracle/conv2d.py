@@ -87,7 +87,7 @@ def encode_weights(orc: Oracle, geo: ConvGeometry, wt, level, pt_scale):
     return pts
 
 
-def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False):
+def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, progress=None):
     """ct [2][level+1][N] -> list of n_out ciphertexts [2][level][N].
 
     evks: dict slot-step -> evaluation key of the Galois element 5^step.
@@ -103,6 +103,8 @@ def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False):
         else:
             slid.append(orc.rotate_from_raised(ct, raised, level, orc.galois_elt(step), evks[step]))
     inter["slide"] = slid
+    if progress:
+        progress("oracle caconv: Slide_f done")
     outs = []
     for o in range(geo.n_out):
         acc = None
@@ -118,6 +120,8 @@ def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False):
             steps_out.append(cur)
         inter["ras"].append(steps_out)
         outs.append(cur)
+        if progress:
+            progress("oracle caconv: output %d/%d done" % (o + 1, geo.n_out))
     return (outs, inter) if keep else outs
 
 

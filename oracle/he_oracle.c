@@ -24,6 +24,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 typedef uint64_t u64;
 typedef unsigned __int128 u128;
@@ -83,6 +86,14 @@ orc_ctx* orc_create(uint32_t logN, const u64* q, uint32_t nq, const u64* p, uint
     return c;
 }
 void orc_destroy(orc_ctx* c) { free(c); }
+/* threads the limb-parallel loops will use */
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 u64 orc_psi(const orc_ctx* c, uint32_t mi) { return c->psi[mi]; }
 u64 orc_modulus(const orc_ctx* c, uint32_t mi) { return c->mod[mi]; }
 

@@ -50,6 +50,11 @@ def lib():
     return _lib
 
 
+def num_threads():
+    """Threads the oracle's limb-parallel loops use (OpenMP default)."""
+    return int(lib().orc_num_threads())
+
+
 def _p(a, typ=_u64p):
     return a.ctypes.data_as(typ)
 

@@ -16,7 +16,7 @@ HE_OK = 0
 _STATUS = {0: "HE_OK", -1: "HE_ERR_BADARG", -2: "HE_ERR_LEVEL", -3: "HE_ERR_NOKEY", -4: "HE_ERR_ALLOC", -5: "HE_ERR_HIP"}
 
 EXPORTS = [
-    "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync",
+    "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_rescale", "he_conv2d",
 ]
@@ -30,6 +30,10 @@ class HEError(RuntimeError):
 
 class Counters(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("keyswitch", "modup", "ntt_limbs", "intt_limbs", "mac", "rescale", "automorph")]
+
+
+class Profile(C.Structure):
+    _fields_ = [("transform_launches", C.c_uint64), ("transform_limb_passes", C.c_uint64), ("transform_ms", C.c_double)]
 
 
 class ConvPlan(C.Structure):
@@ -57,6 +61,8 @@ def load():
         "he_counters": [vp, C.POINTER(Counters)],
         "he_counters_reset": [vp],
         "he_sync": [vp],
+        "he_profile_begin": [vp],
+        "he_profile_end": [vp, C.POINTER(Profile)],
         "he_ntt": [vp, vp, u32p, u32],
         "he_intt": [vp, vp, u32p, u32],
         "he_automorph": [vp, vp, vp, u32p, u32, u32, i32],
@@ -88,6 +94,12 @@ def _dev(t, what="tensor"):
     if not t.is_contiguous():
         raise ValueError("%s must be contiguous" % what)
     return C.c_void_p(t.data_ptr())
+
+
+def _need(t, n, what):
+    """A buffer shorter than what the library will touch is the one mistake it cannot see itself."""
+    if t.numel() < n:
+        raise ValueError("%s holds %d elements, the call needs %d" % (what, t.numel(), n))
 
 
 def _u32arr(xs):
@@ -152,72 +164,89 @@ class HEContext:
     def he_sync(self):
         self._ck(self._lib.he_sync(self._h))
 
+    def he_profile_begin(self):
+        self._ck(self._lib.he_profile_begin(self._h))
+
+    def he_profile_end(self):
+        p = Profile()
+        self._ck(self._lib.he_profile_end(self._h, C.byref(p)))
+        return {n: getattr(p, n) for n, _ in Profile._fields_}
+
     def galois_elt(self, step):
         return pow(5, step % (self.N // 2), 2 * self.N)
 
     # ---- transforms
     def he_ntt(self, data, mod_idx):
         arr, n = _u32arr(mod_idx)
-        assert data.numel() == n * self.N
+        _need(data, n * self.N, "data")
         self._ck(self._lib.he_ntt(self._h, _dev(data), arr, n))
         return data
 
     def he_intt(self, data, mod_idx):
         arr, n = _u32arr(mod_idx)
-        assert data.numel() == n * self.N
+        _need(data, n * self.N, "data")
         self._ck(self._lib.he_intt(self._h, _dev(data), arr, n))
         return data
 
     def he_automorph(self, src, dst, mod_idx, galois_elt, ntt_form=True):
         arr, n = _u32arr(mod_idx)
-        assert src.numel() == n * self.N and dst.numel() == n * self.N
+        _need(src, n * self.N, "src")
+        _need(dst, n * self.N, "dst")
         self._ck(self._lib.he_automorph(self._h, _dev(src), _dev(dst), arr, n, galois_elt, 1 if ntt_form else 0))
         return dst
 
     # ---- key switching
     def he_evk_register(self, galois_elt, evk):
-        assert evk.numel() == self.dnum * 2 * (self.nq + self.np_) * self.N
+        _need(evk, self.dnum * 2 * (self.nq + self.np_) * self.N, "evk")
         self._ck(self._lib.he_evk_register(self._h, galois_elt, _dev(evk)))
         self._keys[galois_elt] = evk
 
     def he_keyswitch(self, poly, level, galois_elt_of_key, out0, out1):
-        assert poly.numel() == (level + 1) * self.N == out0.numel() == out1.numel()
+        for t, w in ((poly, "poly"), (out0, "out0"), (out1, "out1")):
+            _need(t, (level + 1) * self.N, w)
         self._ck(self._lib.he_keyswitch(self._h, _dev(poly), level, galois_elt_of_key, _dev(out0), _dev(out1)))
         return out0, out1
 
     def he_rotate_hoisted(self, ct, level, steps, outs):
         steps = [int(s) for s in steps]
-        assert len(outs) == len(steps) and ct.numel() == 2 * (level + 1) * self.N
-        for o in outs:
-            assert o.numel() == ct.numel()
+        if len(outs) != len(steps):
+            raise ValueError("one output per step")
+        for t in [ct] + list(outs):
+            _need(t, 2 * (level + 1) * self.N, "ciphertext")
         sa = (C.c_int32 * max(1, len(steps)))(*steps)
         pa = (C.c_void_p * max(1, len(outs)))(*[_dev(o).value for o in outs])
         self._ck(self._lib.he_rotate_hoisted(self._h, _dev(ct), level, sa, len(steps), pa))
         return outs
 
     def he_rotate(self, ct, level, step, out):
-        assert ct.numel() == 2 * (level + 1) * self.N == out.numel()
+        _need(ct, 2 * (level + 1) * self.N, "ct")
+        _need(out, 2 * (level + 1) * self.N, "out")
         self._ck(self._lib.he_rotate(self._h, _dev(ct), level, int(step), _dev(out)))
         return out
 
     def he_conjugate(self, ct, level, out):
-        assert ct.numel() == 2 * (level + 1) * self.N == out.numel()
+        _need(ct, 2 * (level + 1) * self.N, "ct")
+        _need(out, 2 * (level + 1) * self.N, "out")
         self._ck(self._lib.he_conjugate(self._h, _dev(ct), level, _dev(out)))
         return out
 
     # ---- MulPt accumulate / add / rescale
     def he_ptct_mac(self, acc, ct, pt, level, init):
-        assert acc.numel() == ct.numel() == 2 * (level + 1) * self.N and pt.numel() == (level + 1) * self.N
+        _need(acc, 2 * (level + 1) * self.N, "acc")
+        _need(ct, 2 * (level + 1) * self.N, "ct")
+        _need(pt, (level + 1) * self.N, "pt")
         self._ck(self._lib.he_ptct_mac(self._h, _dev(acc), _dev(ct), _dev(pt), level, 1 if init else 0))
         return acc
 
     def he_add(self, a, b, level, out):
-        assert a.numel() == b.numel() == out.numel() == 2 * (level + 1) * self.N
+        for t, w in ((a, "a"), (b, "b"), (out, "out")):
+            _need(t, 2 * (level + 1) * self.N, w)
         self._ck(self._lib.he_add(self._h, _dev(a), _dev(b), level, _dev(out)))
         return out
 
     def he_rescale(self, ct, level, out):
-        assert ct.numel() == 2 * (level + 1) * self.N and out.numel() == 2 * level * self.N
+        _need(ct, 2 * (level + 1) * self.N, "ct")
+        _need(out, 2 * level * self.N, "out")
         self._ck(self._lib.he_rescale(self._h, _dev(ct), level, _dev(out)))
         return out
 
@@ -225,11 +254,13 @@ class HEContext:
     def he_conv2d(self, C_a, H, W, R, f, level, weights, ct_in, outs):
         """weights: list of n_out*f*f device tensors [level+1][N]; outs: n_out tensors [2][level][N]."""
         n_out = len(outs)
-        assert len(weights) == n_out * f * f and ct_in.numel() == 2 * (level + 1) * self.N
+        if len(weights) != n_out * f * f:
+            raise ValueError("need n_out*f*f weight plaintexts")
+        _need(ct_in, 2 * (level + 1) * self.N, "ct_in")
         for w in weights:
-            assert w.numel() == (level + 1) * self.N
+            _need(w, (level + 1) * self.N, "weight plaintext")
         for o in outs:
-            assert o.numel() == 2 * level * self.N
+            _need(o, 2 * level * self.N, "output")
         wa = (C.c_void_p * len(weights))(*[_dev(w).value for w in weights])
         oa = (C.c_void_p * n_out)(*[_dev(o).value for o in outs])
         plan = ConvPlan(C_a, H, W, R, f, n_out, level, C.cast(wa, C.POINTER(C.c_void_p)))

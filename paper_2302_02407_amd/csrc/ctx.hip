@@ -113,6 +113,7 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
     c->d_ws = nullptr; c->ws_bytes = 0;
     c->d_up_hat = c->d_dn_hat = c->d_pinv = c->d_pinv_sh = c->d_qlinv = c->d_qlinv_sh = nullptr;
     memset(&c->cnt, 0, sizeof(c->cnt));
+    c->prof_on = false;
     if (hipGetDevice(&c->device) != hipSuccess) {
         delete c;
         return he_fail(nullptr, HE_ERR_HIP, "he_ctx_create: no HIP device");
@@ -194,6 +195,7 @@ int32_t he_ctx_destroy(he_ctx* c) {
     if (c->d_itw) (void)hipFree(c->d_itw);
     if (c->d_itw_sh) (void)hipFree(c->d_itw_sh);
     if (c->d_ws) (void)hipFree(c->d_ws);
+    for (auto& s : c->prof_events) { (void)hipEventDestroy(s.e0); (void)hipEventDestroy(s.e1); }
     ks_free_tables(c);
     delete c;
     return HE_OK;
@@ -214,6 +216,34 @@ int32_t he_counters(const he_ctx* ctx, he_counters_t* h_out) {
 int32_t he_counters_reset(he_ctx* ctx) {
     if (!ctx) return HE_ERR_BADARG;
     memset(&ctx->cnt, 0, sizeof(ctx->cnt));
+    return HE_OK;
+}
+
+int32_t he_profile_begin(he_ctx* ctx) {
+    if (!ctx) return HE_ERR_BADARG;
+    for (auto& s : ctx->prof_events) { (void)hipEventDestroy(s.e0); (void)hipEventDestroy(s.e1); }
+    ctx->prof_events.clear();
+    ctx->prof_on = true;
+    return HE_OK;
+}
+
+int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out) {
+    if (!ctx || !h_out) return HE_ERR_BADARG;
+    ctx->prof_on = false;
+    HE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    h_out->transform_launches = 0;
+    h_out->transform_limb_passes = 0;
+    h_out->transform_ms = 0.0;
+    for (auto& s : ctx->prof_events) {
+        float ms = 0.f;
+        HE_HIP(ctx, hipEventElapsedTime(&ms, s.e0, s.e1));
+        h_out->transform_launches += 1;
+        h_out->transform_limb_passes += s.limbs;
+        h_out->transform_ms += ms;
+        (void)hipEventDestroy(s.e0);
+        (void)hipEventDestroy(s.e1);
+    }
+    ctx->prof_events.clear();
     return HE_OK;
 }
 

@@ -36,6 +36,11 @@ struct ScaleList {
     u64 s_sh[HE_MAX_MODULI];
 };
 
+struct ProfSpan {
+    hipEvent_t e0, e1;
+    uint32_t limbs;   // limbs transformed by the launch between the two events
+};
+
 struct he_ctx {
     uint32_t logN, N, nq, np, dnum, alpha, M; // M = nq + np
     hipStream_t stream;
@@ -64,6 +69,8 @@ struct he_ctx {
     size_t ws_bytes;
     std::map<uint32_t, const u64*> evk; // Galois element -> device key
     he_counters_t cnt;
+    bool prof_on;                       // time every transform launch with an event pair
+    std::vector<ProfSpan> prof_events;
     std::string err;
 };
 

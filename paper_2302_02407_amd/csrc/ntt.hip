@@ -143,11 +143,21 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
         a.s_begin = strided ? 0 : sA;
         a.s_end = strided ? sA : ctx->logN;
         a.last = (FWD ? !strided : (strided || sA == 0)) ? 1 : 0;
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (ctx->prof_on) {
+            HE_HIP(ctx, hipEventCreate(&e0));
+            HE_HIP(ctx, hipEventCreate(&e1));
+            HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
+        }
         if (scale)
             hipLaunchKernelGGL((ntt_tile_kernel<FWD, true>), grid, block, 0, ctx->stream, a, ll, sc);
         else
             hipLaunchKernelGGL((ntt_tile_kernel<FWD, false>), grid, block, 0, ctx->stream, a, ll, sc);
         HE_HIP(ctx, hipGetLastError());
+        if (ctx->prof_on) {
+            HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
+            ctx->prof_events.push_back({e0, e1, live});
+        }
     }
     if (FWD) ctx->cnt.ntt_limbs += live; else ctx->cnt.intt_limbs += live;
     return HE_OK;
@@ -164,6 +174,7 @@ extern "C" {
 
 int32_t he_ntt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_t n_limbs) {
     if (!ctx) return HE_ERR_BADARG;
+    if (n_limbs == 0) return HE_OK;
     if (!d_data || !h_mod_idx) return he_fail(ctx, HE_ERR_BADARG, "he_ntt: null argument");
     for (uint32_t i = 0; i < n_limbs; i++)
         if (h_mod_idx[i] >= ctx->M) return he_fail(ctx, HE_ERR_BADARG, "he_ntt: modulus index %u out of range", h_mod_idx[i]);
@@ -177,6 +188,7 @@ int32_t he_ntt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_
 
 int32_t he_intt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_t n_limbs) {
     if (!ctx) return HE_ERR_BADARG;
+    if (n_limbs == 0) return HE_OK;
     if (!d_data || !h_mod_idx) return he_fail(ctx, HE_ERR_BADARG, "he_intt: null argument");
     for (uint32_t i = 0; i < n_limbs; i++)
         if (h_mod_idx[i] >= ctx->M) return he_fail(ctx, HE_ERR_BADARG, "he_intt: modulus index %u out of range", h_mod_idx[i]);

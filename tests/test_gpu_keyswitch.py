@@ -1,0 +1,166 @@
+"""GPU parity: key switching, rotations (single and hoisted), conjugation, MulPt-accumulate,
+add and rescale vs the CPU oracle, bit-exact; plus Dec(Rot(Enc z)) = roll(z) on the GPU result."""
+import numpy as np
+import pytest
+
+from he_inputs import sampling as S
+from he_inputs.params import config_params, toy_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(prm, seed):
+    from oracle import ckks_client as K
+    from oracle.he_oracle import Oracle
+    from paper_2302_02407_amd.binding import HEContext
+    rng = S.make_rng(seed)
+    orc, ctx = Oracle.from_params(prm), HEContext.from_params(prm)
+    cl = K.Client(orc, S.ternary_secret(rng, prm.N, prm.hamming))
+    return rng, orc, ctx, cl
+
+
+def _key(prm, rng, cl, g):
+    return cl.rotation_key(g, S.uniform_limbs(rng, prm.moduli, prm.N, prm.dnum),
+                           S.gaussian_error(rng, prm.N, prm.sigma, prm.dnum))
+
+
+def _rand_ct(prm, rng, level):
+    return np.stack([S.uniform_limbs(rng, prm.q[:level + 1], prm.N)[0] for _ in range(2)])
+
+
+@pytest.mark.parametrize("level", [5, 4, 3, 2, 0])
+def test_keyswitch_and_rotations_partial_digits(level):
+    """6 primes, dnum 3 (alpha 2): levels with a partial last digit and fewer digits than dnum."""
+    from gpu_util import dev, host, zeros
+    prm = toy_params(logN=8, q_bits=30, nq=6, p_bits=32, np_=2, dnum=3, hamming=16, seed=60)
+    rng, orc, ctx, cl = _setup(prm, 60 + level)
+    N = prm.N
+    steps = [1, 5, N // 2 - 3]
+    keys = {s: _key(prm, rng, cl, orc.galois_elt(s)) for s in steps}
+    for s, k in keys.items():
+        ctx.he_evk_register(ctx.galois_elt(s), dev(k))
+    ct = _rand_ct(prm, rng, level)
+    # plain key switch of c1 with the key of step 1
+    o0, o1 = zeros(level + 1, N), zeros(level + 1, N)
+    ctx.he_keyswitch(dev(ct[1]), level, ctx.galois_elt(1), o0, o1)
+    w0, w1 = orc.keyswitch(ct[1], level, keys[1])
+    assert (host(o0) == w0).all() and (host(o1) == w1).all()
+    # hoisted rotations (with a zero step and a negative step) == oracle == single rotations
+    hs = [1, 0, 5, -3]
+    outs = [zeros(2, level + 1, N) for _ in hs]
+    ctx.he_rotate_hoisted(dev(ct), level, hs, outs)
+    for s, o in zip(hs, outs):
+        want = ct if s == 0 else orc.rotate(ct, level, orc.galois_elt(s), keys[s % (N // 2)])
+        assert (host(o) == want).all(), s
+        single = zeros(2, level + 1, N)
+        ctx.he_rotate(dev(ct), level, s, single)
+        assert (host(single) == want).all(), s
+
+
+def test_counters_and_errors():
+    from gpu_util import dev, zeros
+    from paper_2302_02407_amd.binding import HEError
+    prm = toy_params(logN=8, q_bits=30, nq=6, p_bits=32, np_=2, dnum=3, hamming=16, seed=61)
+    rng, orc, ctx, cl = _setup(prm, 61)
+    N, level = prm.N, 5
+    ct = dev(_rand_ct(prm, rng, level))
+    out = zeros(2, level + 1, N)
+    with pytest.raises(HEError) as e:
+        ctx.he_rotate(ct, level, 1, out)                    # no key registered
+    assert e.value.code == -3
+    with pytest.raises(HEError) as e:
+        ctx.he_rotate(zeros(2, 7, N), 6, 1, zeros(2, 7, N))  # level above L
+    assert e.value.code == -2
+    ctx.he_evk_register(ctx.galois_elt(1), dev(_key(prm, rng, cl, orc.galois_elt(1))))
+    with pytest.raises(HEError):
+        ctx.he_rotate(ct, level, 1, ct)                     # output overlaps input
+    with pytest.raises(HEError):
+        ctx.he_rescale(ct, 0, out)                          # cannot rescale at level 0
+    ctx.he_counters_reset()
+    ctx.he_rotate_hoisted(ct, level, [1, 0, 1], [zeros(2, level + 1, N) for _ in range(3)])
+    c = ctx.he_counters()
+    assert c["modup"] == 1 and c["keyswitch"] == 2
+    # per key switch at level 5 (beta=3, R=8): iNTT 6 + 2*2, NTT 3*6 + 2*6
+    assert c["intt_limbs"] == 6 + 2 * 4 and c["ntt_limbs"] == 18 + 2 * 12
+
+
+@pytest.mark.parametrize("cfg,level", [(0, 2), (0, 1), (2, 23), (2, 9)])
+def test_rotation_real_encryption(cfg, level):
+    """Real keys and a real encryption at the workload's parameters: GPU == oracle bit for bit, and
+    the GPU result decrypts to the rotated message."""
+    from gpu_util import dev, host, zeros
+    prm = config_params(cfg)
+    rng, orc, ctx, cl = _setup(prm, prm.seed)
+    N = prm.N
+    z = rng.uniform(-1, 1, N // 2) + 1j * rng.uniform(-1, 1, N // 2)
+    ct = cl.encrypt(z, prm.scale, level, S.uniform_limbs(rng, prm.q[:level + 1], N)[0], S.gaussian_error(rng, N, prm.sigma)[0])
+    steps = [1, 1 << (prm.logN - 2)]
+    # key-switch noise ~ beta*alpha*(q_max/P)*sqrt(N)*sigma/Delta: large at the tiny workload (one 41-bit
+    # special prime against 40-bit digits, Delta = 2^30), small at N = 2^16 (P = 2^472, Delta = 2^40)
+    tol = 1e-3 if cfg == 0 else 2e-5
+    keys = {s: _key(prm, rng, cl, orc.galois_elt(s)) for s in steps}
+    kc = _key(prm, rng, cl, orc.galois_conj)
+    for s, k in keys.items():
+        ctx.he_evk_register(ctx.galois_elt(s), dev(k))
+    ctx.he_evk_register(2 * N - 1, dev(kc))
+    outs = [zeros(2, level + 1, N) for _ in steps]
+    ctx.he_rotate_hoisted(dev(ct), level, steps, outs)
+    for s, o in zip(steps, outs):
+        got = host(o)
+        assert (got == orc.rotate(ct, level, orc.galois_elt(s), keys[s])).all()
+        assert np.max(np.abs(cl.decrypt(got, level, prm.scale) - np.roll(z, -s))) < tol
+    oc = zeros(2, level + 1, N)
+    ctx.he_conjugate(dev(ct), level, oc)
+    got = host(oc)
+    assert (got == orc.rotate(ct, level, orc.galois_conj, kc)).all()
+    assert np.max(np.abs(cl.decrypt(got, level, prm.scale) - np.conj(z))) < tol
+
+
+def test_config2_uniform_ciphertexts_subset():
+    """Workload 2 shape: uniform-random ciphertexts at level 23, rotated by power-of-two steps, singly and
+    hoisted; a seeded subset is compared with the oracle, hoisted == single on all of it."""
+    from gpu_util import dev, host, zeros
+    prm = config_params(2)
+    rng, orc, ctx, cl = _setup(prm, prm.seed)
+    N, level = prm.N, 23
+    steps = [1 << 0, 1 << 7, 1 << 14]
+    keys = {s: _key(prm, rng, cl, orc.galois_elt(s)) for s in steps}
+    for s, k in keys.items():
+        ctx.he_evk_register(ctx.galois_elt(s), dev(k))
+    for c in range(2):
+        ct = _rand_ct(prm, rng, level)
+        d = dev(ct)
+        outs = [zeros(2, level + 1, N) for _ in steps]
+        ctx.he_rotate_hoisted(d, level, steps, outs)
+        raised = orc.modup(ct[1], level)
+        for s, o in zip(steps, outs):
+            single = zeros(2, level + 1, N)
+            ctx.he_rotate(d, level, s, single)
+            got = host(o)
+            assert (got == host(single)).all()
+            assert (got == orc.rotate_from_raised(ct, raised, level, orc.galois_elt(s), keys[s])).all(), (c, s)
+
+
+@pytest.mark.parametrize("cfg,level", [(0, 2), (2, 23), (2, 1)])
+def test_mac_add_rescale(cfg, level):
+    from gpu_util import dev, host, zeros
+    prm = config_params(cfg)
+    rng, orc, ctx, cl = _setup(prm, 70 + cfg)
+    N = prm.N
+    ct, ct2 = _rand_ct(prm, rng, level), _rand_ct(prm, rng, level)
+    pt, pt2 = S.uniform_limbs(rng, prm.q[:level + 1], N)[0], S.uniform_limbs(rng, prm.q[:level + 1], N)[0]
+    pt[0, :5] = 0
+    ct[0, 0, :5] = np.uint64(prm.q[0] - 1)
+    acc = dev(np.full((2, level + 1, N), 12345, dtype=np.uint64))     # init must overwrite garbage
+    ctx.he_ptct_mac(acc, dev(ct), dev(pt), level, init=True)
+    w = orc.ptct_mac(None, ct, pt, level, init=True)
+    assert (host(acc) == w).all()
+    ctx.he_ptct_mac(acc, dev(ct2), dev(pt2), level, init=False)
+    w = orc.ptct_mac(w, ct2, pt2, level, init=False)
+    assert (host(acc) == w).all()
+    s = zeros(2, level + 1, N)
+    ctx.he_add(dev(ct), dev(ct2), level, s)
+    assert (host(s) == orc.add(ct, ct2, level)).all()
+    out = zeros(2, level, N)
+    ctx.he_rescale(acc, level, out)
+    assert (host(out) == orc.rescale(w, level)).all()
