@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhe_mi355x.so")
-SOURCES = ["ctx.hip", "ntt.hip", "elementwise.hip", "keyswitch.hip", "conv2d.hip"]
+SOURCES = ["ctx.hip", "ntt.hip", "ntt16.hip", "elementwise.hip", "keyswitch.hip", "conv2d.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fgpu-rdc" if False else "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

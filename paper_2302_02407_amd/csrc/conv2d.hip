@@ -104,7 +104,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
     for (uint32_t t = 0; t < taps; t++) {
         if (tap_g[t] == 1) { mt.ct[t] = ct_in; continue; }
         u64* out = slid + (size_t)nb++ * ct_e;
-        rc = ks_inner_moddown(ctx, raised, level, tap_g[t], tap_key[t], ct_in, out, out + (size_t)L1 * N, scratch);
+        rc = ks_inner_moddown(ctx, raised, ct_in + (size_t)L1 * N, level, tap_g[t], tap_key[t], ct_in, out, out + (size_t)L1 * N, scratch);
         if (rc != HE_OK) return rc;
         mt.ct[t] = out;
     }
@@ -124,7 +124,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         for (size_t s = 0; s < ras_g.size(); s++) {
             rc = modup_impl(ctx, out + (size_t)level * N, lo, raised_lo, scratch_lo);
             if (rc != HE_OK) return rc;
-            rc = ks_inner_moddown(ctx, raised_lo, lo, ras_g[s], ras_key[s], out, rot, rot + (size_t)level * N, scratch_lo);
+            rc = ks_inner_moddown(ctx, raised_lo, out + (size_t)level * N, lo, ras_g[s], ras_key[s], out, rot, rot + (size_t)level * N, scratch_lo);
             if (rc != HE_OK) return rc;
             dim3 g2(N / CV_THREADS, 2 * level);
             hipLaunchKernelGGL(add_inplace_kernel, g2, block, 0, ctx->stream, out, rot, ctx->d_mc, ctx->logN, level);

@@ -95,15 +95,32 @@ uint32_t h_galois_of_step(const he_ctx* ctx, int32_t step);
 // (which must already include N^-1).
 int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n);
 int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale);
+int32_t launch_ntt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n);
+int32_t launch_intt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n,
+                         const ScaleList* scale);
+int32_t launch_transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
+                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale);
 int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g);
 int32_t launch_automorph_coef(he_ctx* ctx, const u64* in, u64* out, const uint32_t* mod_idx, uint32_t n, uint32_t g);
 
 // key switching internals (keyswitch.hip)
 int32_t ks_init_tables(he_ctx* ctx);
 void ks_free_tables(he_ctx* ctx);
-int32_t ks_modup(he_ctx* ctx, const u64* d_poly, uint32_t level, u64* d_raised);
-int32_t ks_inner_moddown(he_ctx* ctx, const u64* d_raised, uint32_t level, uint32_t g_perm, const u64* d_evk,
-                         const u64* d_c0, u64* d_out0, u64* d_out1, u64* d_scratch);
+int32_t ks_inner_moddown(he_ctx* ctx, const u64* d_raised, const u64* d_own, uint32_t level, uint32_t g_perm,
+                         const u64* d_evk, const u64* d_c0, u64* d_out0, u64* d_out1, u64* d_scratch);
+// Epilogue of ModDown fused into the last pass of the forward transform of the converted p-part:
+// limb i of the launch is component i / L1, limb r = i % L1; out_c[r] = (acc_c[r] - ntt) * P^-1
+// (+ c0[r] gathered by the Galois map of g for component 0).
+struct ModDownEpilogue {
+    const u64* acc;     // [2][R][N]
+    const u64* c0;      // [L1][N] or nullptr
+    u64* out0;
+    u64* out1;
+    const u64* pinv;    // [nq]
+    const u64* pinv_sh;
+    uint32_t R, L1, g;
+};
+int32_t launch_ntt16_moddown(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ModDownEpilogue& ep);
 int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, u64* d_tmp);
 size_t rescale_ws_elems(const he_ctx* c, uint32_t level);
 int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u64* ws);

@@ -24,8 +24,8 @@ __device__ __forceinline__ uint32_t galois_src_ks(uint32_t j, uint32_t g, uint32
 struct ConvJob {
     const u64* src;       // [ns][N] coefficient form, already multiplied by the inverse "hat" factors
     u64* dst;             // target limb t is written at dst + tgt_limb[t]*N
-    const u64* hat;       // hat[i*hat_stride + modulus index] = (S/s_i) mod that modulus
-    uint32_t ns, nt, hat_stride, pad;
+    const u64* hat;       // hat[m*hat_w + i] = (S/s_i) mod modulus m, zero for i >= ns
+    uint32_t ns, nt, hat_w, pad;   // hat_w = ns rounded up to a multiple of 8 (<= 64)
     uint8_t tgt_limb[HE_MAX_MODULI];
     uint8_t tgt_mod[HE_MAX_MODULI];
 };
@@ -33,41 +33,71 @@ struct ConvBatch {
     ConvJob job[CONV_MAX_JOBS];
 };
 
-// grid: (N/256, ceil(nt_max/CONV_TGT_PER_BLOCK), jobs)
+// Fast basis conversion.  grid: (N/512, ceil(nt_max/CONV_TGT_PER_BLOCK), jobs); each thread owns two
+// adjacent coefficients (16-byte loads and stores).  The block's conversion constants and target
+// moduli are staged in LDS once and then read as broadcasts.  With at most 8 source limbs
+// (ONE_CHUNK) the pre-scaled sources stay in registers across all targets of the block.
+template <bool ONE_CHUNK>
 __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const ModConst* mc, uint32_t logN) {
+    __shared__ u64 s_hat[CONV_TGT_PER_BLOCK * 64];
+    __shared__ u64 s_q[CONV_TGT_PER_BLOCK], s_mu[CONV_TGT_PER_BLOCK];
+    __shared__ uint32_t s_bits[CONV_TGT_PER_BLOCK];
     const ConvJob& job = b.job[blockIdx.z];
-    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
     const uint32_t t0 = blockIdx.y * CONV_TGT_PER_BLOCK;
     if (t0 >= job.nt) return;
-    const uint32_t t1 = min(t0 + CONV_TGT_PER_BLOCK, job.nt);
-    const uint32_t ns = job.ns;
-    u64 y[8];
+    const uint32_t nt = min((uint32_t)CONV_TGT_PER_BLOCK, job.nt - t0);
+    const uint32_t ns = job.ns, w = job.hat_w;
+    for (uint32_t idx = threadIdx.x; idx < nt * w; idx += KS_THREADS) {
+        uint32_t tt = idx / w, i = idx - tt * w;
+        s_hat[tt * 64 + i] = job.hat[(size_t)job.tgt_mod[t0 + tt] * w + i];
+    }
+    if (threadIdx.x < nt) {
+        const ModConst m = mc[job.tgt_mod[t0 + threadIdx.x]];
+        s_q[threadIdx.x] = m.q; s_mu[threadIdx.x] = m.mu; s_bits[threadIdx.x] = m.bits;
+    }
+    __syncthreads();
+    const size_t n = (size_t)(blockIdx.x * KS_THREADS + threadIdx.x) * 2;
+    if (n >= ((size_t)1 << logN)) return;      // rings smaller than one block of coefficient pairs
+    ulonglong2 y[8];
+    if (ONE_CHUNK) {
 #pragma unroll
-    for (uint32_t i = 0; i < 8; i++) y[i] = i < ns ? job.src[((size_t)i << logN) + n] : 0;
-    for (uint32_t t = t0; t < t1; t++) {
-        const uint32_t mi = job.tgt_mod[t];
-        const ModConst m = mc[mi];
-        u128 acc = 0;
-        if (ns <= 8) {
+        for (uint32_t i = 0; i < 8; i++)
+            y[i] = i < ns ? *reinterpret_cast<const ulonglong2*>(job.src + ((size_t)i << logN) + n) : make_ulonglong2(0, 0);
+    }
+    for (uint32_t tt = 0; tt < nt; tt++) {
+        const u64 q = s_q[tt], mu = s_mu[tt];
+        const uint32_t bits = s_bits[tt];
+        const u64* h = s_hat + tt * 64;
+        u128 a0 = 0, a1 = 0;
+        if (ONE_CHUNK) {
 #pragma unroll
-            for (uint32_t i = 0; i < 8; i++)
-                if (i < ns) acc += (u128)y[i] * job.hat[i * job.hat_stride + mi];
+            for (uint32_t i = 0; i < 8; i++) {
+                a0 += (u128)y[i].x * h[i];
+                a1 += (u128)y[i].y * h[i];
+            }
         } else {
             for (uint32_t i0 = 0; i0 < ns; i0 += 8) {
-                if (i0) acc = barrett128(acc, m.q, m.mu, m.bits);
-                for (uint32_t i = i0; i < min(i0 + 8, ns); i++)
-                    acc += (u128)job.src[((size_t)i << logN) + n] * job.hat[i * job.hat_stride + mi];
+                if (i0) { a0 = barrett128(a0, q, mu, bits); a1 = barrett128(a1, q, mu, bits); }
+                for (uint32_t i = i0; i < min(i0 + 8, ns); i++) {
+                    ulonglong2 v = *reinterpret_cast<const ulonglong2*>(job.src + ((size_t)i << logN) + n);
+                    a0 += (u128)v.x * h[i];
+                    a1 += (u128)v.y * h[i];
+                }
             }
         }
-        job.dst[((size_t)job.tgt_limb[t] << logN) + n] = barrett128(acc, m.q, m.mu, m.bits);
+        ulonglong2 o = make_ulonglong2(barrett128(a0, q, mu, bits), barrett128(a1, q, mu, bits));
+        *reinterpret_cast<ulonglong2*>(job.dst + ((size_t)job.tgt_limb[t0 + tt] << logN) + n) = o;
     }
 }
 
-// grid: (N/256, R).  raised [beta][R][N]; evk [dnum][2][M][N]; acc [2][R][N].
-__global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(const u64* __restrict__ raised, const u64* __restrict__ evk,
-                                                                   u64* __restrict__ acc, const ModConst* mc, uint32_t logN,
-                                                                   uint32_t R, uint32_t beta, uint32_t M, uint32_t level,
-                                                                   uint32_t nq, uint32_t g) {
+// grid: (N/256, R).  raised [beta][R][N]; evk [dnum][2][M][N]; acc [2][R][N].  A digit's own limbs
+// (limb r of digit r/alpha) are never materialised in `raised`: they are read from the input
+// polynomial `own` [level+1][N], which is what ModUp would have copied.
+__global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(const u64* __restrict__ raised, const u64* __restrict__ own,
+                                                                   const u64* __restrict__ evk, u64* __restrict__ acc,
+                                                                   const ModConst* mc, uint32_t logN, uint32_t R, uint32_t beta,
+                                                                   uint32_t M, uint32_t level, uint32_t nq, uint32_t alpha,
+                                                                   uint32_t g) {
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
     const uint32_t r = blockIdx.y;
     const uint32_t mi = r <= level ? r : nq + (r - level - 1);
@@ -79,7 +109,8 @@ __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(const u64* __
             a0 = barrett128(a0, m.q, m.mu, m.bits);
             a1 = barrett128(a1, m.q, m.mu, m.bits);
         }
-        u64 d = raised[((size_t)(j * R + r) << logN) + src];
+        const u64* dj = (r <= level && r / alpha == j) ? own + ((size_t)r << logN) : raised + ((size_t)(j * R + r) << logN);
+        u64 d = dj[src];
         a0 += (u128)d * evk[((size_t)((j * 2 + 0) * M + mi) << logN) + n];
         a1 += (u128)d * evk[((size_t)((j * 2 + 1) * M + mi) << logN) + n];
     }
@@ -134,6 +165,7 @@ __global__ __launch_bounds__(KS_THREADS) void rescale_final_kernel(const u64* __
 // ---------------------------------------------------------------- host: tables
 
 static uint32_t num_digits(const he_ctx* c, uint32_t level) { return (level + c->alpha) / c->alpha; }
+static uint32_t pad8(uint32_t x) { return (x + 7u) & ~7u; }
 
 size_t ks_raised_elems(const he_ctx* c, uint32_t level) {
     return (size_t)num_digits(c, level) * (level + 1 + c->np) * c->N;
@@ -163,35 +195,38 @@ int32_t ks_init_tables(he_ctx* c) {
         HE_HIP(c, hipMemcpy(c->d_qlinv_sh, inv_sh.data(), b, hipMemcpyHostToDevice));
     }
     if (np == 0) return HE_OK;
-    // ModUp: for digit j holding its first sz limbs (sz = 1..alpha), Q = prod of those limbs
-    std::vector<u64> hat((size_t)dn * al * al * M, 0);
+    // ModUp: digit j holding its first sz limbs (sz = 1..alpha), Q = product of those limbs.
+    // Device layout [j][sz-1][modulus m][i padded to aw]: the constants of one target are contiguous.
+    const uint32_t aw = pad8(al), pw = pad8(np);
+    std::vector<u64> hat((size_t)dn * al * M * aw, 0);
     c->h_up_invhat.assign((size_t)dn * al * al, 0);
     for (uint32_t j = 0; j < dn; j++) {
         uint32_t lo = j * al;
         for (uint32_t sz = 1; sz <= al && lo + sz <= nq; sz++)
             for (uint32_t i = 0; i < sz; i++) {
-                size_t base = ((size_t)(j * al + (sz - 1)) * al + i);
+                size_t slab = (size_t)(j * al + (sz - 1));
+                u64 own = 0;
                 for (uint32_t m = 0; m < M; m++) {
                     u64 v = 1;
                     for (uint32_t k = 0; k < sz; k++)
                         if (k != i) v = h_mulmod(v, c->mod[lo + k] % c->mod[m], c->mod[m]);
-                    hat[base * M + m] = v;
+                    hat[(slab * M + m) * aw + i] = v;
+                    if (m == lo + i) own = v;
                 }
-                u64 qi = c->mod[lo + i];
-                c->h_up_invhat[base] = h_invmod(hat[base * M + (lo + i)], qi);
+                c->h_up_invhat[slab * al + i] = h_invmod(own, c->mod[lo + i]);
             }
     }
-    // ModDown: P/p_t mod every modulus, (P/p_t)^-1 mod p_t, P^-1 mod q_r
-    std::vector<u64> dhat((size_t)np * M, 0), pinv(nq), pinv_sh(nq);
+    // ModDown: P/p_t mod every modulus ([m][t padded to pw]), (P/p_t)^-1 mod p_t, P^-1 mod q_r
+    std::vector<u64> dhat((size_t)M * pw, 0), pinv(nq), pinv_sh(nq);
     c->h_dn_invhat.assign(np, 0);
     for (uint32_t t = 0; t < np; t++) {
         for (uint32_t m = 0; m < M; m++) {
             u64 v = 1;
             for (uint32_t k = 0; k < np; k++)
                 if (k != t) v = h_mulmod(v, c->mod[nq + k] % c->mod[m], c->mod[m]);
-            dhat[(size_t)t * M + m] = v;
+            dhat[(size_t)m * pw + t] = v;
         }
-        c->h_dn_invhat[t] = h_invmod(dhat[(size_t)t * M + nq + t], c->mod[nq + t]);
+        c->h_dn_invhat[t] = h_invmod(dhat[(size_t)(nq + t) * pw + t], c->mod[nq + t]);
     }
     for (uint32_t r = 0; r < nq; r++) {
         u64 P = 1;
@@ -221,22 +256,22 @@ void ks_free_tables(he_ctx* c) {
 
 // ---------------------------------------------------------------- host: ModUp / ModDown
 
-static int32_t launch_baseconv(he_ctx* c, const ConvBatch& b, uint32_t jobs, uint32_t nt_max) {
-    dim3 grid(c->N / KS_THREADS, (nt_max + CONV_TGT_PER_BLOCK - 1) / CONV_TGT_PER_BLOCK, jobs), block(KS_THREADS);
-    hipLaunchKernelGGL(baseconv_kernel, grid, block, 0, c->stream, b, c->d_mc, c->logN);
+static int32_t launch_baseconv(he_ctx* c, const ConvBatch& b, uint32_t jobs, uint32_t nt_max, uint32_t ns_max) {
+    dim3 grid((c->N + 2 * KS_THREADS - 1) / (2 * KS_THREADS), (nt_max + CONV_TGT_PER_BLOCK - 1) / CONV_TGT_PER_BLOCK, jobs), block(KS_THREADS);
+    if (ns_max <= 8) hipLaunchKernelGGL(baseconv_kernel<true>, grid, block, 0, c->stream, b, c->d_mc, c->logN);
+    else hipLaunchKernelGGL(baseconv_kernel<false>, grid, block, 0, c->stream, b, c->d_mc, c->logN);
     HE_HIP(c, hipGetLastError());
     return HE_OK;
 }
 
-// d_poly [level+1][N] NTT form -> d_raised [beta][R][N] NTT form.  Uses scratch tmp_up
-// (level+1 limbs) at the start of the scratch region that follows d_raised in the workspace.
+// d_poly [level+1][N] NTT form -> d_raised [beta][R][N] NTT form, EXCEPT each digit's own limbs,
+// which are left unwritten (the inner product reads them from d_poly).  d_tmp: level+1 limbs.
 int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, u64* d_tmp) {
     const uint32_t N = c->N, L1 = level + 1, R = L1 + c->np, beta = num_digits(c, level), al = c->alpha;
-    const size_t limb_b = (size_t)N * sizeof(u64);
     // coefficient form of all limbs, each pre-multiplied by N^-1 * (Q_j/q_i)^-1
-    HE_HIP(c, hipMemcpyAsync(d_tmp, d_poly, L1 * limb_b, hipMemcpyDeviceToDevice, c->stream));
     ScaleList sc;
     uint32_t idx[HE_MAX_MODULI];
+    uint16_t from[HE_MAX_MODULI];
     for (uint32_t i = 0; i < L1; i++) {
         uint32_t j = i / al, lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1, sz = hi - lo;
         u64 qi = c->mod[i];
@@ -244,19 +279,21 @@ int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, 
         sc.s[i] = s;
         sc.s_sh[i] = h_shoup(s, qi);
         idx[i] = i;
+        from[i] = (uint16_t)i;
     }
-    int32_t rc = launch_intt(c, d_tmp, idx, L1, &sc);
+    int32_t rc = launch_intt_from(c, d_poly, from, d_tmp, idx, L1, &sc);
     if (rc != HE_OK) return rc;
+    const uint32_t aw = pad8(al);
     for (uint32_t j0 = 0; j0 < beta; j0 += CONV_MAX_JOBS) {
         ConvBatch b;
-        uint32_t jobs = beta - j0 < CONV_MAX_JOBS ? beta - j0 : CONV_MAX_JOBS, nt_max = 0;
+        uint32_t jobs = beta - j0 < CONV_MAX_JOBS ? beta - j0 : CONV_MAX_JOBS, nt_max = 0, ns_max = 0;
         for (uint32_t jj = 0; jj < jobs; jj++) {
             uint32_t j = j0 + jj, lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1, sz = hi - lo;
             ConvJob& job = b.job[jj];
             job.src = d_tmp + (size_t)lo * N;
             job.dst = d_raised + (size_t)j * R * N;
-            job.hat = c->d_up_hat + (size_t)(j * al + (sz - 1)) * al * c->M;
-            job.hat_stride = c->M;
+            job.hat = c->d_up_hat + (size_t)(j * al + (sz - 1)) * c->M * aw;
+            job.hat_w = aw;
             job.ns = sz;
             job.nt = 0;
             for (uint32_t r = 0; r < R; r++) {
@@ -266,10 +303,9 @@ int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, 
                 job.nt++;
             }
             if (job.nt > nt_max) nt_max = job.nt;
-            // the digit's own limbs are copied unchanged (already NTT form)
-            HE_HIP(c, hipMemcpyAsync(job.dst + (size_t)lo * N, d_poly + (size_t)lo * N, sz * limb_b, hipMemcpyDeviceToDevice, c->stream));
+            if (sz > ns_max) ns_max = sz;
         }
-        rc = launch_baseconv(c, b, jobs, nt_max);
+        rc = launch_baseconv(c, b, jobs, nt_max, ns_max);
         if (rc != HE_OK) return rc;
     }
     // NTT of every converted limb; own limbs are marked "skip"
@@ -289,14 +325,10 @@ int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, 
     return HE_OK;
 }
 
-int32_t ks_modup(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised) {
-    // tmp_up lives at the start of the scratch region, directly behind the raised digits
-    return modup_impl(c, d_poly, level, d_raised, d_raised + ks_raised_elems(c, level));
-}
-
-// raised [beta][R][N] -> (out0, out1) [level+1][N].  g_perm: Galois element applied to the
-// raised digits (and to c0 if given) as a gather; 1 = none.  d_scratch: ks_scratch_elems.
-int32_t ks_inner_moddown(he_ctx* c, const u64* d_raised, uint32_t level, uint32_t g_perm, const u64* d_evk,
+// raised [beta][R][N] (own limbs taken from d_own [level+1][N]) -> (out0, out1) [level+1][N].
+// g_perm: Galois element applied to the raised digits (and to c0 if given) as a gather; 1 = none.
+// d_scratch: ks_scratch_elems.
+int32_t ks_inner_moddown(he_ctx* c, const u64* d_raised, const u64* d_own, uint32_t level, uint32_t g_perm, const u64* d_evk,
                          const u64* d_c0, u64* d_out0, u64* d_out1, u64* d_scratch) {
     const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
     u64* acc = d_scratch + (size_t)L1 * N;       // after tmp_up
@@ -304,27 +336,25 @@ int32_t ks_inner_moddown(he_ctx* c, const u64* d_raised, uint32_t level, uint32_
     u64* conv = tmp_dn + (size_t)2 * k * N;      // [2][L1][N]
     {
         dim3 grid(N / KS_THREADS, R), block(KS_THREADS);
-        hipLaunchKernelGGL(inner_product_kernel, grid, block, 0, c->stream, d_raised, d_evk, acc, c->d_mc, c->logN, R, beta,
-                           c->M, level, c->nq, g_perm);
+        hipLaunchKernelGGL(inner_product_kernel, grid, block, 0, c->stream, d_raised, d_own, d_evk, acc, c->d_mc, c->logN, R,
+                           beta, c->M, level, c->nq, c->alpha, g_perm);
         HE_HIP(c, hipGetLastError());
     }
     // p-limbs of both accumulators -> coefficient form, pre-multiplied by N^-1 * (P/p_t)^-1
-    const size_t limb_b = (size_t)N * sizeof(u64);
-    for (uint32_t comp = 0; comp < 2; comp++)
-        HE_HIP(c, hipMemcpyAsync(tmp_dn + (size_t)comp * k * N, acc + ((size_t)comp * R + L1) * N, k * limb_b,
-                                 hipMemcpyDeviceToDevice, c->stream));
     if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
     ScaleList sc;
     uint32_t idx[HE_MAX_MODULI];
+    uint16_t from[HE_MAX_MODULI];
     for (uint32_t i = 0; i < 2 * k; i++) {
         uint32_t t = i % k;
+        from[i] = (uint16_t)((i / k) * R + L1 + t);
         u64 p = c->mod[c->nq + t];
         u64 s = h_mulmod(c->h_mc[c->nq + t].ninv, c->h_dn_invhat[t], p);
         sc.s[i] = s;
         sc.s_sh[i] = h_shoup(s, p);
         idx[i] = c->nq + t;
     }
-    int32_t rc = launch_intt(c, tmp_dn, idx, 2 * k, &sc);
+    int32_t rc = launch_intt_from(c, acc, from, tmp_dn, idx, 2 * k, &sc);
     if (rc != HE_OK) return rc;
     ConvBatch b;
     for (uint32_t comp = 0; comp < 2; comp++) {
@@ -332,18 +362,25 @@ int32_t ks_inner_moddown(he_ctx* c, const u64* d_raised, uint32_t level, uint32_
         job.src = tmp_dn + (size_t)comp * k * N;
         job.dst = conv + (size_t)comp * L1 * N;
         job.hat = c->d_dn_hat;
-        job.hat_stride = c->M;
+        job.hat_w = pad8(k);
         job.ns = k;
         job.nt = L1;
         for (uint32_t r = 0; r < L1; r++) { job.tgt_limb[r] = (uint8_t)r; job.tgt_mod[r] = (uint8_t)r; }
     }
-    rc = launch_baseconv(c, b, 2, L1);
+    rc = launch_baseconv(c, b, 2, L1, k);
     if (rc != HE_OK) return rc;
     std::vector<uint32_t> mods(2 * L1);
     for (uint32_t i = 0; i < 2 * L1; i++) mods[i] = i % L1;
-    rc = launch_ntt(c, conv, mods.data(), 2 * L1);
-    if (rc != HE_OK) return rc;
-    {
+    if (c->logN == 16 && 2 * L1 <= HE_MAX_LAUNCH_LIMBS) {
+        // the last NTT pass applies (acc - conv) * P^-1 (+ sigma_g(c0)) and writes the outputs itself
+        ModDownEpilogue ep;
+        ep.acc = acc; ep.c0 = d_c0; ep.out0 = d_out0; ep.out1 = d_out1;
+        ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1; ep.g = g_perm;
+        rc = launch_ntt16_moddown(c, conv, mods.data(), 2 * L1, ep);
+        if (rc != HE_OK) return rc;
+    } else {
+        rc = launch_ntt(c, conv, mods.data(), 2 * L1);
+        if (rc != HE_OK) return rc;
         dim3 grid(N / KS_THREADS, L1, 2), block(KS_THREADS);
         hipLaunchKernelGGL(moddown_final_kernel, grid, block, 0, c->stream, acc, conv, d_c0, d_out0, d_out1, c->d_mc, c->d_pinv,
                            c->d_pinv_sh, c->logN, R, L1, g_perm);
@@ -372,12 +409,9 @@ int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u
     const uint32_t N = ctx->N, L1 = level + 1;
     u64* tmp = ws;
     u64* delta = tmp + (size_t)2 * N;
-    const size_t limb_b = (size_t)N * sizeof(u64);
-    for (uint32_t comp = 0; comp < 2; comp++)
-        HE_HIP(ctx, hipMemcpyAsync(tmp + (size_t)comp * N, d_ct + ((size_t)comp * L1 + level) * N, limb_b,
-                                   hipMemcpyDeviceToDevice, ctx->stream));
     uint32_t two[2] = {level, level};
-    int32_t rc = launch_intt(ctx, tmp, two, 2, nullptr);
+    uint16_t from[2] = {(uint16_t)level, (uint16_t)(L1 + level)};
+    int32_t rc = launch_intt_from(ctx, d_ct, from, tmp, two, 2, nullptr);
     if (rc != HE_OK) return rc;
     dim3 grid(N / KS_THREADS, level, 2), block(KS_THREADS);
     hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level);
@@ -410,7 +444,7 @@ int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t
     u64* scratch = raised + ks_raised_elems(ctx, level);
     rc = modup_impl(ctx, (const u64*)d_in, level, raised, scratch);
     if (rc != HE_OK) return rc;
-    return ks_inner_moddown(ctx, raised, level, 1, it->second, nullptr, (u64*)d_out0, (u64*)d_out1, scratch);
+    return ks_inner_moddown(ctx, raised, (const u64*)d_in, level, 1, it->second, nullptr, (u64*)d_out0, (u64*)d_out1, scratch);
 }
 
 int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const int32_t* h_steps, uint32_t n_steps,
@@ -449,7 +483,7 @@ int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, con
             HE_HIP(ctx, hipMemcpyAsync(out, d_ct, ct_b, hipMemcpyDeviceToDevice, ctx->stream));
             continue;
         }
-        rc = ks_inner_moddown(ctx, raised, level, gs[i], keys[i], (const u64*)d_ct, out, out + (size_t)L1 * N, scratch);
+        rc = ks_inner_moddown(ctx, raised, (const u64*)d_ct + (size_t)L1 * N, level, gs[i], keys[i], (const u64*)d_ct, out, out + (size_t)L1 * N, scratch);
         if (rc != HE_OK) return rc;
     }
     return HE_OK;
@@ -474,7 +508,7 @@ int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t
     u64* scratch = raised + ks_raised_elems(ctx, level);
     rc = modup_impl(ctx, (const u64*)d_ct + (size_t)L1 * N, level, raised, scratch);
     if (rc != HE_OK) return rc;
-    return ks_inner_moddown(ctx, raised, level, g, it->second, (const u64*)d_ct, (u64*)d_out, (u64*)d_out + (size_t)L1 * N, scratch);
+    return ks_inner_moddown(ctx, raised, (const u64*)d_ct + (size_t)L1 * N, level, g, it->second, (const u64*)d_ct, (u64*)d_out, (u64*)d_out + (size_t)L1 * N, scratch);
 }
 
 int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out) {

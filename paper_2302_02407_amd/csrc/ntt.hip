@@ -164,10 +164,38 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
 }
 
 int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n) {
+    if (ctx->logN == 16) return launch_transform16(ctx, true, d, nullptr, d, mod_idx, n, nullptr);
     return run_transform<true>(ctx, d, mod_idx, n, nullptr);
 }
 int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale) {
+    if (ctx->logN == 16) return launch_transform16(ctx, false, d, nullptr, d, mod_idx, n, scale);
     return run_transform<false>(ctx, d, mod_idx, n, scale);
+}
+
+// Out-of-place variants: limb i is read at src + src_limb[i]*N and its transform written at
+// dst + i*N.  The N = 2^16 path reads the source directly in its first pass; other ring sizes
+// copy first and transform in place.
+static int32_t gather_limbs(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n) {
+    const size_t N = ctx->N;
+    for (uint32_t i = 0; i < n;) {
+        if (mod_idx[i] == 0xFFu) { i++; continue; }
+        uint32_t j = i + 1;     // extend over a run of consecutive source limbs
+        while (j < n && mod_idx[j] != 0xFFu && src_limb[j] == src_limb[i] + (j - i)) j++;
+        HE_HIP(ctx, hipMemcpyAsync(dst + i * N, src + (size_t)src_limb[i] * N, (j - i) * N * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream));
+        i = j;
+    }
+    return HE_OK;
+}
+int32_t launch_ntt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n) {
+    if (ctx->logN == 16) return launch_transform16(ctx, true, src, src_limb, dst, mod_idx, n, nullptr);
+    int32_t rc = gather_limbs(ctx, src, src_limb, dst, mod_idx, n);
+    return rc != HE_OK ? rc : run_transform<true>(ctx, dst, mod_idx, n, nullptr);
+}
+int32_t launch_intt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n,
+                         const ScaleList* scale) {
+    if (ctx->logN == 16) return launch_transform16(ctx, false, src, src_limb, dst, mod_idx, n, scale);
+    int32_t rc = gather_limbs(ctx, src, src_limb, dst, mod_idx, n);
+    return rc != HE_OK ? rc : run_transform<false>(ctx, dst, mod_idx, n, scale);
 }
 
 extern "C" {

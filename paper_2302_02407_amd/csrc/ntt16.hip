@@ -1,0 +1,319 @@
+// N = 2^16 fast path of the negacyclic NTT / iNTT (ring of paper Section 2.1).
+//
+// The limb is viewed as 256 x 256 (row-major).  A transform is two launches of 8 stages:
+//   forward : pass A on columns (stages 0..7, row distance 128..1), pass B on rows (stages 8..15);
+//   inverse : pass B on rows (stages 15..8), pass A on columns (stages 7..0) + final scaling.
+// Inside a pass every thread keeps 16 points of one 256-point sub-transform in registers and
+// runs 4 butterfly stages on them, then the 16 threads of the sub-transform exchange points
+// through LDS and run the other 4 stages: one LDS round trip replaces eight.  Points are held
+// either "strided" (thread t holds e = t + 16k, k-distance 8,4,2,1 = point distance 128..16) or
+// "contiguous" (e = 16t + j, point distance 8..1).
+//
+// Arithmetic: Harvey butterflies with Shoup twiddles.  For moduli below 2^58 the forward
+// butterflies never reduce: each stage adds at most 2q to the bound, 16 stages stay below 33q
+// < 2^64, and one small-quotient reduction canonicalises at the very end.  Wider moduli use
+// the classic [0,4q) form with one conditional subtraction per butterfly.  The inverse keeps
+// [0,2q) throughout.
+#include "modarith.cuh"
+
+#define T16_THREADS 256
+
+struct Ntt16Args {
+    const u64* src;     // limb i is read at src + src_limb[i]*N (first pass only)
+    u64* dst;           // and written / transformed in place at dst + i*N
+    const ModConst* mc;
+    const u64* tw;      // [M][N] forward or inverse twiddles
+    const u64* tw_sh;
+};
+struct SrcList {
+    uint16_t limb[HE_MAX_LAUNCH_LIMBS];
+};
+
+template <bool WIDE>
+__device__ __forceinline__ void ct_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q2) {
+    if (WIDE) X = csub(X, q2);
+    u64 T = shoup_lazy(Y, w, w_sh, q);
+    Y = X - T + q2;
+    X = X + T;
+}
+
+__device__ __forceinline__ void gs_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q2) {
+    u64 s = csub(X + Y, q2);
+    u64 d = X - Y + q2;
+    Y = shoup_lazy(d, w, w_sh, q);
+    X = s;
+}
+
+// Four forward stages on 16 register points; stage u pairs (k, k + (8>>u)); the twiddle of the
+// pair's group g = k >> (4-u) is tw[(1 << (s0+u)) + (G << u) + g], G = group of the 16 points at
+// stage s0.
+template <bool WIDE>
+__device__ __forceinline__ void fwd_block4(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh,
+                                           uint32_t s0, uint32_t G, u64 q, u64 q2) {
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+        const int dist = 8 >> u;
+        const uint32_t base = (1u << (s0 + u)) + (G << u);
+#pragma unroll
+        for (int g = 0; g < (1 << u); g++) {
+            const u64 w = tw[base + g], w_sh = tw_sh[base + g];
+#pragma unroll
+            for (int k = 0; k < dist; k++) {
+                const int a = g * 2 * dist + k;
+                ct_bfly<WIDE>(x[a], x[a + dist], w, w_sh, q, q2);
+            }
+        }
+    }
+}
+
+// Four inverse stages (point distance 1,2,4,8 in register index), same twiddle indexing.
+__device__ __forceinline__ void inv_block4(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh,
+                                           uint32_t s0, uint32_t G, u64 q, u64 q2) {
+#pragma unroll
+    for (int u = 3; u >= 0; u--) {
+        const int dist = 8 >> u;
+        const uint32_t base = (1u << (s0 + u)) + (G << u);
+#pragma unroll
+        for (int g = 0; g < (1 << u); g++) {
+            const u64 w = tw[base + g], w_sh = tw_sh[base + g];
+#pragma unroll
+            for (int k = 0; k < dist; k++) {
+                const int a = g * 2 * dist + k;
+                gs_bfly(x[a], x[a + dist], w, w_sh, q, q2);
+            }
+        }
+    }
+}
+
+// v mod q for v < 64q: a 6-bit quotient estimated from the top bits (never too large, at most 2
+// too small), then two conditional subtractions.
+__device__ __forceinline__ u64 reduce_small(u64 v, u64 q, uint32_t bits, uint32_t mrec) {
+    const uint32_t sh = bits - 8;                       // q >> sh in [128, 256)
+    uint32_t v1 = (uint32_t)(v >> sh);                  // < 2^14
+    uint32_t qh = (v1 * mrec) >> 24;                    // mrec = floor(2^24 / ((q >> sh) + 1))
+    u64 r = v - (u64)qh * q;
+    r = csub(r, 2 * q);
+    return csub(r, q);
+}
+
+// ---------------------------------------------------------------- forward
+// Pass A: workgroup = 16 adjacent columns x all 256 rows of one limb; tid = t*16 + col.
+template <bool WIDE>
+__device__ __forceinline__ void fwd_pass_a(const u64* __restrict__ src, u64* __restrict__ dst, u64* sm, const u64* tw,
+                                           const u64* tw_sh, uint32_t tile, u64 q, u64 q2) {
+    const uint32_t t = threadIdx.x >> 4, cl = threadIdx.x & 15, c = tile * 16 + cl;
+    u64 x[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = src[(size_t)(t + 16 * k) * 256 + c];
+    fwd_block4<WIDE>(x, tw, tw_sh, 0, 0, q, q2);
+#pragma unroll
+    for (int k = 0; k < 16; k++) sm[(t + 16 * k) * 16 + cl] = x[k];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; j++) x[j] = sm[(16 * t + j) * 16 + cl];
+    fwd_block4<WIDE>(x, tw, tw_sh, 4, t, q, q2);
+#pragma unroll
+    for (int j = 0; j < 16; j++) dst[(size_t)(16 * t + j) * 256 + c] = x[j];
+}
+
+__device__ __forceinline__ uint32_t galois_src16(uint32_t j, uint32_t g) {
+    uint32_t k = __brev(j) >> 16;
+    uint32_t kp = (g * k + ((g - 1) >> 1)) & 0xFFFFu;
+    return __brev(kp) >> 16;
+}
+
+// Pass B: workgroup = 16 consecutive rows (256-point blocks); tid = blk*16 + t.  With EPI the
+// canonical result is not stored: it feeds the ModDown epilogue, which writes the outputs.
+template <bool WIDE, bool EPI>
+__device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, const u64* tw, const u64* tw_sh, uint32_t tile,
+                                           const ModConst& m, uint32_t mrec, const ModDownEpilogue& ep, uint32_t limb) {
+    const u64 q = m.q, q2 = m.q2;
+    const uint32_t blk = threadIdx.x >> 4, t = threadIdx.x & 15, b = tile * 16 + blk;
+    u64* row = data + (size_t)b * 256;
+    u64* s = sm + blk * 272;                            // 16 groups of 17: conflict-free both ways
+    u64 x[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = row[t + 16 * k];
+    fwd_block4<WIDE>(x, tw, tw_sh, 8, b, q, q2);
+#pragma unroll
+    for (int k = 0; k < 16; k++) s[t + 17 * k] = x[k];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; j++) x[j] = s[17 * t + j];
+    fwd_block4<WIDE>(x, tw, tw_sh, 12, 16 * b + t, q, q2);
+#pragma unroll
+    for (int j = 0; j < 16; j++) x[j] = WIDE ? csub(csub(x[j], q2), q) : reduce_small(x[j], q, m.bits, mrec);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; j++) s[17 * t + j] = x[j];
+    __syncthreads();
+    if (!EPI) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) row[t + 16 * k] = s[t + 17 * k];
+    } else {
+        const uint32_t comp = limb / ep.L1, r = limb - comp * ep.L1;
+        const u64 pinv = ep.pinv[r], pinv_sh = ep.pinv_sh[r];
+        const u64* acc = ep.acc + ((size_t)(comp * ep.R + r) << 16) + (size_t)b * 256;
+        u64* out = (comp ? ep.out1 : ep.out0) + ((size_t)r << 16) + (size_t)b * 256;
+        const u64* c0 = (comp == 0 && ep.c0) ? ep.c0 + ((size_t)r << 16) : nullptr;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const uint32_t e = t + 16 * k;
+            u64 v = shoup_mul(submod(acc[e], s[t + 17 * k], q), pinv, pinv_sh, q);
+            if (c0) v = addmod(v, c0[ep.g == 1 ? b * 256 + e : galois_src16(b * 256 + e, ep.g)], q);
+            out[e] = v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_a_kernel(Ntt16Args a, LimbList ll, SrcList sl) {
+    __shared__ u64 sm[4096];
+    const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
+    const uint32_t mi = ll.mod[limb];
+    if (mi == 0xFFu) return;
+    const ModConst m = a.mc[mi];
+    const u64* src = a.src + ((size_t)sl.limb[limb] << 16);
+    u64* dst = a.dst + ((size_t)limb << 16);
+    const u64* tw = a.tw + ((size_t)mi << 16);
+    const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
+    if (m.bits >= 58) fwd_pass_a<true>(src, dst, sm, tw, tw_sh, tile, m.q, m.q2);
+    else fwd_pass_a<false>(src, dst, sm, tw, tw_sh, tile, m.q, m.q2);
+}
+
+template <bool EPI>
+__global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_b_kernel(Ntt16Args a, LimbList ll, ModDownEpilogue ep) {
+    __shared__ u64 sm[16 * 272];
+    const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
+    const uint32_t mi = ll.mod[limb];
+    if (mi == 0xFFu) return;
+    const ModConst m = a.mc[mi];
+    u64* data = a.dst + ((size_t)limb << 16);
+    const u64* tw = a.tw + ((size_t)mi << 16);
+    const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
+    if (m.bits >= 58) {
+        fwd_pass_b<true, EPI>(data, sm, tw, tw_sh, tile, m, 0, ep, limb);
+    } else {
+        const uint32_t mrec = (1u << 24) / ((uint32_t)(m.q >> (m.bits - 8)) + 1);
+        fwd_pass_b<false, EPI>(data, sm, tw, tw_sh, tile, m, mrec, ep, limb);
+    }
+}
+
+// ---------------------------------------------------------------- inverse
+// Pass B (rows) first: stages 15..12 on contiguous points, exchange, stages 11..8 on strided points.
+__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, LimbList ll, SrcList sl) {
+    __shared__ u64 sm[16 * 272];
+    const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
+    const uint32_t mi = ll.mod[limb];
+    if (mi == 0xFFu) return;
+    const ModConst m = a.mc[mi];
+    const u64 q = m.q, q2 = m.q2;
+    const u64* tw = a.tw + ((size_t)mi << 16);
+    const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
+    const uint32_t blk = threadIdx.x >> 4, t = threadIdx.x & 15, b = tile * 16 + blk;
+    const u64* in = a.src + ((size_t)sl.limb[limb] << 16) + (size_t)b * 256;
+    u64* out = a.dst + ((size_t)limb << 16) + (size_t)b * 256;
+    u64* s = sm + blk * 272;
+    u64 x[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) s[t + 17 * k] = in[t + 16 * k];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; j++) x[j] = s[17 * t + j];
+    inv_block4(x, tw, tw_sh, 12, 16 * b + t, q, q2);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; j++) s[17 * t + j] = x[j];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = s[t + 17 * k];
+    inv_block4(x, tw, tw_sh, 8, b, q, q2);
+#pragma unroll
+    for (int k = 0; k < 16; k++) out[t + 16 * k] = x[k];
+}
+
+// Pass A (columns): stages 7..4 on rows 16t+j, exchange, stages 3..0 on rows t+16k, final scale.
+template <bool CUSTOM_SCALE>
+__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, LimbList ll, ScaleList sc) {
+    __shared__ u64 sm[4096];
+    const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
+    const uint32_t mi = ll.mod[limb];
+    if (mi == 0xFFu) return;
+    const ModConst m = a.mc[mi];
+    const u64 q = m.q, q2 = m.q2;
+    const u64* tw = a.tw + ((size_t)mi << 16);
+    const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
+    u64* data = a.dst + ((size_t)limb << 16);
+    const uint32_t t = threadIdx.x >> 4, cl = threadIdx.x & 15, c = tile * 16 + cl;
+    u64 x[16];
+#pragma unroll
+    for (int j = 0; j < 16; j++) x[j] = data[(size_t)(16 * t + j) * 256 + c];
+    inv_block4(x, tw, tw_sh, 4, t, q, q2);
+#pragma unroll
+    for (int j = 0; j < 16; j++) sm[(16 * t + j) * 16 + cl] = x[j];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = sm[(t + 16 * k) * 16 + cl];
+    inv_block4(x, tw, tw_sh, 0, 0, q, q2);
+    const u64 scale = CUSTOM_SCALE ? sc.s[limb] : m.ninv;
+    const u64 scale_sh = CUSTOM_SCALE ? sc.s_sh[limb] : m.ninv_sh;
+#pragma unroll
+    for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(shoup_lazy(x[k], scale, scale_sh, q), q);
+}
+
+// ---------------------------------------------------------------- host
+// n <= HE_MAX_LAUNCH_LIMBS limbs; mod_idx[i] == 0xFF leaves limb i untouched.  src_limb == nullptr
+// means limb i is read at src + i*N (src may equal dst for an in-place transform).
+static int32_t transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
+                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale, const ModDownEpilogue* ep);
+
+int32_t launch_transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
+                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale) {
+    return transform16(ctx, fwd, src, src_limb, dst, mod_idx, n, scale, nullptr);
+}
+
+// Forward transform of d (in place for its first pass) whose last pass applies the ModDown epilogue.
+int32_t launch_ntt16_moddown(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ModDownEpilogue& ep) {
+    return transform16(ctx, true, d, nullptr, d, mod_idx, n, nullptr, &ep);
+}
+
+static int32_t transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
+                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale, const ModDownEpilogue* ep) {
+    if (n == 0) return HE_OK;
+    if (n > HE_MAX_LAUNCH_LIMBS || (scale && n > HE_MAX_MODULI)) return he_fail(ctx, HE_ERR_BADARG, "transform: too many limbs in one launch");
+    LimbList ll;
+    SrcList sl;
+    uint32_t live = 0;
+    for (uint32_t i = 0; i < n; i++) {
+        sl.limb[i] = src_limb ? src_limb[i] : (uint16_t)i;
+        if (mod_idx[i] == 0xFFu) { ll.mod[i] = 0xFF; continue; }
+        if (mod_idx[i] >= ctx->M) return he_fail(ctx, HE_ERR_BADARG, "transform: modulus index %u out of range", mod_idx[i]);
+        ll.mod[i] = (uint8_t)mod_idx[i];
+        live++;
+    }
+    Ntt16Args a;
+    a.src = src; a.dst = dst; a.mc = ctx->d_mc;
+    a.tw = fwd ? ctx->d_tw : ctx->d_itw;
+    a.tw_sh = fwd ? ctx->d_tw_sh : ctx->d_itw_sh;
+    dim3 grid(n * 16), block(T16_THREADS);
+    for (int pass = 0; pass < 2; pass++) {
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (ctx->prof_on) {
+            HE_HIP(ctx, hipEventCreate(&e0));
+            HE_HIP(ctx, hipEventCreate(&e1));
+            HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
+        }
+        if (fwd && pass == 0) hipLaunchKernelGGL(ntt16_fwd_a_kernel, grid, block, 0, ctx->stream, a, ll, sl);
+        else if (fwd && ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<true>, grid, block, 0, ctx->stream, a, ll, *ep);
+        else if (fwd) { ModDownEpilogue none = {}; hipLaunchKernelGGL(ntt16_fwd_b_kernel<false>, grid, block, 0, ctx->stream, a, ll, none); }
+        else if (pass == 0) hipLaunchKernelGGL(ntt16_inv_b_kernel, grid, block, 0, ctx->stream, a, ll, sl);
+        else if (scale) hipLaunchKernelGGL(ntt16_inv_a_kernel<true>, grid, block, 0, ctx->stream, a, ll, *scale);
+        else { ScaleList none; hipLaunchKernelGGL(ntt16_inv_a_kernel<false>, grid, block, 0, ctx->stream, a, ll, none); }
+        HE_HIP(ctx, hipGetLastError());
+        if (ctx->prof_on) {
+            HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
+            ctx->prof_events.push_back({e0, e1, live});
+        }
+    }
+    if (fwd) ctx->cnt.ntt_limbs += live; else ctx->cnt.intt_limbs += live;
+    return HE_OK;
+}

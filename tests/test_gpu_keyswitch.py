@@ -57,6 +57,21 @@ def test_keyswitch_and_rotations_partial_digits(level):
         assert (host(single) == want).all(), s
 
 
+def test_wide_digits_generic_conversion_path():
+    """alpha = 10 > 8 source limbs per digit: the conversion kernel's chunked path (and a 60-limb raised basis)."""
+    from gpu_util import dev, host, zeros
+    prm = toy_params(logN=8, q_bits=30, nq=20, p_bits=32, np_=10, dnum=2, hamming=16, seed=62)
+    rng, orc, ctx, cl = _setup(prm, 62)
+    N = prm.N
+    key = _key(prm, rng, cl, orc.galois_elt(3))
+    ctx.he_evk_register(ctx.galois_elt(3), dev(key))
+    for level in (19, 14, 9, 4):
+        ct = _rand_ct(prm, rng, level)
+        out = zeros(2, level + 1, N)
+        ctx.he_rotate(dev(ct), level, 3, out)
+        assert (host(out) == orc.rotate(ct, level, orc.galois_elt(3), key)).all(), level
+
+
 def test_counters_and_errors():
     from gpu_util import dev, zeros
     from paper_2302_02407_amd.binding import HEError
