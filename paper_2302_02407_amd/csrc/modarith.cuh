@@ -18,6 +18,21 @@ __device__ __forceinline__ u64 shoup_lazy(u64 y, u64 w, u64 w_sh, u64 q) {
 
 __device__ __forceinline__ u64 csub(u64 x, u64 q) { return x >= q ? x - q : x; }
 
+// High word of a*b from three 32x32 products (the low*low product and the carries out of the
+// middle column are dropped): never above the true value, at most 2 below it.
+__device__ __forceinline__ u64 mulhi64_approx(u64 a, u64 b) {
+    const uint32_t al = (uint32_t)a, ah = (uint32_t)(a >> 32), bl = (uint32_t)b, bh = (uint32_t)(b >> 32);
+    const u64 mid = (u64)__umulhi(ah, bl) + (u64)__umulhi(al, bh);
+    return (u64)ah * bh + mid;
+}
+
+// w*y mod q in [0, 4q): Shoup's product with the approximate quotient above (one multiply fewer
+// and no carry chain; the quotient is at most 2 short, each unit adds q to the remainder).
+__device__ __forceinline__ u64 shoup_lazy4(u64 y, u64 w, u64 w_sh, u64 q) {
+    u64 h = mulhi64_approx(w_sh, y);
+    return w * y - h * q;
+}
+
 // canonical w*y mod q
 __device__ __forceinline__ u64 shoup_mul(u64 y, u64 w, u64 w_sh, u64 q) { return csub(shoup_lazy(y, w, w_sh, q), q); }
 

@@ -9,11 +9,12 @@
 // either "strided" (thread t holds e = t + 16k, k-distance 8,4,2,1 = point distance 128..16) or
 // "contiguous" (e = 16t + j, point distance 8..1).
 //
-// Arithmetic: Harvey butterflies with Shoup twiddles.  For moduli below 2^58 the forward
-// butterflies never reduce: each stage adds at most 2q to the bound, 16 stages stay below 33q
-// < 2^64, and one small-quotient reduction canonicalises at the very end.  Wider moduli use
-// the classic [0,4q) form with one conditional subtraction per butterfly.  The inverse keeps
-// [0,2q) throughout.
+// Arithmetic: Harvey butterflies with Shoup twiddles whose quotient is taken from three 32-bit
+// products, so a twiddle product lands in [0,4q).  For moduli below 2^57 the forward butterflies
+// never reduce: each stage adds at most 4q to the bound, 16 stages stay below 65q < 2^64, and
+// one small-quotient reduction canonicalises at the very end.  Wider moduli (below 2^60) keep
+// [0,8q) with one conditional subtraction of 4q per butterfly.  The inverse keeps [0,4q)
+// throughout (sums are reduced, differences re-enter through the twiddle product).
 #include "modarith.cuh"
 
 #define T16_THREADS 256
@@ -28,19 +29,40 @@ struct Ntt16Args {
 struct SrcList {
     uint16_t limb[HE_MAX_LAUNCH_LIMBS];
 };
+// Work order of the row passes.  Their twiddles depend on (modulus, tile), so limbs that share a
+// modulus should run the same tile back to back on the same XCD (one L2 per XCD; workgroups are
+// handed to the 8 XCDs round-robin).  order[] lists the live limbs sorted by modulus, padded with
+// 0xFFFF to a multiple of the chunk size C = 1 << log_chunk; the linear work index
+// L = (chunk_of_limbs*16 + tile)*C + j walks the C limbs of a chunk for one tile, and
+// workgroup id -> L keeps each run of C consecutive L on one XCD.
+struct RowSched {
+    uint16_t order[HE_MAX_LAUNCH_LIMBS];
+    uint32_t log_chunk;
+};
 
+__device__ __forceinline__ bool row_sched_decode(const RowSched& rs, uint32_t& limb, uint32_t& tile) {
+    const uint32_t lc = rs.log_chunk, idx = blockIdx.x;
+    const uint32_t xcd = idx & 7u, slot = idx >> 3;
+    const uint32_t L = ((((slot >> lc) << 3) + xcd) << lc) | (slot & ((1u << lc) - 1u));
+    const uint32_t pchunk = L >> (4 + lc), rem = L & ((16u << lc) - 1u);
+    tile = rem >> lc;
+    limb = rs.order[(pchunk << lc) + (rem & ((1u << lc) - 1u))];
+    return limb != 0xFFFFu;
+}
+
+// q4 = 4q throughout this file.
 template <bool WIDE>
-__device__ __forceinline__ void ct_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q2) {
-    if (WIDE) X = csub(X, q2);
-    u64 T = shoup_lazy(Y, w, w_sh, q);
-    Y = X - T + q2;
+__device__ __forceinline__ void ct_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q4) {
+    if (WIDE) X = csub(X, q4);
+    u64 T = shoup_lazy4(Y, w, w_sh, q);
+    Y = (X + q4) - T;
     X = X + T;
 }
 
-__device__ __forceinline__ void gs_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q2) {
-    u64 s = csub(X + Y, q2);
-    u64 d = X - Y + q2;
-    Y = shoup_lazy(d, w, w_sh, q);
+__device__ __forceinline__ void gs_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q4) {
+    u64 s = csub(X + Y, q4);
+    u64 d = (X + q4) - Y;
+    Y = shoup_lazy4(d, w, w_sh, q);
     X = s;
 }
 
@@ -49,7 +71,7 @@ __device__ __forceinline__ void gs_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, 
 // stage s0.
 template <bool WIDE>
 __device__ __forceinline__ void fwd_block4(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh,
-                                           uint32_t s0, uint32_t G, u64 q, u64 q2) {
+                                           uint32_t s0, uint32_t G, u64 q, u64 q4) {
 #pragma unroll
     for (int u = 0; u < 4; u++) {
         const int dist = 8 >> u;
@@ -60,7 +82,7 @@ __device__ __forceinline__ void fwd_block4(u64 (&x)[16], const u64* __restrict__
 #pragma unroll
             for (int k = 0; k < dist; k++) {
                 const int a = g * 2 * dist + k;
-                ct_bfly<WIDE>(x[a], x[a + dist], w, w_sh, q, q2);
+                ct_bfly<WIDE>(x[a], x[a + dist], w, w_sh, q, q4);
             }
         }
     }
@@ -68,7 +90,7 @@ __device__ __forceinline__ void fwd_block4(u64 (&x)[16], const u64* __restrict__
 
 // Four inverse stages (point distance 1,2,4,8 in register index), same twiddle indexing.
 __device__ __forceinline__ void inv_block4(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh,
-                                           uint32_t s0, uint32_t G, u64 q, u64 q2) {
+                                           uint32_t s0, uint32_t G, u64 q, u64 q4) {
 #pragma unroll
     for (int u = 3; u >= 0; u--) {
         const int dist = 8 >> u;
@@ -79,17 +101,17 @@ __device__ __forceinline__ void inv_block4(u64 (&x)[16], const u64* __restrict__
 #pragma unroll
             for (int k = 0; k < dist; k++) {
                 const int a = g * 2 * dist + k;
-                gs_bfly(x[a], x[a + dist], w, w_sh, q, q2);
+                gs_bfly(x[a], x[a + dist], w, w_sh, q, q4);
             }
         }
     }
 }
 
-// v mod q for v < 64q: a 6-bit quotient estimated from the top bits (never too large, at most 2
+// v mod q for v < 100q: a 7-bit quotient estimated from the top bits (never too large, at most 2
 // too small), then two conditional subtractions.
 __device__ __forceinline__ u64 reduce_small(u64 v, u64 q, uint32_t bits, uint32_t mrec) {
     const uint32_t sh = bits - 8;                       // q >> sh in [128, 256)
-    uint32_t v1 = (uint32_t)(v >> sh);                  // < 2^14
+    uint32_t v1 = (uint32_t)(v >> sh);                  // < 100 * 256
     uint32_t qh = (v1 * mrec) >> 24;                    // mrec = floor(2^24 / ((q >> sh) + 1))
     u64 r = v - (u64)qh * q;
     r = csub(r, 2 * q);
@@ -100,18 +122,18 @@ __device__ __forceinline__ u64 reduce_small(u64 v, u64 q, uint32_t bits, uint32_
 // Pass A: workgroup = 16 adjacent columns x all 256 rows of one limb; tid = t*16 + col.
 template <bool WIDE>
 __device__ __forceinline__ void fwd_pass_a(const u64* __restrict__ src, u64* __restrict__ dst, u64* sm, const u64* tw,
-                                           const u64* tw_sh, uint32_t tile, u64 q, u64 q2) {
+                                           const u64* tw_sh, uint32_t tile, u64 q, u64 q4) {
     const uint32_t t = threadIdx.x >> 4, cl = threadIdx.x & 15, c = tile * 16 + cl;
     u64 x[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = src[(size_t)(t + 16 * k) * 256 + c];
-    fwd_block4<WIDE>(x, tw, tw_sh, 0, 0, q, q2);
+    fwd_block4<WIDE>(x, tw, tw_sh, 0, 0, q, q4);
 #pragma unroll
     for (int k = 0; k < 16; k++) sm[(t + 16 * k) * 16 + cl] = x[k];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) x[j] = sm[(16 * t + j) * 16 + cl];
-    fwd_block4<WIDE>(x, tw, tw_sh, 4, t, q, q2);
+    fwd_block4<WIDE>(x, tw, tw_sh, 4, t, q, q4);
 #pragma unroll
     for (int j = 0; j < 16; j++) dst[(size_t)(16 * t + j) * 256 + c] = x[j];
 }
@@ -127,22 +149,22 @@ __device__ __forceinline__ uint32_t galois_src16(uint32_t j, uint32_t g) {
 template <bool WIDE, bool EPI>
 __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, const u64* tw, const u64* tw_sh, uint32_t tile,
                                            const ModConst& m, uint32_t mrec, const ModDownEpilogue& ep, uint32_t limb) {
-    const u64 q = m.q, q2 = m.q2;
+    const u64 q = m.q, q2 = m.q2, q4 = 2 * m.q2;
     const uint32_t blk = threadIdx.x >> 4, t = threadIdx.x & 15, b = tile * 16 + blk;
     u64* row = data + (size_t)b * 256;
     u64* s = sm + blk * 272;                            // 16 groups of 17: conflict-free both ways
     u64 x[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = row[t + 16 * k];
-    fwd_block4<WIDE>(x, tw, tw_sh, 8, b, q, q2);
+    fwd_block4<WIDE>(x, tw, tw_sh, 8, b, q, q4);
 #pragma unroll
     for (int k = 0; k < 16; k++) s[t + 17 * k] = x[k];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) x[j] = s[17 * t + j];
-    fwd_block4<WIDE>(x, tw, tw_sh, 12, 16 * b + t, q, q2);
+    fwd_block4<WIDE>(x, tw, tw_sh, 12, 16 * b + t, q, q4);
 #pragma unroll
-    for (int j = 0; j < 16; j++) x[j] = WIDE ? csub(csub(x[j], q2), q) : reduce_small(x[j], q, m.bits, mrec);
+    for (int j = 0; j < 16; j++) x[j] = WIDE ? csub(csub(csub(x[j], q4), q2), q) : reduce_small(x[j], q, m.bits, mrec);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) s[17 * t + j] = x[j];
@@ -176,21 +198,21 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_a_kernel(Ntt16Args a, L
     u64* dst = a.dst + ((size_t)limb << 16);
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
-    if (m.bits >= 58) fwd_pass_a<true>(src, dst, sm, tw, tw_sh, tile, m.q, m.q2);
-    else fwd_pass_a<false>(src, dst, sm, tw, tw_sh, tile, m.q, m.q2);
+    if (m.bits > 57) fwd_pass_a<true>(src, dst, sm, tw, tw_sh, tile, m.q, 2 * m.q2);
+    else fwd_pass_a<false>(src, dst, sm, tw, tw_sh, tile, m.q, 2 * m.q2);
 }
 
 template <bool EPI>
-__global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_b_kernel(Ntt16Args a, LimbList ll, ModDownEpilogue ep) {
+__global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_b_kernel(Ntt16Args a, LimbList ll, RowSched rs, ModDownEpilogue ep) {
     __shared__ u64 sm[16 * 272];
-    const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
+    uint32_t limb, tile;
+    if (!row_sched_decode(rs, limb, tile)) return;
     const uint32_t mi = ll.mod[limb];
-    if (mi == 0xFFu) return;
     const ModConst m = a.mc[mi];
     u64* data = a.dst + ((size_t)limb << 16);
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
-    if (m.bits >= 58) {
+    if (m.bits > 57) {
         fwd_pass_b<true, EPI>(data, sm, tw, tw_sh, tile, m, 0, ep, limb);
     } else {
         const uint32_t mrec = (1u << 24) / ((uint32_t)(m.q >> (m.bits - 8)) + 1);
@@ -200,13 +222,13 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_b_kernel(Ntt16Args a, L
 
 // ---------------------------------------------------------------- inverse
 // Pass B (rows) first: stages 15..12 on contiguous points, exchange, stages 11..8 on strided points.
-__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, LimbList ll, SrcList sl) {
+__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, LimbList ll, SrcList sl, RowSched rs) {
     __shared__ u64 sm[16 * 272];
-    const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
+    uint32_t limb, tile;
+    if (!row_sched_decode(rs, limb, tile)) return;
     const uint32_t mi = ll.mod[limb];
-    if (mi == 0xFFu) return;
     const ModConst m = a.mc[mi];
-    const u64 q = m.q, q2 = m.q2;
+    const u64 q = m.q, q4 = 2 * m.q2;
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
     const uint32_t blk = threadIdx.x >> 4, t = threadIdx.x & 15, b = tile * 16 + blk;
@@ -219,14 +241,14 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) x[j] = s[17 * t + j];
-    inv_block4(x, tw, tw_sh, 12, 16 * b + t, q, q2);
+    inv_block4(x, tw, tw_sh, 12, 16 * b + t, q, q4);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) s[17 * t + j] = x[j];
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = s[t + 17 * k];
-    inv_block4(x, tw, tw_sh, 8, b, q, q2);
+    inv_block4(x, tw, tw_sh, 8, b, q, q4);
 #pragma unroll
     for (int k = 0; k < 16; k++) out[t + 16 * k] = x[k];
 }
@@ -239,7 +261,7 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, L
     const uint32_t mi = ll.mod[limb];
     if (mi == 0xFFu) return;
     const ModConst m = a.mc[mi];
-    const u64 q = m.q, q2 = m.q2;
+    const u64 q = m.q, q2 = m.q2, q4 = 2 * m.q2;
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
     u64* data = a.dst + ((size_t)limb << 16);
@@ -247,17 +269,17 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, L
     u64 x[16];
 #pragma unroll
     for (int j = 0; j < 16; j++) x[j] = data[(size_t)(16 * t + j) * 256 + c];
-    inv_block4(x, tw, tw_sh, 4, t, q, q2);
+    inv_block4(x, tw, tw_sh, 4, t, q, q4);
 #pragma unroll
     for (int j = 0; j < 16; j++) sm[(16 * t + j) * 16 + cl] = x[j];
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = sm[(t + 16 * k) * 16 + cl];
-    inv_block4(x, tw, tw_sh, 0, 0, q, q2);
+    inv_block4(x, tw, tw_sh, 0, 0, q, q4);
     const u64 scale = CUSTOM_SCALE ? sc.s[limb] : m.ninv;
     const u64 scale_sh = CUSTOM_SCALE ? sc.s_sh[limb] : m.ninv_sh;
 #pragma unroll
-    for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(shoup_lazy(x[k], scale, scale_sh, q), q);
+    for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(csub(shoup_lazy4(x[k], scale, scale_sh, q), q2), q);
 }
 
 // ---------------------------------------------------------------- host
@@ -290,11 +312,28 @@ static int32_t transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t
         ll.mod[i] = (uint8_t)mod_idx[i];
         live++;
     }
+    if (live == 0) return HE_OK;
     Ntt16Args a;
     a.src = src; a.dst = dst; a.mc = ctx->d_mc;
     a.tw = fwd ? ctx->d_tw : ctx->d_itw;
     a.tw_sh = fwd ? ctx->d_tw_sh : ctx->d_itw_sh;
     dim3 grid(n * 16), block(T16_THREADS);
+    // row-pass schedule: live limbs sorted by modulus (stable counting sort), chunked
+    RowSched rs;
+    uint32_t distinct = 0;
+    {
+        uint32_t count[HE_MAX_MODULI] = {0}, start[HE_MAX_MODULI];
+        for (uint32_t i = 0; i < n; i++) if (ll.mod[i] != 0xFF) count[ll.mod[i]]++;
+        uint32_t acc = 0;
+        for (uint32_t m = 0; m < ctx->M; m++) { start[m] = acc; acc += count[m]; if (count[m]) distinct++; }
+        for (uint32_t i = 0; i < n; i++) if (ll.mod[i] != 0xFF) rs.order[start[ll.mod[i]]++] = (uint16_t)i;
+    }
+    uint32_t lc = 0;
+    while (lc < 4 && (2u << lc) * distinct <= live) lc++;      // chunk <= average group size, at most 16
+    rs.log_chunk = lc;
+    uint32_t padded = (live + (1u << lc) - 1) & ~((1u << lc) - 1u);
+    for (uint32_t i = live; i < padded && i < HE_MAX_LAUNCH_LIMBS; i++) rs.order[i] = 0xFFFF;
+    dim3 grid_rows(padded * 16);
     for (int pass = 0; pass < 2; pass++) {
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (ctx->prof_on) {
@@ -303,9 +342,9 @@ static int32_t transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
         }
         if (fwd && pass == 0) hipLaunchKernelGGL(ntt16_fwd_a_kernel, grid, block, 0, ctx->stream, a, ll, sl);
-        else if (fwd && ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<true>, grid, block, 0, ctx->stream, a, ll, *ep);
-        else if (fwd) { ModDownEpilogue none = {}; hipLaunchKernelGGL(ntt16_fwd_b_kernel<false>, grid, block, 0, ctx->stream, a, ll, none); }
-        else if (pass == 0) hipLaunchKernelGGL(ntt16_inv_b_kernel, grid, block, 0, ctx->stream, a, ll, sl);
+        else if (fwd && ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<true>, grid_rows, block, 0, ctx->stream, a, ll, rs, *ep);
+        else if (fwd) { ModDownEpilogue none = {}; hipLaunchKernelGGL(ntt16_fwd_b_kernel<false>, grid_rows, block, 0, ctx->stream, a, ll, rs, none); }
+        else if (pass == 0) hipLaunchKernelGGL(ntt16_inv_b_kernel, grid_rows, block, 0, ctx->stream, a, ll, sl, rs);
         else if (scale) hipLaunchKernelGGL(ntt16_inv_a_kernel<true>, grid, block, 0, ctx->stream, a, ll, *scale);
         else { ScaleList none; hipLaunchKernelGGL(ntt16_inv_a_kernel<false>, grid, block, 0, ctx->stream, a, ll, none); }
         HE_HIP(ctx, hipGetLastError());
