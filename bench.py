@@ -4,7 +4,8 @@
 Primary workload (BASELINE configs[2]): rotation / key-switch benchmark at N = 2^16, 24 ciphertext
 limbs of 54 bits + 8 special primes of 60 bits, dnum = 3.  One step = a batch of ciphertexts, each
 rotated by all 15 power-of-two steps 2^0..2^14, once singly (own ModUp per rotation) and once
-hoisted (one shared ModUp): 30 key switches per ciphertext per step.  value = key switches / s.
+hoisted (one shared ModUp), both through the batched entry point he_rotate_batch: 30 key switches
+per ciphertext per step.  value = key switches / s.
 The same run also reports the NTT round-trip rate of configs[1] and the he_conv2d latency of
 configs[3] as extra fields, the roofline of the dominant kernel (the NTT tile kernel) from HIP
 events around each of its launches, and the CPU oracle timed on a bounded sample.
@@ -38,7 +39,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--batch", type=int, default=16, help="ciphertexts per step (configs[2] names 64; value is a rate)")
+    ap.add_argument("--batch", type=int, default=64, help="ciphertexts per step (configs[2] names 64)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the NTT and conv2d extra measurements")
     args = ap.parse_args()
@@ -68,13 +69,11 @@ def main():
         ctx.he_evk_register(ctx.galois_elt(s), keys[s])
     B = args.batch
     cts = [uniform_dev(torch, gen, prm.q, N, lead=(2,)) for _ in range(B)]
-    outs = [torch.empty((2, L1, N), dtype=torch.uint64, device="cuda") for _ in steps15]
+    outs = [torch.empty((2, L1, N), dtype=torch.uint64, device="cuda") for _ in range(B * 15)]
 
     def step():
-        for ct in cts:
-            for i, s in enumerate(steps15):          # singly: every rotation does its own ModUp
-                ctx.he_rotate(ct, level, s, outs[i])
-            ctx.he_rotate_hoisted(ct, level, steps15, outs)   # hoisted: one ModUp for the 15 steps
+        ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=False)   # singly: a ModUp per rotation
+        ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=True)    # hoisted: one ModUp per ciphertext
 
     ks_per_step = B * 30
     for _ in range(args.warmup):
@@ -100,12 +99,11 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    def single_pass():
-        for i, s in enumerate(steps15):
-            ctx.he_rotate(cts[0], level, s, outs[i])
-
-    ms_single = timed(single_pass)
-    ms_hoisted = timed(lambda: ctx.he_rotate_hoisted(cts[0], level, steps15, outs))
+    ms_single = timed(lambda: ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=False), reps=2)
+    ms_hoisted = timed(lambda: ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=True), reps=2)
+    # one ciphertext at a time through the plain entry points (latency-oriented callers)
+    ms_one_single = timed(lambda: [ctx.he_rotate(cts[0], level, s, outs[i]) for i, s in enumerate(steps15)])
+    ms_one_hoisted = timed(lambda: ctx.he_rotate_hoisted(cts[0], level, steps15, outs[:15]))
 
     # roofline of the dominant kernel: one more, identical step with an event pair around every
     # transform launch (kept out of the timed steps so the events do not perturb `value`)
@@ -131,8 +129,10 @@ def main():
     }
 
     extras = {
-        "single_keyswitch_per_s": round(15 / (ms_single * 1e-3), 1),
-        "hoisted_keyswitch_per_s": round(15 / (ms_hoisted * 1e-3), 1),
+        "single_keyswitch_per_s": round(15 * B / (ms_single * 1e-3), 1),
+        "hoisted_keyswitch_per_s": round(15 * B / (ms_hoisted * 1e-3), 1),
+        "one_ct_single_keyswitch_per_s": round(15 / (ms_one_single * 1e-3), 1),
+        "one_ct_hoisted_keyswitch_per_s": round(15 / (ms_one_hoisted * 1e-3), 1),
     }
     if not args.no_extras:
         # configs[1]: NTT + iNTT round trip of 16 polys x 24 limbs; limb-GB/s counts the limb read and

@@ -141,6 +141,14 @@ int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t
  * (ks0, ks1) = ModDown(acc); out = (sigma_g(c0) + ks0, ks1). */
 int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const int32_t* h_steps,
                           uint32_t n_steps, uint64_t* const* h_d_out);
+/* Batched CRot: every ciphertext h_d_ct[c] (c < n_ct, all [2][level+1][N] at `level`) rotated by
+ * every amount h_steps[s] (s < n_steps); h_d_out[c*n_steps + s] receives CRot(ct_c; steps_s).
+ * hoisted != 0: one ModUp per ciphertext shared by its n_steps rotations; hoisted == 0: one ModUp
+ * per rotation (the cost of n_ct*n_steps independent CRot calls; the results are the same bits).
+ * Launches are shared across the batch and rotations that use the same key share one pass over
+ * it.  No output may overlap an input or another output.  Workspace grows with the batch. */
+int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level,
+                        const int32_t* h_steps, uint32_t n_steps, uint64_t* const* h_d_out, int32_t hoisted);
 /* CRot(ct; step): identical bits to he_rotate_hoisted with n_steps = 1. */
 int32_t he_rotate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, int32_t step, uint64_t* d_out);
 /* Slot-wise complex conjugation (Galois element 2N-1, key registered under 2N-1). */

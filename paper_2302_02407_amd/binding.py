@@ -17,7 +17,7 @@ _STATUS = {0: "HE_OK", -1: "HE_ERR_BADARG", -2: "HE_ERR_LEVEL", -3: "HE_ERR_NOKE
 
 EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
-    "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate",
+    "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_rescale", "he_conv2d",
 ]
 
@@ -69,6 +69,7 @@ def load():
         "he_evk_register": [vp, u32, vp],
         "he_keyswitch": [vp, vp, u32, u32, vp, vp],
         "he_rotate_hoisted": [vp, vp, u32, i32p, u32, C.POINTER(vp)],
+        "he_rotate_batch": [vp, C.POINTER(vp), u32, u32, i32p, u32, C.POINTER(vp), i32],
         "he_rotate": [vp, vp, u32, i32, vp],
         "he_conjugate": [vp, vp, u32, vp],
         "he_ptct_mac": [vp, vp, vp, vp, u32, i32],
@@ -216,6 +217,19 @@ class HEContext:
         sa = (C.c_int32 * max(1, len(steps)))(*steps)
         pa = (C.c_void_p * max(1, len(outs)))(*[_dev(o).value for o in outs])
         self._ck(self._lib.he_rotate_hoisted(self._h, _dev(ct), level, sa, len(steps), pa))
+        return outs
+
+    def he_rotate_batch(self, cts, level, steps, outs, hoisted=True):
+        """outs[c*len(steps) + s] = CRot(cts[c]; steps[s])."""
+        steps = [int(s) for s in steps]
+        if len(outs) != len(cts) * len(steps):
+            raise ValueError("need len(cts)*len(steps) outputs")
+        for t in list(cts) + list(outs):
+            _need(t, 2 * (level + 1) * self.N, "ciphertext")
+        sa = (C.c_int32 * max(1, len(steps)))(*steps)
+        ca = (C.c_void_p * max(1, len(cts)))(*[_dev(c).value for c in cts])
+        oa = (C.c_void_p * max(1, len(outs)))(*[_dev(o).value for o in outs])
+        self._ck(self._lib.he_rotate_batch(self._h, ca, len(cts), level, sa, len(steps), oa, 1 if hoisted else 0))
         return outs
 
     def he_rotate(self, ct, level, step, out):

@@ -1,6 +1,8 @@
 // Channel-aligned convolution CAConv (paper Section 3.1) assembled from Slide_f and
 // MulFilter&Sum_f (Algorithm 1), Rescale (Section 2.1) and rotate-and-sum over C_a
 // (Section 2.2), all enqueued on the context's stream with no host synchronisation.
+#include <algorithm>
+
 #include "modarith.cuh"
 
 #define CV_THREADS 256
@@ -32,14 +34,6 @@ __global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTaps taps, u64*
     }
     acc[o0] = barrett128(a0, m.q, m.mu, m.bits);
     acc[o1] = barrett128(a1, m.q, m.mu, m.bits);
-}
-
-__global__ __launch_bounds__(CV_THREADS) void add_inplace_kernel(u64* __restrict__ a, const u64* __restrict__ b,
-                                                                 const ModConst* mc, uint32_t logN, uint32_t n_limbs) {
-    uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
-    u64 q = mc[blockIdx.y % n_limbs].q;
-    size_t o = ((size_t)blockIdx.y << logN) + n;
-    a[o] = addmod(a[o], b[o], q);
 }
 
 extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64_t* d_ct_in, uint64_t* const* h_d_ct_out) {
@@ -80,56 +74,67 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         if (!plan->h_d_weights[i]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: weight plaintext %u is null", i);
     for (uint32_t o = 0; o < plan->n_out; o++)
         if (!h_d_ct_out[o]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: output %u is null", o);
-    // workspace: [key-switch region at `level`][rescale scratch][taps-1 rotated inputs][acc][rot]
-    const size_t ct_e = (size_t)2 * L1 * N;
-    const size_t ks_e = ks_raised_elems(ctx, level) + ks_scratch_elems(ctx, level);
+    // workspace: [key-switch engine region][rescale scratch][taps-1 rotated inputs][acc][n_out temporaries]
+    const uint32_t lo = level - 1;                       // level after the rescale
+    const uint32_t n_out = plan->n_out, n_ras = (uint32_t)ras_g.size();
+    const size_t ct_e = (size_t)2 * L1 * N, ct_lo_e = (size_t)2 * level * N;
+    const size_t ks_e = std::max(ks_engine_ws_elems(ctx, level, 1, taps - 1), ks_engine_ws_elems(ctx, lo, n_out, n_out));
     const size_t rs_e = rescale_ws_elems(ctx, level);
-    const size_t total = ks_e + rs_e + (size_t)(taps + 1) * ct_e;
+    const size_t total = ks_e + rs_e + (size_t)taps * ct_e + (size_t)n_out * ct_lo_e;
     int32_t rc = he_ensure_ws(ctx, total * sizeof(u64));
     if (rc != HE_OK) return rc;
-    u64* raised = ctx->d_ws;
-    u64* scratch = raised + ks_raised_elems(ctx, level);
     u64* rs_ws = ctx->d_ws + ks_e;
     u64* slid = rs_ws + rs_e;
     u64* acc = slid + (size_t)(taps - 1) * ct_e;
-    u64* rot = acc + ct_e;
+    u64* tmp = acc + ct_e;                               // [n_out] ciphertexts at level lo
     const u64* ct_in = (const u64*)d_ct_in;
 
     // Slide_f: one ModUp of c1 shared by all taps
-    rc = modup_impl(ctx, ct_in + (size_t)L1 * N, level, raised, scratch);
-    if (rc != HE_OK) return rc;
     MacTaps mt;
     mt.n = taps;
-    uint32_t nb = 0;
-    for (uint32_t t = 0; t < taps; t++) {
-        if (tap_g[t] == 1) { mt.ct[t] = ct_in; continue; }
-        u64* out = slid + (size_t)nb++ * ct_e;
-        rc = ks_inner_moddown(ctx, raised, ct_in + (size_t)L1 * N, level, tap_g[t], tap_key[t], ct_in, out, out + (size_t)L1 * N, scratch);
+    {
+        KsSrc src = {ct_in, ct_in + (size_t)L1 * N};
+        std::vector<KsJob> jobs;
+        uint32_t nb = 0;
+        for (uint32_t t = 0; t < taps; t++) {
+            if (tap_g[t] == 1) { mt.ct[t] = ct_in; continue; }
+            u64* out = slid + (size_t)nb++ * ct_e;
+            jobs.push_back({0, tap_g[t], tap_key[t], out, out + (size_t)L1 * N, 0});
+            mt.ct[t] = out;
+        }
+        rc = ks_engine(ctx, level, &src, 1, jobs.data(), (uint32_t)jobs.size());
         if (rc != HE_OK) return rc;
-        mt.ct[t] = out;
     }
-    const uint32_t lo = level - 1; // level after the rescale
-    u64* raised_lo = ctx->d_ws;
-    u64* scratch_lo = raised_lo + ks_raised_elems(ctx, lo);
-    for (uint32_t o = 0; o < plan->n_out; o++) {
+    // MulFilter&Sum_f and Rescale per output.  The rotate-and-sum steps ping-pong between the
+    // caller's output buffers and the temporaries; start so that the last step lands in the output.
+    std::vector<u64*> cur(n_out), nxt(n_out);
+    for (uint32_t o = 0; o < n_out; o++) {
+        u64* a = (u64*)h_d_ct_out[o];
+        u64* b = tmp + (size_t)o * ct_lo_e;
+        cur[o] = (n_ras & 1u) ? b : a;
+        nxt[o] = (n_ras & 1u) ? a : b;
+    }
+    for (uint32_t o = 0; o < n_out; o++) {
         for (uint32_t t = 0; t < taps; t++) mt.pt[t] = (const u64*)plan->h_d_weights[(size_t)o * taps + t];
         dim3 grid(N / CV_THREADS, L1), block(CV_THREADS);
         hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc, ctx->d_mc, ctx->logN, L1);
         HE_HIP(ctx, hipGetLastError());
         ctx->cnt.mac += taps;
-        u64* out = (u64*)h_d_ct_out[o];
-        rc = rescale_impl(ctx, acc, level, out, rs_ws);
+        rc = rescale_impl(ctx, acc, level, cur[o], rs_ws);
         if (rc != HE_OK) return rc;
-        // rotate-and-sum over the outermost channel dimension
-        for (size_t s = 0; s < ras_g.size(); s++) {
-            rc = modup_impl(ctx, out + (size_t)level * N, lo, raised_lo, scratch_lo);
-            if (rc != HE_OK) return rc;
-            rc = ks_inner_moddown(ctx, raised_lo, out + (size_t)level * N, lo, ras_g[s], ras_key[s], out, rot, rot + (size_t)level * N, scratch_lo);
-            if (rc != HE_OK) return rc;
-            dim3 g2(N / CV_THREADS, 2 * level);
-            hipLaunchKernelGGL(add_inplace_kernel, g2, block, 0, ctx->stream, out, rot, ctx->d_mc, ctx->logN, level);
-            HE_HIP(ctx, hipGetLastError());
+    }
+    // rotate-and-sum over the outermost channel dimension: every step is one batch over all
+    // outputs (same key), the addition ct + Rot(ct) is done by the ModDown epilogue
+    for (uint32_t s = 0; s < n_ras; s++) {
+        std::vector<KsSrc> srcs(n_out);
+        std::vector<KsJob> jobs(n_out);
+        for (uint32_t o = 0; o < n_out; o++) {
+            srcs[o] = {cur[o], cur[o] + (size_t)level * N};
+            jobs[o] = {o, ras_g[s], ras_key[s], nxt[o], nxt[o] + (size_t)level * N, 1};
         }
+        rc = ks_engine(ctx, lo, srcs.data(), n_out, jobs.data(), n_out);
+        if (rc != HE_OK) return rc;
+        std::swap(cur, nxt);
     }
     return HE_OK;
 }

@@ -174,7 +174,7 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
     }
     // workspace for one key switch at the top level (raised digits + accumulators + temporaries)
     if (np > 0) {
-        size_t elems = ks_raised_elems(c, nq - 1) + ks_scratch_elems(c, nq - 1);
+        size_t elems = ks_engine_ws_elems(c, nq - 1, 1, 1);
         int32_t rc = he_ensure_ws(c, elems * sizeof(u64));
         if (rc != HE_OK) {
             g_create_err = c->err;

@@ -90,39 +90,69 @@ uint32_t h_galois_of_step(const he_ctx* ctx, int32_t step);
     } while (0)
 
 // ---- internal device-work launchers (all enqueue on ctx->stream, none synchronises)
-// Transforms of n limbs (n <= HE_MAX_LAUNCH_LIMBS) whose modulus indices are mod_idx[0..n).
-// scale == nullptr: inverse multiplies by N^-1; else limb i is multiplied by scale->s[i]
-// (which must already include N^-1).
+#define HE_MAX_SEGS 16      // distinct source allocations one transform launch can read from
+#define HE_MAX_KS_JOBS 16   // key-switch jobs whose ModDown runs in one set of launches
+
+// Epilogue of ModDown fused into the last pass of the forward transform of the converted p-part
+// (separate kernel on the generic path).  The launch covers J jobs x 2 components x L1 limbs:
+// limb i -> job i/(2*L1), component (i/L1)&1, limb r = i%L1;
+//   out_c[r] = (acc_c[r] - ntt) * P^-1  (+ c0[r] gathered by the Galois map of g for component 0)
+//              (+ the job's own c0[r] / c1[r], ungathered, when add_self: out = ct + Rot(ct)).
+struct ModDownEpilogue {
+    const u64* acc;      // [J][2][R][N]
+    const u64* pinv;     // [nq]
+    const u64* pinv_sh;
+    uint32_t R, L1;
+    const u64* c0[HE_MAX_KS_JOBS];   // [L1][N] or nullptr (plain key switch)
+    const u64* c1[HE_MAX_KS_JOBS];   // [L1][N], read only when add_self
+    u64* out0[HE_MAX_KS_JOBS];
+    u64* out1[HE_MAX_KS_JOBS];
+    uint32_t g[HE_MAX_KS_JOBS];
+    uint8_t add_self[HE_MAX_KS_JOBS];
+};
+
+// One batched transform launch (both passes).  Limb i is read at seg[src_seg[i]] + src_limb[i]*N
+// by the first pass and lives at dst + i*N afterwards; mod_idx[i] == 0xFF leaves limb i alone.
+struct TransformDesc {
+    bool fwd;
+    const u64* seg[HE_MAX_SEGS];
+    uint32_t n_seg;
+    u64* dst;
+    uint32_t n;                  // <= HE_MAX_LAUNCH_LIMBS
+    const uint32_t* mod_idx;     // [n]
+    const uint8_t* src_seg;      // [n] or nullptr (all segment 0)
+    const uint16_t* src_limb;    // [n] (< 4096) or nullptr (identity)
+    const ScaleList* scale;      // inverse only: limb i is multiplied by scale[i % scale_period]
+    uint32_t scale_period;       //   (must include N^-1); nullptr = plain N^-1
+    const ModDownEpilogue* ep;   // forward only, or nullptr
+};
+int32_t launch_transform(he_ctx* ctx, const TransformDesc& d);
+int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d);   // N = 2^16 fast path
+int32_t launch_moddown_final(he_ctx* ctx, const u64* conv, uint32_t n_jobs, const ModDownEpilogue& ep);
+
+// in-place conveniences
 int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n);
 int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale);
-int32_t launch_ntt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n);
-int32_t launch_intt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n,
-                         const ScaleList* scale);
-int32_t launch_transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
-                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale);
 int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g);
 int32_t launch_automorph_coef(he_ctx* ctx, const u64* in, u64* out, const uint32_t* mod_idx, uint32_t n, uint32_t g);
 
-// key switching internals (keyswitch.hip)
+// key switching engine (keyswitch.hip)
 int32_t ks_init_tables(he_ctx* ctx);
 void ks_free_tables(he_ctx* ctx);
-int32_t ks_inner_moddown(he_ctx* ctx, const u64* d_raised, const u64* d_own, uint32_t level, uint32_t g_perm,
-                         const u64* d_evk, const u64* d_c0, u64* d_out0, u64* d_out1, u64* d_scratch);
-// Epilogue of ModDown fused into the last pass of the forward transform of the converted p-part:
-// limb i of the launch is component i / L1, limb r = i % L1; out_c[r] = (acc_c[r] - ntt) * P^-1
-// (+ c0[r] gathered by the Galois map of g for component 0).
-struct ModDownEpilogue {
-    const u64* acc;     // [2][R][N]
-    const u64* c0;      // [L1][N] or nullptr
-    u64* out0;
-    u64* out1;
-    const u64* pinv;    // [nq]
-    const u64* pinv_sh;
-    uint32_t R, L1, g;
+struct KsSrc {
+    const u64* c0;   // [level+1][N] or nullptr (plain key switch: nothing is added to out0)
+    const u64* c1;   // [level+1][N]: the polynomial that is raised and switched
 };
-int32_t launch_ntt16_moddown(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ModDownEpilogue& ep);
-int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, u64* d_tmp);
+struct KsJob {
+    uint32_t src;        // index into the sources
+    uint32_t g;          // Galois element applied to the raised digits and to c0 (1 = none)
+    const u64* evk;      // key used
+    u64* out0;           // [level+1][N]
+    u64* out1;
+    uint32_t add_self;   // out += the source ciphertext itself (rotate-and-sum step)
+};
+// Runs every job: one ModUp per source, then inner product + ModDown per job, batched.
+int32_t ks_engine(he_ctx* ctx, uint32_t level, const KsSrc* srcs, uint32_t n_src, const KsJob* jobs, uint32_t n_jobs);
+size_t ks_engine_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_src, uint32_t n_jobs);
 size_t rescale_ws_elems(const he_ctx* c, uint32_t level);
 int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u64* ws);
-size_t ks_raised_elems(const he_ctx* ctx, uint32_t level);
-size_t ks_scratch_elems(const he_ctx* ctx, uint32_t level);

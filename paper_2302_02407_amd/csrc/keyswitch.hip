@@ -1,5 +1,5 @@
 // Hybrid key switching with dnum digits (the inner step of CRot; paper Section 2.1 for CRot,
-// Appendix for evaluation keys and dnum), hoisted rotations, and rescale.
+// Appendix for evaluation keys and dnum), batched rotations, and rescale.
 //
 //   ModUp   : digit limbs -> coefficient form (iNTT with the factor (Q_j/q_i)^-1 folded into
 //             the N^-1 scaling) -> fast basis conversion to every other limb of
@@ -9,6 +9,13 @@
 //             q_0..q_l -> NTT -> (acc - conv) * P^-1 (+ sigma_g(c0) for a rotation).
 // Neither conversion corrects the overflow multiple; each term is a canonical residue and
 // the sum is reduced exactly, so results are defined bit for bit.
+//
+// The engine takes a list of sources (ciphertexts to raise) and a list of jobs (source, Galois
+// element, key, output).  Sources are raised several at a time and the jobs' ModDown chains
+// run HE_MAX_KS_JOBS at a time, so that every launch covers hundreds of limbs even when one
+// ciphertext has only 24; jobs that use the same key share one pass over the key.
+#include <algorithm>
+
 #include "modarith.cuh"
 
 #define KS_THREADS 256
@@ -29,20 +36,26 @@ struct ConvJob {
     uint8_t tgt_limb[HE_MAX_MODULI];
     uint8_t tgt_mod[HE_MAX_MODULI];
 };
+// njobs descriptors, each applied `reps` times with src/dst advanced by a fixed stride per repeat.
 struct ConvBatch {
     ConvJob job[CONV_MAX_JOBS];
+    uint32_t njobs, reps;
+    size_t src_stride, dst_stride;   // elements per repeat
 };
 
-// Fast basis conversion.  grid: (N/512, ceil(nt_max/CONV_TGT_PER_BLOCK), jobs); each thread owns two
-// adjacent coefficients (16-byte loads and stores).  The block's conversion constants and target
-// moduli are staged in LDS once and then read as broadcasts.  With at most 8 source limbs
-// (ONE_CHUNK) the pre-scaled sources stay in registers across all targets of the block.
+// Fast basis conversion.  grid: (N/512, ceil(nt_max/CONV_TGT_PER_BLOCK), njobs*reps); each thread
+// owns two adjacent coefficients (16-byte loads and stores).  The block's conversion constants
+// and target moduli are staged in LDS once and then read as broadcasts.  With at most 8 source
+// limbs (ONE_CHUNK) the pre-scaled sources stay in registers across all targets of the block.
 template <bool ONE_CHUNK>
 __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const ModConst* mc, uint32_t logN) {
     __shared__ u64 s_hat[CONV_TGT_PER_BLOCK * 64];
     __shared__ u64 s_q[CONV_TGT_PER_BLOCK], s_mu[CONV_TGT_PER_BLOCK];
     __shared__ uint32_t s_bits[CONV_TGT_PER_BLOCK];
-    const ConvJob& job = b.job[blockIdx.z];
+    const uint32_t ji = blockIdx.z % b.njobs, rep = blockIdx.z / b.njobs;
+    const ConvJob& job = b.job[ji];
+    const u64* src = job.src + rep * b.src_stride;
+    u64* dst = job.dst + rep * b.dst_stride;
     const uint32_t t0 = blockIdx.y * CONV_TGT_PER_BLOCK;
     if (t0 >= job.nt) return;
     const uint32_t nt = min((uint32_t)CONV_TGT_PER_BLOCK, job.nt - t0);
@@ -62,7 +75,7 @@ __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const
     if (ONE_CHUNK) {
 #pragma unroll
         for (uint32_t i = 0; i < 8; i++)
-            y[i] = i < ns ? *reinterpret_cast<const ulonglong2*>(job.src + ((size_t)i << logN) + n) : make_ulonglong2(0, 0);
+            y[i] = i < ns ? *reinterpret_cast<const ulonglong2*>(src + ((size_t)i << logN) + n) : make_ulonglong2(0, 0);
     }
     for (uint32_t tt = 0; tt < nt; tt++) {
         const u64 q = s_q[tt], mu = s_mu[tt];
@@ -79,59 +92,118 @@ __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const
             for (uint32_t i0 = 0; i0 < ns; i0 += 8) {
                 if (i0) { a0 = barrett128(a0, q, mu, bits); a1 = barrett128(a1, q, mu, bits); }
                 for (uint32_t i = i0; i < min(i0 + 8, ns); i++) {
-                    ulonglong2 v = *reinterpret_cast<const ulonglong2*>(job.src + ((size_t)i << logN) + n);
+                    ulonglong2 v = *reinterpret_cast<const ulonglong2*>(src + ((size_t)i << logN) + n);
                     a0 += (u128)v.x * h[i];
                     a1 += (u128)v.y * h[i];
                 }
             }
         }
         ulonglong2 o = make_ulonglong2(barrett128(a0, q, mu, bits), barrett128(a1, q, mu, bits));
-        *reinterpret_cast<ulonglong2*>(job.dst + ((size_t)job.tgt_limb[t0 + tt] << logN) + n) = o;
+        *reinterpret_cast<ulonglong2*>(dst + ((size_t)job.tgt_limb[t0 + tt] << logN) + n) = o;
     }
 }
 
-// grid: (N/256, R).  raised [beta][R][N]; evk [dnum][2][M][N]; acc [2][R][N].  A digit's own limbs
-// (limb r of digit r/alpha) are never materialised in `raised`: they are read from the input
-// polynomial `own` [level+1][N], which is what ModUp would have copied.
-__global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(const u64* __restrict__ raised, const u64* __restrict__ own,
-                                                                   const u64* __restrict__ evk, u64* __restrict__ acc,
-                                                                   const ModConst* mc, uint32_t logN, uint32_t R, uint32_t beta,
-                                                                   uint32_t M, uint32_t level, uint32_t nq, uint32_t alpha,
-                                                                   uint32_t g) {
+// Jobs of one launch grouped by key: group z holds jobs [start[z], start[z]+count[z]) which all use
+// evk[z] and Galois element g[z].
+struct IpBatch {
+    const u64* evk[HE_MAX_KS_JOBS];
+    uint32_t g[HE_MAX_KS_JOBS];
+    uint32_t start[HE_MAX_KS_JOBS];
+    uint32_t count[HE_MAX_KS_JOBS];
+    const u64* raised[HE_MAX_KS_JOBS];   // per job: [beta][R][N] (own limbs not materialised)
+    const u64* own[HE_MAX_KS_JOBS];      // per job: the switched polynomial [level+1][N]
+};
+
+// grid: (N/256, R, groups).  acc [job][2][R][N].  A block loads the key values of its limb once
+// and reuses them for every job of the group.  A digit's own limbs (limb r of digit r/alpha) are
+// never materialised in `raised`: they are read from the job's input polynomial.
+template <int BETA_MAX>
+__global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(IpBatch ib, u64* __restrict__ acc, const ModConst* mc,
+                                                                   uint32_t logN, uint32_t R, uint32_t beta, uint32_t M,
+                                                                   uint32_t level, uint32_t nq, uint32_t alpha) {
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
-    const uint32_t r = blockIdx.y;
+    const uint32_t r = blockIdx.y, z = blockIdx.z;
     const uint32_t mi = r <= level ? r : nq + (r - level - 1);
     const ModConst m = mc[mi];
+    const uint32_t g = ib.g[z];
     const uint32_t src = g == 1 ? n : galois_src_ks(n, g, logN);
-    u128 a0 = 0, a1 = 0;
-    for (uint32_t j = 0; j < beta; j++) {
-        if (j && (j & 7) == 0) {
-            a0 = barrett128(a0, m.q, m.mu, m.bits);
-            a1 = barrett128(a1, m.q, m.mu, m.bits);
-        }
-        const u64* dj = (r <= level && r / alpha == j) ? own + ((size_t)r << logN) : raised + ((size_t)(j * R + r) << logN);
-        u64 d = dj[src];
-        a0 += (u128)d * evk[((size_t)((j * 2 + 0) * M + mi) << logN) + n];
-        a1 += (u128)d * evk[((size_t)((j * 2 + 1) * M + mi) << logN) + n];
+    const u64* evk = ib.evk[z];
+    u64 kb[BETA_MAX], ka[BETA_MAX];
+#pragma unroll
+    for (uint32_t j = 0; j < BETA_MAX; j++) {
+        kb[j] = j < beta ? evk[((size_t)((j * 2 + 0) * M + mi) << logN) + n] : 0;
+        ka[j] = j < beta ? evk[((size_t)((j * 2 + 1) * M + mi) << logN) + n] : 0;
     }
-    acc[((size_t)r << logN) + n] = barrett128(a0, m.q, m.mu, m.bits);
-    acc[((size_t)(R + r) << logN) + n] = barrett128(a1, m.q, m.mu, m.bits);
+    for (uint32_t jb = ib.start[z]; jb < ib.start[z] + ib.count[z]; jb++) {
+        const u64* raised = ib.raised[jb];
+        const u64* own = ib.own[jb];
+        u128 a0 = 0, a1 = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < BETA_MAX; j++) {
+            if (j < beta) {
+                const u64* dj = (r <= level && r / alpha == j) ? own + ((size_t)r << logN) : raised + ((size_t)(j * R + r) << logN);
+                u64 d = dj[src];
+                a0 += (u128)d * kb[j];
+                a1 += (u128)d * ka[j];
+            }
+        }
+        u64* out = acc + ((size_t)jb * 2 * R << logN);
+        out[((size_t)r << logN) + n] = barrett128(a0, m.q, m.mu, m.bits);
+        out[((size_t)(R + r) << logN) + n] = barrett128(a1, m.q, m.mu, m.bits);
+    }
 }
 
-// grid: (N/256, level+1, 2).  out_c[r] = (acc_c[r] - conv_c[r]) * P^-1 (+ sigma_g(c0)[r] for c = 0).
-__global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __restrict__ acc, const u64* __restrict__ conv,
-                                                                   const u64* __restrict__ c0, u64* __restrict__ out0,
-                                                                   u64* __restrict__ out1, const ModConst* mc,
-                                                                   const u64* pinv, const u64* pinv_sh, uint32_t logN,
-                                                                   uint32_t R, uint32_t L1, uint32_t g) {
+// Any number of digits (reduces every 8 terms); no key reuse in registers.
+__global__ __launch_bounds__(KS_THREADS) void inner_product_wide_kernel(IpBatch ib, u64* __restrict__ acc, const ModConst* mc,
+                                                                        uint32_t logN, uint32_t R, uint32_t beta, uint32_t M,
+                                                                        uint32_t level, uint32_t nq, uint32_t alpha) {
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
-    const uint32_t r = blockIdx.y, comp = blockIdx.z;
+    const uint32_t r = blockIdx.y, z = blockIdx.z;
+    const uint32_t mi = r <= level ? r : nq + (r - level - 1);
+    const ModConst m = mc[mi];
+    const uint32_t g = ib.g[z];
+    const uint32_t src = g == 1 ? n : galois_src_ks(n, g, logN);
+    const u64* evk = ib.evk[z];
+    for (uint32_t jb = ib.start[z]; jb < ib.start[z] + ib.count[z]; jb++) {
+        const u64* raised = ib.raised[jb];
+        const u64* own = ib.own[jb];
+        u128 a0 = 0, a1 = 0;
+        for (uint32_t j = 0; j < beta; j++) {
+            if (j && (j & 7) == 0) {
+                a0 = barrett128(a0, m.q, m.mu, m.bits);
+                a1 = barrett128(a1, m.q, m.mu, m.bits);
+            }
+            const u64* dj = (r <= level && r / alpha == j) ? own + ((size_t)r << logN) : raised + ((size_t)(j * R + r) << logN);
+            u64 d = dj[src];
+            a0 += (u128)d * evk[((size_t)((j * 2 + 0) * M + mi) << logN) + n];
+            a1 += (u128)d * evk[((size_t)((j * 2 + 1) * M + mi) << logN) + n];
+        }
+        u64* out = acc + ((size_t)jb * 2 * R << logN);
+        out[((size_t)r << logN) + n] = barrett128(a0, m.q, m.mu, m.bits);
+        out[((size_t)(R + r) << logN) + n] = barrett128(a1, m.q, m.mu, m.bits);
+    }
+}
+
+// Generic-ring ModDown epilogue.  grid: (N/256, L1, 2*jobs).  conv [job][2][L1][N].
+__global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __restrict__ conv, ModDownEpilogue ep,
+                                                                   const ModConst* mc, uint32_t logN) {
+    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
+    const uint32_t r = blockIdx.y, pc = blockIdx.z, job = pc >> 1, comp = pc & 1u;
     const u64 q = mc[r].q;
-    u64 a = acc[((size_t)(comp * R + r) << logN) + n];
-    u64 c = conv[((size_t)(comp * L1 + r) << logN) + n];
-    u64 v = shoup_mul(submod(a, c, q), pinv[r], pinv_sh[r], q);
-    if (comp == 0 && c0) v = addmod(v, c0[((size_t)r << logN) + (g == 1 ? n : galois_src_ks(n, g, logN))], q);
-    (comp ? out1 : out0)[((size_t)r << logN) + n] = v;
+    u64 a = ep.acc[((size_t)(pc * ep.R + r) << logN) + n];
+    u64 c = conv[((size_t)(pc * ep.L1 + r) << logN) + n];
+    u64 v = shoup_mul(submod(a, c, q), ep.pinv[r], ep.pinv_sh[r], q);
+    const uint32_t g = ep.g[job];
+    if (comp == 0 && ep.c0[job]) v = addmod(v, ep.c0[job][((size_t)r << logN) + (g == 1 ? n : galois_src_ks(n, g, logN))], q);
+    if (ep.add_self[job]) v = addmod(v, (comp ? ep.c1[job] : ep.c0[job])[((size_t)r << logN) + n], q);
+    (comp ? ep.out1[job] : ep.out0[job])[((size_t)r << logN) + n] = v;
+}
+
+int32_t launch_moddown_final(he_ctx* c, const u64* conv, uint32_t n_jobs, const ModDownEpilogue& ep) {
+    dim3 grid(c->N / KS_THREADS, ep.L1, 2 * n_jobs), block(KS_THREADS);
+    hipLaunchKernelGGL(moddown_final_kernel, grid, block, 0, c->stream, conv, ep, c->d_mc, c->logN);
+    HE_HIP(c, hipGetLastError());
+    return HE_OK;
 }
 
 // ---------------------------------------------------------------- rescale kernels
@@ -166,15 +238,6 @@ __global__ __launch_bounds__(KS_THREADS) void rescale_final_kernel(const u64* __
 
 static uint32_t num_digits(const he_ctx* c, uint32_t level) { return (level + c->alpha) / c->alpha; }
 static uint32_t pad8(uint32_t x) { return (x + 7u) & ~7u; }
-
-size_t ks_raised_elems(const he_ctx* c, uint32_t level) {
-    return (size_t)num_digits(c, level) * (level + 1 + c->np) * c->N;
-}
-// tmp_up[level+1] + acc[2][R] + tmp_dn[2][k] + conv[2][level+1]
-size_t ks_scratch_elems(const he_ctx* c, uint32_t level) {
-    size_t L1 = level + 1, R = L1 + c->np;
-    return (L1 + 2 * R + 2 * c->np + 2 * L1) * c->N;
-}
 
 int32_t ks_init_tables(he_ctx* c) {
     const uint32_t nq = c->nq, np = c->np, M = c->M, al = c->alpha, dn = c->dnum;
@@ -254,44 +317,78 @@ void ks_free_tables(he_ctx* c) {
     if (c->d_qlinv_sh) (void)hipFree(c->d_qlinv_sh);
 }
 
-// ---------------------------------------------------------------- host: ModUp / ModDown
+// ---------------------------------------------------------------- host: the engine
 
-static int32_t launch_baseconv(he_ctx* c, const ConvBatch& b, uint32_t jobs, uint32_t nt_max, uint32_t ns_max) {
-    dim3 grid((c->N + 2 * KS_THREADS - 1) / (2 * KS_THREADS), (nt_max + CONV_TGT_PER_BLOCK - 1) / CONV_TGT_PER_BLOCK, jobs), block(KS_THREADS);
+static int32_t launch_baseconv(he_ctx* c, const ConvBatch& b, uint32_t nt_max, uint32_t ns_max) {
+    dim3 grid((c->N + 2 * KS_THREADS - 1) / (2 * KS_THREADS), (nt_max + CONV_TGT_PER_BLOCK - 1) / CONV_TGT_PER_BLOCK,
+              b.njobs * b.reps), block(KS_THREADS);
     if (ns_max <= 8) hipLaunchKernelGGL(baseconv_kernel<true>, grid, block, 0, c->stream, b, c->d_mc, c->logN);
     else hipLaunchKernelGGL(baseconv_kernel<false>, grid, block, 0, c->stream, b, c->d_mc, c->logN);
     HE_HIP(c, hipGetLastError());
     return HE_OK;
 }
 
-// d_poly [level+1][N] NTT form -> d_raised [beta][R][N] NTT form, EXCEPT each digit's own limbs,
-// which are left unwritten (the inner product reads them from d_poly).  d_tmp: level+1 limbs.
-int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, u64* d_tmp) {
+// How many sources are raised at once and how many jobs share one ModDown launch set.
+static void engine_shape(const he_ctx* c, uint32_t level, uint32_t n_src, uint32_t n_jobs, uint32_t& cb, uint32_t& jb) {
+    const uint32_t L1 = level + 1, k = c->np;
+    cb = std::min<uint32_t>(std::min<uint32_t>(n_src, HE_MAX_SEGS), std::max<uint32_t>(1, HE_MAX_LAUNCH_LIMBS / L1));
+    cb = std::min<uint32_t>(cb, 8);
+    jb = std::min<uint32_t>(n_jobs, HE_MAX_KS_JOBS);
+    jb = std::min<uint32_t>(jb, std::max<uint32_t>(1, HE_MAX_LAUNCH_LIMBS / (2 * L1)));
+    jb = std::min<uint32_t>(jb, std::max<uint32_t>(1, HE_MAX_LAUNCH_LIMBS / (2 * k)));
+    jb = std::min<uint32_t>(jb, std::max<uint32_t>(1, 4096 / (2 * (L1 + k))));   // source limb offsets are 12 bits
+    if (cb == 0) cb = 1;
+    if (jb == 0) jb = 1;
+}
+
+// raised[cb][beta][R] + tmp_up[cb][L1] + acc[jb][2][R] + tmp_dn[jb][2][k] + conv[jb][2][L1]
+size_t ks_engine_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_src, uint32_t n_jobs) {
+    uint32_t cb, jb;
+    engine_shape(c, level, n_src, n_jobs, cb, jb);
+    const size_t L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
+    return ((size_t)cb * (beta * R + L1) + (size_t)jb * (2 * R + 2 * k + 2 * L1)) * c->N;
+}
+
+// ModUp of `cb` sources at once.  raised [cb][beta][R][N] (own limbs left unwritten), tmp [cb][L1][N].
+static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t level, u64* raised, u64* tmp) {
     const uint32_t N = c->N, L1 = level + 1, R = L1 + c->np, beta = num_digits(c, level), al = c->alpha;
     // coefficient form of all limbs, each pre-multiplied by N^-1 * (Q_j/q_i)^-1
     ScaleList sc;
-    uint32_t idx[HE_MAX_MODULI];
-    uint16_t from[HE_MAX_MODULI];
     for (uint32_t i = 0; i < L1; i++) {
         uint32_t j = i / al, lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1, sz = hi - lo;
         u64 qi = c->mod[i];
         u64 s = h_mulmod(c->h_mc[i].ninv, c->h_up_invhat[(size_t)(j * al + (sz - 1)) * al + (i - lo)], qi);
         sc.s[i] = s;
         sc.s_sh[i] = h_shoup(s, qi);
-        idx[i] = i;
-        from[i] = (uint16_t)i;
     }
-    int32_t rc = launch_intt_from(c, d_poly, from, d_tmp, idx, L1, &sc);
-    if (rc != HE_OK) return rc;
+    {
+        std::vector<uint32_t> mods(cb * L1);
+        std::vector<uint8_t> seg(cb * L1);
+        std::vector<uint16_t> lim(cb * L1);
+        TransformDesc t = {};
+        t.fwd = false; t.n_seg = cb; t.dst = tmp; t.n = cb * L1;
+        for (uint32_t s = 0; s < cb; s++) {
+            t.seg[s] = srcs[s].c1;
+            for (uint32_t i = 0; i < L1; i++) { mods[s * L1 + i] = i; seg[s * L1 + i] = (uint8_t)s; lim[s * L1 + i] = (uint16_t)i; }
+        }
+        t.mod_idx = mods.data(); t.src_seg = seg.data(); t.src_limb = lim.data();
+        t.scale = &sc; t.scale_period = L1;
+        int32_t rc = launch_transform(c, t);
+        if (rc != HE_OK) return rc;
+    }
     const uint32_t aw = pad8(al);
     for (uint32_t j0 = 0; j0 < beta; j0 += CONV_MAX_JOBS) {
         ConvBatch b;
-        uint32_t jobs = beta - j0 < CONV_MAX_JOBS ? beta - j0 : CONV_MAX_JOBS, nt_max = 0, ns_max = 0;
-        for (uint32_t jj = 0; jj < jobs; jj++) {
+        b.njobs = beta - j0 < CONV_MAX_JOBS ? beta - j0 : CONV_MAX_JOBS;
+        b.reps = cb;
+        b.src_stride = (size_t)L1 * N;
+        b.dst_stride = (size_t)beta * R * N;
+        uint32_t nt_max = 0, ns_max = 0;
+        for (uint32_t jj = 0; jj < b.njobs; jj++) {
             uint32_t j = j0 + jj, lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1, sz = hi - lo;
             ConvJob& job = b.job[jj];
-            job.src = d_tmp + (size_t)lo * N;
-            job.dst = d_raised + (size_t)j * R * N;
+            job.src = tmp + (size_t)lo * N;
+            job.dst = raised + (size_t)j * R * N;
             job.hat = c->d_up_hat + (size_t)(j * al + (sz - 1)) * c->M * aw;
             job.hat_w = aw;
             job.ns = sz;
@@ -305,102 +402,172 @@ int32_t modup_impl(he_ctx* c, const u64* d_poly, uint32_t level, u64* d_raised, 
             if (job.nt > nt_max) nt_max = job.nt;
             if (sz > ns_max) ns_max = sz;
         }
-        rc = launch_baseconv(c, b, jobs, nt_max, ns_max);
+        int32_t rc = launch_baseconv(c, b, nt_max, ns_max);
         if (rc != HE_OK) return rc;
     }
     // NTT of every converted limb; own limbs are marked "skip"
-    uint32_t total = beta * R;
-    std::vector<uint32_t> mods(total);
+    const uint32_t per_src = beta * R;
+    std::vector<uint32_t> mods(per_src);
     for (uint32_t j = 0; j < beta; j++) {
         uint32_t lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1;
         for (uint32_t r = 0; r < R; r++)
             mods[j * R + r] = (r >= lo && r < hi) ? 0xFFu : (r <= level ? r : c->nq + (r - level - 1));
     }
-    for (uint32_t o = 0; o < total; o += HE_MAX_LAUNCH_LIMBS) {
-        uint32_t n = total - o < HE_MAX_LAUNCH_LIMBS ? total - o : HE_MAX_LAUNCH_LIMBS;
-        rc = launch_ntt(c, d_raised + (size_t)o * N, mods.data() + o, n);
-        if (rc != HE_OK) return rc;
+    if (per_src <= HE_MAX_LAUNCH_LIMBS) {
+        const uint32_t per_launch = HE_MAX_LAUNCH_LIMBS / per_src;   // sources per launch
+        std::vector<uint32_t> rep;
+        for (uint32_t s0 = 0; s0 < cb; s0 += per_launch) {
+            uint32_t ns = std::min(per_launch, cb - s0);
+            rep.resize((size_t)ns * per_src);
+            for (uint32_t s = 0; s < ns; s++) std::copy(mods.begin(), mods.end(), rep.begin() + (size_t)s * per_src);
+            int32_t rc = launch_ntt(c, raised + (size_t)s0 * per_src * N, rep.data(), ns * per_src);
+            if (rc != HE_OK) return rc;
+        }
+    } else {
+        for (uint32_t s = 0; s < cb; s++)
+            for (uint32_t o = 0; o < per_src; o += HE_MAX_LAUNCH_LIMBS) {
+                uint32_t n = std::min<uint32_t>(HE_MAX_LAUNCH_LIMBS, per_src - o);
+                int32_t rc = launch_ntt(c, raised + ((size_t)s * per_src + o) * N, mods.data() + o, n);
+                if (rc != HE_OK) return rc;
+            }
     }
-    c->cnt.modup += 1;
+    c->cnt.modup += cb;
     return HE_OK;
 }
 
-// raised [beta][R][N] (own limbs taken from d_own [level+1][N]) -> (out0, out1) [level+1][N].
-// g_perm: Galois element applied to the raised digits (and to c0 if given) as a gather; 1 = none.
-// d_scratch: ks_scratch_elems.
-int32_t ks_inner_moddown(he_ctx* c, const u64* d_raised, const u64* d_own, uint32_t level, uint32_t g_perm, const u64* d_evk,
-                         const u64* d_c0, u64* d_out0, u64* d_out1, u64* d_scratch) {
+// Inner product + ModDown of up to HE_MAX_KS_JOBS jobs whose sources are already raised.
+// raised_of[i] / srcs give job i's raised digits and source; scratch: acc, tmp_dn, conv.
+static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs, const KsJob* jobs, const u64* const* raised_of,
+                                   uint32_t J, u64* acc, u64* tmp_dn, u64* conv) {
     const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
-    u64* acc = d_scratch + (size_t)L1 * N;       // after tmp_up
-    u64* tmp_dn = acc + (size_t)2 * R * N;       // [2][k][N]
-    u64* conv = tmp_dn + (size_t)2 * k * N;      // [2][L1][N]
+    // group consecutive jobs that use the same key and Galois element (the caller sorts them)
+    IpBatch ib;
+    uint32_t groups = 0;
+    for (uint32_t i = 0; i < J; i++) {
+        ib.raised[i] = raised_of[i];
+        ib.own[i] = srcs[jobs[i].src].c1;
+        if (groups && ib.evk[groups - 1] == jobs[i].evk && ib.g[groups - 1] == jobs[i].g) {
+            ib.count[groups - 1]++;
+        } else {
+            ib.evk[groups] = jobs[i].evk; ib.g[groups] = jobs[i].g; ib.start[groups] = i; ib.count[groups] = 1;
+            groups++;
+        }
+    }
     {
-        dim3 grid(N / KS_THREADS, R), block(KS_THREADS);
-        hipLaunchKernelGGL(inner_product_kernel, grid, block, 0, c->stream, d_raised, d_own, d_evk, acc, c->d_mc, c->logN, R,
-                           beta, c->M, level, c->nq, c->alpha, g_perm);
+        dim3 grid(N / KS_THREADS, R, groups), block(KS_THREADS);
+        if (beta <= 4)
+            hipLaunchKernelGGL(inner_product_kernel<4>, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M, level,
+                               c->nq, c->alpha);
+        else if (beta <= 8)
+            hipLaunchKernelGGL(inner_product_kernel<8>, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M, level,
+                               c->nq, c->alpha);
+        else
+            hipLaunchKernelGGL(inner_product_wide_kernel, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M,
+                               level, c->nq, c->alpha);
         HE_HIP(c, hipGetLastError());
     }
-    // p-limbs of both accumulators -> coefficient form, pre-multiplied by N^-1 * (P/p_t)^-1
-    if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
+    // p-limbs of all accumulators -> coefficient form, pre-multiplied by N^-1 * (P/p_t)^-1
     ScaleList sc;
-    uint32_t idx[HE_MAX_MODULI];
-    uint16_t from[HE_MAX_MODULI];
-    for (uint32_t i = 0; i < 2 * k; i++) {
-        uint32_t t = i % k;
-        from[i] = (uint16_t)((i / k) * R + L1 + t);
+    for (uint32_t t = 0; t < k; t++) {
         u64 p = c->mod[c->nq + t];
         u64 s = h_mulmod(c->h_mc[c->nq + t].ninv, c->h_dn_invhat[t], p);
-        sc.s[i] = s;
-        sc.s_sh[i] = h_shoup(s, p);
-        idx[i] = c->nq + t;
+        sc.s[t] = s;
+        sc.s_sh[t] = h_shoup(s, p);
     }
-    int32_t rc = launch_intt_from(c, acc, from, tmp_dn, idx, 2 * k, &sc);
-    if (rc != HE_OK) return rc;
-    ConvBatch b;
-    for (uint32_t comp = 0; comp < 2; comp++) {
-        ConvJob& job = b.job[comp];
-        job.src = tmp_dn + (size_t)comp * k * N;
-        job.dst = conv + (size_t)comp * L1 * N;
-        job.hat = c->d_dn_hat;
-        job.hat_w = pad8(k);
-        job.ns = k;
-        job.nt = L1;
+    {
+        const uint32_t n = J * 2 * k;
+        std::vector<uint32_t> mods(n);
+        std::vector<uint16_t> lim(n);
+        for (uint32_t i = 0; i < n; i++) {
+            uint32_t t = i % k, pc = i / k;
+            mods[i] = c->nq + t;
+            lim[i] = (uint16_t)(pc * R + L1 + t);
+        }
+        TransformDesc t = {};
+        t.fwd = false; t.seg[0] = acc; t.n_seg = 1; t.dst = tmp_dn; t.n = n;
+        t.mod_idx = mods.data(); t.src_limb = lim.data(); t.scale = &sc; t.scale_period = k;
+        int32_t rc = launch_transform(c, t);
+        if (rc != HE_OK) return rc;
+    }
+    {
+        ConvBatch b;
+        b.njobs = 1; b.reps = 2 * J;
+        b.src_stride = (size_t)k * N;
+        b.dst_stride = (size_t)L1 * N;
+        ConvJob& job = b.job[0];
+        job.src = tmp_dn; job.dst = conv; job.hat = c->d_dn_hat; job.hat_w = pad8(k); job.ns = k; job.nt = L1;
         for (uint32_t r = 0; r < L1; r++) { job.tgt_limb[r] = (uint8_t)r; job.tgt_mod[r] = (uint8_t)r; }
-    }
-    rc = launch_baseconv(c, b, 2, L1, k);
-    if (rc != HE_OK) return rc;
-    std::vector<uint32_t> mods(2 * L1);
-    for (uint32_t i = 0; i < 2 * L1; i++) mods[i] = i % L1;
-    if (c->logN == 16 && 2 * L1 <= HE_MAX_LAUNCH_LIMBS) {
-        // the last NTT pass applies (acc - conv) * P^-1 (+ sigma_g(c0)) and writes the outputs itself
-        ModDownEpilogue ep;
-        ep.acc = acc; ep.c0 = d_c0; ep.out0 = d_out0; ep.out1 = d_out1;
-        ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1; ep.g = g_perm;
-        rc = launch_ntt16_moddown(c, conv, mods.data(), 2 * L1, ep);
+        int32_t rc = launch_baseconv(c, b, L1, k);
         if (rc != HE_OK) return rc;
-    } else {
-        rc = launch_ntt(c, conv, mods.data(), 2 * L1);
-        if (rc != HE_OK) return rc;
-        dim3 grid(N / KS_THREADS, L1, 2), block(KS_THREADS);
-        hipLaunchKernelGGL(moddown_final_kernel, grid, block, 0, c->stream, acc, conv, d_c0, d_out0, d_out1, c->d_mc, c->d_pinv,
-                           c->d_pinv_sh, c->logN, R, L1, g_perm);
-        HE_HIP(c, hipGetLastError());
     }
-    c->cnt.keyswitch += 1;
-    if (d_c0) c->cnt.automorph += L1;
+    {
+        ModDownEpilogue ep = {};
+        ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
+        for (uint32_t i = 0; i < J; i++) {
+            ep.c0[i] = srcs[jobs[i].src].c0; ep.c1[i] = srcs[jobs[i].src].c1;
+            ep.out0[i] = jobs[i].out0; ep.out1[i] = jobs[i].out1;
+            ep.g[i] = jobs[i].g; ep.add_self[i] = jobs[i].add_self ? 1 : 0;
+            if (ep.c0[i]) c->cnt.automorph += L1;
+        }
+        const uint32_t n = J * 2 * L1;
+        std::vector<uint32_t> mods(n);
+        for (uint32_t i = 0; i < n; i++) mods[i] = i % L1;
+        TransformDesc t = {};
+        t.fwd = true; t.seg[0] = conv; t.n_seg = 1; t.dst = conv; t.n = n; t.mod_idx = mods.data(); t.ep = &ep;
+        int32_t rc = launch_transform(c, t);
+        if (rc != HE_OK) return rc;
+    }
+    c->cnt.keyswitch += J;
     return HE_OK;
 }
 
-static bool overlaps(const void* a, size_t ab, const void* b, size_t bb) {
-    const char *x = (const char*)a, *y = (const char*)b;
-    return x < y + bb && y < x + ab;
+int32_t ks_engine(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t n_src, const KsJob* jobs, uint32_t n_jobs) {
+    if (n_jobs == 0) return HE_OK;
+    const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
+    if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
+    int32_t rc = he_ensure_ws(c, ks_engine_ws_elems(c, level, n_src, n_jobs) * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    uint32_t cb, jb;
+    engine_shape(c, level, n_src, n_jobs, cb, jb);
+    u64* raised = c->d_ws;
+    u64* tmp_up = raised + (size_t)cb * beta * R * N;
+    u64* acc = tmp_up + (size_t)cb * L1 * N;
+    u64* tmp_dn = acc + (size_t)jb * 2 * R * N;
+    u64* conv = tmp_dn + (size_t)jb * 2 * k * N;
+    // jobs ordered by source wave, then by key so that equal keys are adjacent
+    std::vector<uint32_t> order(n_jobs);
+    for (uint32_t i = 0; i < n_jobs; i++) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        uint32_t wa = jobs[a].src / cb, wb = jobs[b].src / cb;
+        if (wa != wb) return wa < wb;
+        if (jobs[a].evk != jobs[b].evk) return jobs[a].evk < jobs[b].evk;
+        return jobs[a].g < jobs[b].g;
+    });
+    size_t pos = 0;
+    for (uint32_t s0 = 0; s0 < n_src; s0 += cb) {
+        const uint32_t ns = std::min(cb, n_src - s0);
+        size_t end = pos;
+        while (end < n_jobs && jobs[order[end]].src / cb == s0 / cb) end++;
+        if (end == pos) continue;                       // no job uses these sources
+        rc = modup_batch(c, srcs + s0, ns, level, raised, tmp_up);
+        if (rc != HE_OK) return rc;
+        while (pos < end) {
+            const uint32_t J = (uint32_t)std::min<size_t>(jb, end - pos);
+            KsJob chunk[HE_MAX_KS_JOBS];
+            const u64* raised_of[HE_MAX_KS_JOBS];
+            for (uint32_t i = 0; i < J; i++) {
+                chunk[i] = jobs[order[pos + i]];
+                raised_of[i] = raised + (size_t)(chunk[i].src - s0) * beta * R * N;
+            }
+            rc = inner_moddown_batch(c, level, srcs, chunk, raised_of, J, acc, tmp_dn, conv);
+            if (rc != HE_OK) return rc;
+            pos += J;
+        }
+    }
+    return HE_OK;
 }
 
-static int32_t check_ks_ready(he_ctx* c, uint32_t level, const char* who) {
-    if (c->np == 0) return he_fail(c, HE_ERR_BADARG, "%s: context has no special primes", who);
-    if (level >= c->nq) return he_fail(c, HE_ERR_LEVEL, "%s: level %u above L=%u", who, level, c->nq - 1);
-    return he_ensure_ws(c, (ks_raised_elems(c, level) + ks_scratch_elems(c, level)) * sizeof(u64));
-}
+// ---------------------------------------------------------------- rescale
 
 size_t rescale_ws_elems(const he_ctx* c, uint32_t level) { return (size_t)(2 + 2 * level) * c->N; }
 
@@ -411,7 +578,9 @@ int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u
     u64* delta = tmp + (size_t)2 * N;
     uint32_t two[2] = {level, level};
     uint16_t from[2] = {(uint16_t)level, (uint16_t)(L1 + level)};
-    int32_t rc = launch_intt_from(ctx, d_ct, from, tmp, two, 2, nullptr);
+    TransformDesc t = {};
+    t.fwd = false; t.seg[0] = d_ct; t.n_seg = 1; t.dst = tmp; t.n = 2; t.mod_idx = two; t.src_limb = from;
+    int32_t rc = launch_transform(ctx, t);
     if (rc != HE_OK) return rc;
     dim3 grid(N / KS_THREADS, level, 2), block(KS_THREADS);
     hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level);
@@ -430,6 +599,19 @@ int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u
     return HE_OK;
 }
 
+// ---------------------------------------------------------------- entry points
+
+static bool overlaps(const void* a, size_t ab, const void* b, size_t bb) {
+    const char *x = (const char*)a, *y = (const char*)b;
+    return x < y + bb && y < x + ab;
+}
+
+static int32_t check_ks_ready(he_ctx* c, uint32_t level, const char* who) {
+    if (c->np == 0) return he_fail(c, HE_ERR_BADARG, "%s: context has no special primes", who);
+    if (level >= c->nq) return he_fail(c, HE_ERR_LEVEL, "%s: level %u above L=%u", who, level, c->nq - 1);
+    return HE_OK;
+}
+
 extern "C" {
 
 int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t galois_elt_of_key, uint64_t* d_out0,
@@ -440,58 +622,82 @@ int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t
     if (rc != HE_OK) return rc;
     auto it = ctx->evk.find(galois_elt_of_key);
     if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_keyswitch: no key registered for Galois element %u", galois_elt_of_key);
-    u64* raised = ctx->d_ws;
-    u64* scratch = raised + ks_raised_elems(ctx, level);
-    rc = modup_impl(ctx, (const u64*)d_in, level, raised, scratch);
-    if (rc != HE_OK) return rc;
-    return ks_inner_moddown(ctx, raised, (const u64*)d_in, level, 1, it->second, nullptr, (u64*)d_out0, (u64*)d_out1, scratch);
+    KsSrc src = {nullptr, (const u64*)d_in};
+    KsJob job = {0, 1, it->second, (u64*)d_out0, (u64*)d_out1, 0};
+    return ks_engine(ctx, level, &src, 1, &job, 1);
 }
 
-int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const int32_t* h_steps, uint32_t n_steps,
-                          uint64_t* const* h_d_out) {
+int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level, const int32_t* h_steps,
+                        uint32_t n_steps, uint64_t* const* h_d_out, int32_t hoisted) {
     if (!ctx) return HE_ERR_BADARG;
-    if (!d_ct || (n_steps && (!h_steps || !h_d_out))) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_hoisted: null argument");
-    int32_t rc = check_ks_ready(ctx, level, "he_rotate_hoisted");
+    if (n_ct == 0 || n_steps == 0) return HE_OK;
+    if (!h_d_ct || !h_steps || !h_d_out) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_batch: null argument");
+    int32_t rc = check_ks_ready(ctx, level, "he_rotate_batch");
     if (rc != HE_OK) return rc;
     const uint32_t N = ctx->N, L1 = level + 1;
     const size_t ct_b = (size_t)2 * L1 * N * sizeof(u64);
     // validate everything before any work is enqueued
     std::vector<uint32_t> gs(n_steps);
     std::vector<const u64*> keys(n_steps, nullptr);
-    bool any_ks = false;
-    for (uint32_t i = 0; i < n_steps; i++) {
-        if (!h_d_out[i]) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_hoisted: output %u is null", i);
-        if (overlaps(h_d_out[i], ct_b, d_ct, ct_b)) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_hoisted: output %u overlaps the input", i);
-        for (uint32_t k = 0; k < i; k++)
-            if (overlaps(h_d_out[i], ct_b, h_d_out[k], ct_b)) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_hoisted: outputs %u and %u overlap", k, i);
-        gs[i] = h_galois_of_step(ctx, h_steps[i]);
-        if (gs[i] == 1) continue;
-        auto it = ctx->evk.find(gs[i]);
-        if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_rotate_hoisted: no key for step %d (Galois element %u)", h_steps[i], gs[i]);
-        keys[i] = it->second;
-        any_ks = true;
+    for (uint32_t s = 0; s < n_steps; s++) {
+        gs[s] = h_galois_of_step(ctx, h_steps[s]);
+        if (gs[s] == 1) continue;
+        auto it = ctx->evk.find(gs[s]);
+        if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_rotate_batch: no key for step %d (Galois element %u)", h_steps[s], gs[s]);
+        keys[s] = it->second;
     }
-    u64* raised = ctx->d_ws;
-    u64* scratch = raised + ks_raised_elems(ctx, level);
-    if (any_ks) {
-        rc = modup_impl(ctx, (const u64*)d_ct + (size_t)L1 * N, level, raised, scratch);
-        if (rc != HE_OK) return rc;
-    }
-    for (uint32_t i = 0; i < n_steps; i++) {
-        u64* out = (u64*)h_d_out[i];
-        if (gs[i] == 1) {
-            HE_HIP(ctx, hipMemcpyAsync(out, d_ct, ct_b, hipMemcpyDeviceToDevice, ctx->stream));
-            continue;
+    const size_t total = (size_t)n_ct * n_steps;
+    for (uint32_t c = 0; c < n_ct; c++)
+        if (!h_d_ct[c]) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_batch: ciphertext %u is null", c);
+    {   // no output may overlap an input or another output: sort all buffers by address and sweep
+        struct Buf { const char* p; bool out; };
+        std::vector<Buf> bufs;
+        bufs.reserve(total + n_ct);
+        for (size_t i = 0; i < total; i++) {
+            if (!h_d_out[i]) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_batch: output %zu is null", i);
+            bufs.push_back({(const char*)h_d_out[i], true});
         }
-        rc = ks_inner_moddown(ctx, raised, (const u64*)d_ct + (size_t)L1 * N, level, gs[i], keys[i], (const u64*)d_ct, out, out + (size_t)L1 * N, scratch);
-        if (rc != HE_OK) return rc;
+        for (uint32_t c = 0; c < n_ct; c++) bufs.push_back({(const char*)h_d_ct[c], false});
+        std::sort(bufs.begin(), bufs.end(), [](const Buf& a, const Buf& b) { return a.p < b.p; });
+        for (size_t i = 1; i < bufs.size(); i++)
+            if (bufs[i].p < bufs[i - 1].p + ct_b && (bufs[i].out || bufs[i - 1].out))
+                return he_fail(ctx, HE_ERR_BADARG, "he_rotate_batch: an output overlaps an input or another output");
     }
-    return HE_OK;
+    std::vector<KsSrc> srcs;
+    std::vector<KsJob> jobs;
+    for (uint32_t c = 0; c < n_ct; c++) {
+        const u64* ct = (const u64*)h_d_ct[c];
+        bool have_src = false;
+        for (uint32_t s = 0; s < n_steps; s++) {
+            u64* out = (u64*)h_d_out[(size_t)c * n_steps + s];
+            if (gs[s] == 1) {
+                HE_HIP(ctx, hipMemcpyAsync(out, ct, ct_b, hipMemcpyDeviceToDevice, ctx->stream));
+                continue;
+            }
+            if (!hoisted || !have_src) {
+                srcs.push_back({ct, ct + (size_t)L1 * N});
+                have_src = true;
+            }
+            jobs.push_back({(uint32_t)srcs.size() - 1, gs[s], keys[s], out, out + (size_t)L1 * N, 0});
+        }
+    }
+    return ks_engine(ctx, level, srcs.data(), (uint32_t)srcs.size(), jobs.data(), (uint32_t)jobs.size());
+}
+
+int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const int32_t* h_steps, uint32_t n_steps,
+                          uint64_t* const* h_d_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_ct) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_hoisted: null argument");
+    const uint64_t* cts[1] = {d_ct};
+    return he_rotate_batch(ctx, cts, 1, level, h_steps, n_steps, h_d_out, 1);
 }
 
 int32_t he_rotate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, int32_t step, uint64_t* d_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_ct || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_rotate: null argument");
+    const uint64_t* cts[1] = {d_ct};
     uint64_t* outs[1] = {d_out};
-    return he_rotate_hoisted(ctx, d_ct, level, &step, 1, outs);
+    return he_rotate_batch(ctx, cts, 1, level, &step, 1, outs, 1);
 }
 
 int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out) {
@@ -504,11 +710,10 @@ int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t
     if (overlaps(d_out, ct_b, d_ct, ct_b)) return he_fail(ctx, HE_ERR_BADARG, "he_conjugate: output overlaps the input");
     auto it = ctx->evk.find(g);
     if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_conjugate: no key registered for Galois element %u", g);
-    u64* raised = ctx->d_ws;
-    u64* scratch = raised + ks_raised_elems(ctx, level);
-    rc = modup_impl(ctx, (const u64*)d_ct + (size_t)L1 * N, level, raised, scratch);
-    if (rc != HE_OK) return rc;
-    return ks_inner_moddown(ctx, raised, (const u64*)d_ct + (size_t)L1 * N, level, g, it->second, (const u64*)d_ct, (u64*)d_out, (u64*)d_out + (size_t)L1 * N, scratch);
+    const u64* ct = (const u64*)d_ct;
+    KsSrc src = {ct, ct + (size_t)L1 * N};
+    KsJob job = {0, g, it->second, (u64*)d_out, (u64*)d_out + (size_t)L1 * N, 0};
+    return ks_engine(ctx, level, &src, 1, &job, 1);
 }
 
 int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out) {

@@ -39,7 +39,7 @@ __device__ __forceinline__ uint32_t tile_global_index(uint32_t e, uint32_t tile,
 }
 
 template <bool FWD, bool CUSTOM_SCALE>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbList ll, ScaleList sc) {
+__global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbList ll, ScaleList sc, uint32_t scale_period) {
     __shared__ u64 sm[1u << NTT_LOG_TILE_MAX];
     const uint32_t tile_elems = 1u << a.log_tile;
     const uint32_t tiles_per_limb = 1u << (a.logN - a.log_tile);
@@ -100,8 +100,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbLi
 
     u64 scale = 0, scale_sh = 0;
     if (!FWD && a.last) {
-        scale = CUSTOM_SCALE ? sc.s[limb] : m.ninv;
-        scale_sh = CUSTOM_SCALE ? sc.s_sh[limb] : m.ninv_sh;
+        scale = CUSTOM_SCALE ? sc.s[limb % scale_period] : m.ninv;
+        scale_sh = CUSTOM_SCALE ? sc.s_sh[limb % scale_period] : m.ninv_sh;
     }
     for (uint32_t e = threadIdx.x; e < tile_elems; e += NTT_THREADS) {
         u64 v = sm[e];
@@ -114,9 +114,9 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbLi
 }
 
 template <bool FWD>
-static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale) {
+static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale, uint32_t scale_period) {
     if (n == 0) return HE_OK;
-    if (n > HE_MAX_LAUNCH_LIMBS || (scale && n > HE_MAX_MODULI)) return he_fail(ctx, HE_ERR_BADARG, "transform: too many limbs in one launch");
+    if (n > HE_MAX_LAUNCH_LIMBS) return he_fail(ctx, HE_ERR_BADARG, "transform: too many limbs in one launch");
     LimbList ll;
     uint32_t live = 0;
     for (uint32_t i = 0; i < n; i++) {
@@ -150,9 +150,9 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
         }
         if (scale)
-            hipLaunchKernelGGL((ntt_tile_kernel<FWD, true>), grid, block, 0, ctx->stream, a, ll, sc);
+            hipLaunchKernelGGL((ntt_tile_kernel<FWD, true>), grid, block, 0, ctx->stream, a, ll, sc, scale_period ? scale_period : 1u);
         else
-            hipLaunchKernelGGL((ntt_tile_kernel<FWD, false>), grid, block, 0, ctx->stream, a, ll, sc);
+            hipLaunchKernelGGL((ntt_tile_kernel<FWD, false>), grid, block, 0, ctx->stream, a, ll, sc, 1u);
         HE_HIP(ctx, hipGetLastError());
         if (ctx->prof_on) {
             HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
@@ -163,39 +163,45 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
     return HE_OK;
 }
 
-int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n) {
-    if (ctx->logN == 16) return launch_transform16(ctx, true, d, nullptr, d, mod_idx, n, nullptr);
-    return run_transform<true>(ctx, d, mod_idx, n, nullptr);
-}
-int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale) {
-    if (ctx->logN == 16) return launch_transform16(ctx, false, d, nullptr, d, mod_idx, n, scale);
-    return run_transform<false>(ctx, d, mod_idx, n, scale);
-}
-
-// Out-of-place variants: limb i is read at src + src_limb[i]*N and its transform written at
-// dst + i*N.  The N = 2^16 path reads the source directly in its first pass; other ring sizes
-// copy first and transform in place.
-static int32_t gather_limbs(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n) {
+// Generic ring sizes: gather the source limbs with device copies, transform in place, and run the
+// ModDown epilogue as its own kernel.
+static int32_t launch_transform_generic(he_ctx* ctx, const TransformDesc& d) {
     const size_t N = ctx->N;
-    for (uint32_t i = 0; i < n;) {
-        if (mod_idx[i] == 0xFFu) { i++; continue; }
-        uint32_t j = i + 1;     // extend over a run of consecutive source limbs
-        while (j < n && mod_idx[j] != 0xFFu && src_limb[j] == src_limb[i] + (j - i)) j++;
-        HE_HIP(ctx, hipMemcpyAsync(dst + i * N, src + (size_t)src_limb[i] * N, (j - i) * N * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream));
+    for (uint32_t i = 0; i < d.n;) {
+        if (d.mod_idx[i] == 0xFFu) { i++; continue; }
+        const u64* base = d.seg[d.src_seg ? d.src_seg[i] : 0];
+        uint32_t sl = d.src_limb ? d.src_limb[i] : i;
+        uint32_t j = i + 1;     // extend over a run of consecutive source limbs of the same segment
+        while (j < d.n && d.mod_idx[j] != 0xFFu && (d.src_seg ? d.src_seg[j] : 0) == (d.src_seg ? d.src_seg[i] : 0) &&
+               (d.src_limb ? d.src_limb[j] : j) == sl + (j - i)) j++;
+        if (base + (size_t)sl * N != d.dst + (size_t)i * N)
+            HE_HIP(ctx, hipMemcpyAsync(d.dst + i * N, base + (size_t)sl * N, (j - i) * N * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream));
         i = j;
     }
+    int32_t rc = d.fwd ? run_transform<true>(ctx, d.dst, d.mod_idx, d.n, nullptr, 1)
+                       : run_transform<false>(ctx, d.dst, d.mod_idx, d.n, d.scale, d.scale_period);
+    if (rc != HE_OK) return rc;
+    if (d.fwd && d.ep) return launch_moddown_final(ctx, d.dst, d.n / (2 * d.ep->L1), *d.ep);
     return HE_OK;
 }
-int32_t launch_ntt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n) {
-    if (ctx->logN == 16) return launch_transform16(ctx, true, src, src_limb, dst, mod_idx, n, nullptr);
-    int32_t rc = gather_limbs(ctx, src, src_limb, dst, mod_idx, n);
-    return rc != HE_OK ? rc : run_transform<true>(ctx, dst, mod_idx, n, nullptr);
+
+int32_t launch_transform(he_ctx* ctx, const TransformDesc& d) {
+    if (d.n == 0) return HE_OK;
+    if (d.n > HE_MAX_LAUNCH_LIMBS) return he_fail(ctx, HE_ERR_BADARG, "transform: too many limbs in one launch");
+    if (d.scale && (d.scale_period == 0 || d.scale_period > HE_MAX_MODULI)) return he_fail(ctx, HE_ERR_BADARG, "transform: bad scale period");
+    return ctx->logN == 16 ? launch_transform16(ctx, d) : launch_transform_generic(ctx, d);
 }
-int32_t launch_intt_from(he_ctx* ctx, const u64* src, const uint16_t* src_limb, u64* dst, const uint32_t* mod_idx, uint32_t n,
-                         const ScaleList* scale) {
-    if (ctx->logN == 16) return launch_transform16(ctx, false, src, src_limb, dst, mod_idx, n, scale);
-    int32_t rc = gather_limbs(ctx, src, src_limb, dst, mod_idx, n);
-    return rc != HE_OK ? rc : run_transform<false>(ctx, dst, mod_idx, n, scale);
+
+int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n) {
+    TransformDesc t = {};
+    t.fwd = true; t.seg[0] = d; t.n_seg = 1; t.dst = d; t.n = n; t.mod_idx = mod_idx;
+    return launch_transform(ctx, t);
+}
+int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale) {
+    TransformDesc t = {};
+    t.fwd = false; t.seg[0] = d; t.n_seg = 1; t.dst = d; t.n = n; t.mod_idx = mod_idx;
+    t.scale = scale; t.scale_period = scale ? n : 0;
+    return launch_transform(ctx, t);
 }
 
 extern "C" {

@@ -20,15 +20,20 @@
 #define T16_THREADS 256
 
 struct Ntt16Args {
-    const u64* src;     // limb i is read at src + src_limb[i]*N (first pass only)
-    u64* dst;           // and written / transformed in place at dst + i*N
+    u64* dst;           // limb i is written / transformed in place at dst + i*N
     const ModConst* mc;
     const u64* tw;      // [M][N] forward or inverse twiddles
     const u64* tw_sh;
 };
+// Where the first pass reads limb i: segment (limb[i] >> 12) at limb offset (limb[i] & 0xFFF).
 struct SrcList {
+    const u64* seg[HE_MAX_SEGS];
     uint16_t limb[HE_MAX_LAUNCH_LIMBS];
 };
+__device__ __forceinline__ const u64* src_of(const SrcList& sl, uint32_t limb) {
+    const uint32_t e = sl.limb[limb];
+    return sl.seg[e >> 12] + ((size_t)(e & 0xFFFu) << 16);
+}
 // Work order of the row passes.  Their twiddles depend on (modulus, tile), so limbs that share a
 // modulus should run the same tile back to back on the same XCD (one L2 per XCD; workgroups are
 // handed to the 8 XCDs round-robin).  order[] lists the live limbs sorted by modulus, padded with
@@ -173,16 +178,19 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
 #pragma unroll
         for (int k = 0; k < 16; k++) row[t + 16 * k] = s[t + 17 * k];
     } else {
-        const uint32_t comp = limb / ep.L1, r = limb - comp * ep.L1;
+        const uint32_t pc = limb / ep.L1, r = limb - pc * ep.L1, job = pc >> 1, comp = pc & 1u;
         const u64 pinv = ep.pinv[r], pinv_sh = ep.pinv_sh[r];
-        const u64* acc = ep.acc + ((size_t)(comp * ep.R + r) << 16) + (size_t)b * 256;
-        u64* out = (comp ? ep.out1 : ep.out0) + ((size_t)r << 16) + (size_t)b * 256;
-        const u64* c0 = (comp == 0 && ep.c0) ? ep.c0 + ((size_t)r << 16) : nullptr;
+        const u64* acc = ep.acc + ((size_t)(pc * ep.R + r) << 16) + (size_t)b * 256;
+        u64* out = (comp ? ep.out1[job] : ep.out0[job]) + ((size_t)r << 16) + (size_t)b * 256;
+        const u64* c0 = (comp == 0 && ep.c0[job]) ? ep.c0[job] + ((size_t)r << 16) : nullptr;
+        const u64* self = ep.add_self[job] ? (comp ? ep.c1[job] : ep.c0[job]) + ((size_t)r << 16) + (size_t)b * 256 : nullptr;
+        const uint32_t g = ep.g[job];
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             const uint32_t e = t + 16 * k;
             u64 v = shoup_mul(submod(acc[e], s[t + 17 * k], q), pinv, pinv_sh, q);
-            if (c0) v = addmod(v, c0[ep.g == 1 ? b * 256 + e : galois_src16(b * 256 + e, ep.g)], q);
+            if (c0) v = addmod(v, c0[g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g)], q);
+            if (self) v = addmod(v, self[e], q);
             out[e] = v;
         }
     }
@@ -194,7 +202,7 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_a_kernel(Ntt16Args a, L
     const uint32_t mi = ll.mod[limb];
     if (mi == 0xFFu) return;
     const ModConst m = a.mc[mi];
-    const u64* src = a.src + ((size_t)sl.limb[limb] << 16);
+    const u64* src = src_of(sl, limb);
     u64* dst = a.dst + ((size_t)limb << 16);
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
@@ -232,7 +240,7 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
     const uint32_t blk = threadIdx.x >> 4, t = threadIdx.x & 15, b = tile * 16 + blk;
-    const u64* in = a.src + ((size_t)sl.limb[limb] << 16) + (size_t)b * 256;
+    const u64* in = src_of(sl, limb) + (size_t)b * 256;
     u64* out = a.dst + ((size_t)limb << 16) + (size_t)b * 256;
     u64* s = sm + blk * 272;
     u64 x[16];
@@ -255,7 +263,7 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
 
 // Pass A (columns): stages 7..4 on rows 16t+j, exchange, stages 3..0 on rows t+16k, final scale.
 template <bool CUSTOM_SCALE>
-__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, LimbList ll, ScaleList sc) {
+__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, LimbList ll, ScaleList sc, uint32_t scale_period) {
     __shared__ u64 sm[4096];
     const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
     const uint32_t mi = ll.mod[limb];
@@ -276,45 +284,32 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, L
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = sm[(t + 16 * k) * 16 + cl];
     inv_block4(x, tw, tw_sh, 0, 0, q, q4);
-    const u64 scale = CUSTOM_SCALE ? sc.s[limb] : m.ninv;
-    const u64 scale_sh = CUSTOM_SCALE ? sc.s_sh[limb] : m.ninv_sh;
+    const u64 scale = CUSTOM_SCALE ? sc.s[limb % scale_period] : m.ninv;
+    const u64 scale_sh = CUSTOM_SCALE ? sc.s_sh[limb % scale_period] : m.ninv_sh;
 #pragma unroll
     for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(csub(shoup_lazy4(x[k], scale, scale_sh, q), q2), q);
 }
 
 // ---------------------------------------------------------------- host
-// n <= HE_MAX_LAUNCH_LIMBS limbs; mod_idx[i] == 0xFF leaves limb i untouched.  src_limb == nullptr
-// means limb i is read at src + i*N (src may equal dst for an in-place transform).
-static int32_t transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
-                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale, const ModDownEpilogue* ep);
-
-int32_t launch_transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
-                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale) {
-    return transform16(ctx, fwd, src, src_limb, dst, mod_idx, n, scale, nullptr);
-}
-
-// Forward transform of d (in place for its first pass) whose last pass applies the ModDown epilogue.
-int32_t launch_ntt16_moddown(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ModDownEpilogue& ep) {
-    return transform16(ctx, true, d, nullptr, d, mod_idx, n, nullptr, &ep);
-}
-
-static int32_t transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t* src_limb, u64* dst,
-                           const uint32_t* mod_idx, uint32_t n, const ScaleList* scale, const ModDownEpilogue* ep) {
-    if (n == 0) return HE_OK;
-    if (n > HE_MAX_LAUNCH_LIMBS || (scale && n > HE_MAX_MODULI)) return he_fail(ctx, HE_ERR_BADARG, "transform: too many limbs in one launch");
+int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
+    const uint32_t n = d.n;
     LimbList ll;
     SrcList sl;
     uint32_t live = 0;
+    for (uint32_t s = 0; s < HE_MAX_SEGS; s++) sl.seg[s] = s < d.n_seg ? d.seg[s] : d.seg[0];
     for (uint32_t i = 0; i < n; i++) {
-        sl.limb[i] = src_limb ? src_limb[i] : (uint16_t)i;
-        if (mod_idx[i] == 0xFFu) { ll.mod[i] = 0xFF; continue; }
-        if (mod_idx[i] >= ctx->M) return he_fail(ctx, HE_ERR_BADARG, "transform: modulus index %u out of range", mod_idx[i]);
-        ll.mod[i] = (uint8_t)mod_idx[i];
+        uint32_t seg = d.src_seg ? d.src_seg[i] : 0, lim = d.src_limb ? d.src_limb[i] : i;
+        if (seg >= HE_MAX_SEGS || seg >= d.n_seg || lim >= 4096) return he_fail(ctx, HE_ERR_BADARG, "transform: source limb out of range");
+        sl.limb[i] = (uint16_t)((seg << 12) | lim);
+        if (d.mod_idx[i] == 0xFFu) { ll.mod[i] = 0xFF; continue; }
+        if (d.mod_idx[i] >= ctx->M) return he_fail(ctx, HE_ERR_BADARG, "transform: modulus index %u out of range", d.mod_idx[i]);
+        ll.mod[i] = (uint8_t)d.mod_idx[i];
         live++;
     }
     if (live == 0) return HE_OK;
+    const bool fwd = d.fwd;
     Ntt16Args a;
-    a.src = src; a.dst = dst; a.mc = ctx->d_mc;
+    a.dst = d.dst; a.mc = ctx->d_mc;
     a.tw = fwd ? ctx->d_tw : ctx->d_itw;
     a.tw_sh = fwd ? ctx->d_tw_sh : ctx->d_itw_sh;
     dim3 grid(n * 16), block(T16_THREADS);
@@ -342,11 +337,11 @@ static int32_t transform16(he_ctx* ctx, bool fwd, const u64* src, const uint16_t
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
         }
         if (fwd && pass == 0) hipLaunchKernelGGL(ntt16_fwd_a_kernel, grid, block, 0, ctx->stream, a, ll, sl);
-        else if (fwd && ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<true>, grid_rows, block, 0, ctx->stream, a, ll, rs, *ep);
+        else if (fwd && d.ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<true>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
         else if (fwd) { ModDownEpilogue none = {}; hipLaunchKernelGGL(ntt16_fwd_b_kernel<false>, grid_rows, block, 0, ctx->stream, a, ll, rs, none); }
         else if (pass == 0) hipLaunchKernelGGL(ntt16_inv_b_kernel, grid_rows, block, 0, ctx->stream, a, ll, sl, rs);
-        else if (scale) hipLaunchKernelGGL(ntt16_inv_a_kernel<true>, grid, block, 0, ctx->stream, a, ll, *scale);
-        else { ScaleList none; hipLaunchKernelGGL(ntt16_inv_a_kernel<false>, grid, block, 0, ctx->stream, a, ll, none); }
+        else if (d.scale) hipLaunchKernelGGL(ntt16_inv_a_kernel<true>, grid, block, 0, ctx->stream, a, ll, *d.scale, d.scale_period);
+        else { ScaleList none; hipLaunchKernelGGL(ntt16_inv_a_kernel<false>, grid, block, 0, ctx->stream, a, ll, none, 1u); }
         HE_HIP(ctx, hipGetLastError());
         if (ctx->prof_on) {
             HE_HIP(ctx, hipEventRecord(e1, ctx->stream));

@@ -57,6 +57,50 @@ def test_keyswitch_and_rotations_partial_digits(level):
         assert (host(single) == want).all(), s
 
 
+@pytest.mark.parametrize("cfg,level,n_ct,steps", [
+    ("toy", 5, 5, [1, 5, 0, -3, 1]),
+    ("toy", 2, 11, [5, 1]),
+    (2, 23, 3, [1 << i for i in range(0, 15, 2)]),      # 24 jobs: several ModDown launch sets, shared keys
+    (2, 4, 9, [1, 1 << 14]),                             # more sources than one ModUp wave
+])
+def test_rotate_batch_matches_single_calls_and_oracle(cfg, level, n_ct, steps):
+    """he_rotate_batch, hoisted and not, equals he_rotate call by call (bit for bit) and the oracle on a sample."""
+    from gpu_util import dev, host, zeros
+    prm = (toy_params(logN=8, q_bits=30, nq=6, p_bits=32, np_=2, dnum=3, hamming=16, seed=63) if cfg == "toy"
+           else config_params(cfg))
+    rng, orc, ctx, cl = _setup(prm, 63)
+    N = prm.N
+    keys = {}
+    for s in steps:
+        g = orc.galois_elt(s)
+        if g != 1 and g not in keys:
+            keys[g] = _key(prm, rng, cl, g)
+            ctx.he_evk_register(g, dev(keys[g]))
+    cts = [_rand_ct(prm, rng, level) for _ in range(n_ct)]
+    d_cts = [dev(c) for c in cts]
+    ref = {}
+    for c in range(n_ct):
+        for i, s in enumerate(steps):
+            o = zeros(2, level + 1, N)
+            ctx.he_rotate(d_cts[c], level, s, o)
+            ref[(c, i)] = host(o)
+    for hoisted in (True, False):
+        outs = [zeros(2, level + 1, N) for _ in range(n_ct * len(steps))]
+        ctx.he_counters_reset()
+        ctx.he_rotate_batch(d_cts, level, steps, outs, hoisted=hoisted)
+        cnt = ctx.he_counters()
+        nz = sum(1 for s in steps if orc.galois_elt(s) != 1)
+        assert cnt["keyswitch"] == n_ct * nz
+        assert cnt["modup"] == (n_ct if hoisted else n_ct * nz)
+        for c in range(n_ct):
+            for i, s in enumerate(steps):
+                assert (host(outs[c * len(steps) + i]) == ref[(c, i)]).all(), (hoisted, c, s)
+    for c, i in ((0, 0), (n_ct - 1, len(steps) - 1)):
+        g = orc.galois_elt(steps[i])
+        want = cts[c] if g == 1 else orc.rotate(cts[c], level, g, keys[g])
+        assert (ref[(c, i)] == want).all()
+
+
 def test_wide_digits_generic_conversion_path():
     """alpha = 10 > 8 source limbs per digit: the conversion kernel's chunked path (and a 60-limb raised basis)."""
     from gpu_util import dev, host, zeros
