@@ -45,11 +45,16 @@ struct ConvBatch {
 
 // Fast basis conversion.  grid: (N/512, ceil(nt_max/CONV_TGT_PER_BLOCK), njobs*reps); each thread
 // owns two adjacent coefficients (16-byte loads and stores).  The block's conversion constants
-// and target moduli are staged in LDS once and then read as broadcasts.  With at most 8 source
-// limbs (ONE_CHUNK) the pre-scaled sources stay in registers across all targets of the block.
+// and target moduli are staged in LDS once and then read as broadcasts.
+//
+// ONE_CHUNK (at most 8 source limbs): sources stay in registers across all targets, split into
+// 30-bit halves, and so are the constants; the four partial sums of 8 products of 30-bit halves
+// stay below 2^63, so they are plain 32x32+64 multiply-add chains with no carry handling, and
+// the 128-bit sum is assembled once per output (all moduli are below 2^60).
 template <bool ONE_CHUNK>
 __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const ModConst* mc, uint32_t logN) {
     __shared__ u64 s_hat[CONV_TGT_PER_BLOCK * 64];
+    __shared__ uint32_t s_h0[CONV_TGT_PER_BLOCK * 8], s_h1[CONV_TGT_PER_BLOCK * 8];
     __shared__ u64 s_q[CONV_TGT_PER_BLOCK], s_mu[CONV_TGT_PER_BLOCK];
     __shared__ uint32_t s_bits[CONV_TGT_PER_BLOCK];
     const uint32_t ji = blockIdx.z % b.njobs, rep = blockIdx.z / b.njobs;
@@ -62,7 +67,15 @@ __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const
     const uint32_t ns = job.ns, w = job.hat_w;
     for (uint32_t idx = threadIdx.x; idx < nt * w; idx += KS_THREADS) {
         uint32_t tt = idx / w, i = idx - tt * w;
-        s_hat[tt * 64 + i] = job.hat[(size_t)job.tgt_mod[t0 + tt] * w + i];
+        u64 h = job.hat[(size_t)job.tgt_mod[t0 + tt] * w + i];
+        if (ONE_CHUNK) {
+            if (i < 8) {                       // entries beyond the (at most 8) sources are zero padding
+                s_h0[tt * 8 + i] = (uint32_t)h & 0x3FFFFFFFu;
+                s_h1[tt * 8 + i] = (uint32_t)(h >> 30);
+            }
+        } else {
+            s_hat[tt * 64 + i] = h;
+        }
     }
     if (threadIdx.x < nt) {
         const ModConst m = mc[job.tgt_mod[t0 + threadIdx.x]];
@@ -71,24 +84,35 @@ __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const
     __syncthreads();
     const size_t n = (size_t)(blockIdx.x * KS_THREADS + threadIdx.x) * 2;
     if (n >= ((size_t)1 << logN)) return;      // rings smaller than one block of coefficient pairs
-    ulonglong2 y[8];
     if (ONE_CHUNK) {
+        uint32_t ya0[8], ya1[8], yb0[8], yb1[8];   // 30-bit halves of the two coefficients' sources
 #pragma unroll
-        for (uint32_t i = 0; i < 8; i++)
-            y[i] = i < ns ? *reinterpret_cast<const ulonglong2*>(src + ((size_t)i << logN) + n) : make_ulonglong2(0, 0);
-    }
-    for (uint32_t tt = 0; tt < nt; tt++) {
-        const u64 q = s_q[tt], mu = s_mu[tt];
-        const uint32_t bits = s_bits[tt];
-        const u64* h = s_hat + tt * 64;
-        u128 a0 = 0, a1 = 0;
-        if (ONE_CHUNK) {
+        for (uint32_t i = 0; i < 8; i++) {
+            ulonglong2 v = i < ns ? *reinterpret_cast<const ulonglong2*>(src + ((size_t)i << logN) + n) : make_ulonglong2(0, 0);
+            ya0[i] = (uint32_t)v.x & 0x3FFFFFFFu; ya1[i] = (uint32_t)(v.x >> 30);
+            yb0[i] = (uint32_t)v.y & 0x3FFFFFFFu; yb1[i] = (uint32_t)(v.y >> 30);
+        }
+        for (uint32_t tt = 0; tt < nt; tt++) {
+            const u64 q = s_q[tt], mu = s_mu[tt];
+            const uint32_t bits = s_bits[tt];
+            u64 a00 = 0, a01 = 0, a10 = 0, a11 = 0, b00 = 0, b01 = 0, b10 = 0, b11 = 0;
 #pragma unroll
             for (uint32_t i = 0; i < 8; i++) {
-                a0 += (u128)y[i].x * h[i];
-                a1 += (u128)y[i].y * h[i];
+                const uint32_t h0 = s_h0[tt * 8 + i], h1 = s_h1[tt * 8 + i];
+                a00 += (u64)ya0[i] * h0; a01 += (u64)ya0[i] * h1; a10 += (u64)ya1[i] * h0; a11 += (u64)ya1[i] * h1;
+                b00 += (u64)yb0[i] * h0; b01 += (u64)yb0[i] * h1; b10 += (u64)yb1[i] * h0; b11 += (u64)yb1[i] * h1;
             }
-        } else {
+            u128 sa = (u128)a00 + ((u128)(a01 + a10) << 30) + ((u128)a11 << 60);
+            u128 sb = (u128)b00 + ((u128)(b01 + b10) << 30) + ((u128)b11 << 60);
+            ulonglong2 o = make_ulonglong2(barrett128(sa, q, mu, bits), barrett128(sb, q, mu, bits));
+            *reinterpret_cast<ulonglong2*>(dst + ((size_t)job.tgt_limb[t0 + tt] << logN) + n) = o;
+        }
+    } else {
+        for (uint32_t tt = 0; tt < nt; tt++) {
+            const u64 q = s_q[tt], mu = s_mu[tt];
+            const uint32_t bits = s_bits[tt];
+            const u64* h = s_hat + tt * 64;
+            u128 a0 = 0, a1 = 0;
             for (uint32_t i0 = 0; i0 < ns; i0 += 8) {
                 if (i0) { a0 = barrett128(a0, q, mu, bits); a1 = barrett128(a1, q, mu, bits); }
                 for (uint32_t i = i0; i < min(i0 + 8, ns); i++) {
@@ -97,9 +121,9 @@ __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const
                     a1 += (u128)v.y * h[i];
                 }
             }
+            ulonglong2 o = make_ulonglong2(barrett128(a0, q, mu, bits), barrett128(a1, q, mu, bits));
+            *reinterpret_cast<ulonglong2*>(dst + ((size_t)job.tgt_limb[t0 + tt] << logN) + n) = o;
         }
-        ulonglong2 o = make_ulonglong2(barrett128(a0, q, mu, bits), barrett128(a1, q, mu, bits));
-        *reinterpret_cast<ulonglong2*>(dst + ((size_t)job.tgt_limb[t0 + tt] << logN) + n) = o;
     }
 }
 
@@ -665,20 +689,32 @@ int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_c
     }
     std::vector<KsSrc> srcs;
     std::vector<KsJob> jobs;
-    for (uint32_t c = 0; c < n_ct; c++) {
-        const u64* ct = (const u64*)h_d_ct[c];
-        bool have_src = false;
+    for (uint32_t c = 0; c < n_ct; c++)
+        for (uint32_t s = 0; s < n_steps; s++)
+            if (gs[s] == 1)
+                HE_HIP(ctx, hipMemcpyAsync((u64*)h_d_out[(size_t)c * n_steps + s], h_d_ct[c], ct_b, hipMemcpyDeviceToDevice, ctx->stream));
+    if (hoisted) {
+        // one source per ciphertext; the engine sorts each wave's jobs by key
+        for (uint32_t c = 0; c < n_ct; c++) {
+            const u64* ct = (const u64*)h_d_ct[c];
+            bool have_src = false;
+            for (uint32_t s = 0; s < n_steps; s++) {
+                if (gs[s] == 1) continue;
+                if (!have_src) { srcs.push_back({ct, ct + (size_t)L1 * N}); have_src = true; }
+                u64* out = (u64*)h_d_out[(size_t)c * n_steps + s];
+                jobs.push_back({(uint32_t)srcs.size() - 1, gs[s], keys[s], out, out + (size_t)L1 * N, 0});
+            }
+        }
+    } else {
+        // one source per rotation, step-major, so that the sources raised together use the same key
         for (uint32_t s = 0; s < n_steps; s++) {
-            u64* out = (u64*)h_d_out[(size_t)c * n_steps + s];
-            if (gs[s] == 1) {
-                HE_HIP(ctx, hipMemcpyAsync(out, ct, ct_b, hipMemcpyDeviceToDevice, ctx->stream));
-                continue;
-            }
-            if (!hoisted || !have_src) {
+            if (gs[s] == 1) continue;
+            for (uint32_t c = 0; c < n_ct; c++) {
+                const u64* ct = (const u64*)h_d_ct[c];
+                u64* out = (u64*)h_d_out[(size_t)c * n_steps + s];
                 srcs.push_back({ct, ct + (size_t)L1 * N});
-                have_src = true;
+                jobs.push_back({(uint32_t)srcs.size() - 1, gs[s], keys[s], out, out + (size_t)L1 * N, 0});
             }
-            jobs.push_back({(uint32_t)srcs.size() - 1, gs[s], keys[s], out, out + (size_t)L1 * N, 0});
         }
     }
     return ks_engine(ctx, level, srcs.data(), (uint32_t)srcs.size(), jobs.data(), (uint32_t)jobs.size());
