@@ -150,7 +150,9 @@ __device__ __forceinline__ uint32_t galois_src16(uint32_t j, uint32_t g) {
 }
 
 // Pass B: workgroup = 16 consecutive rows (256-point blocks); tid = blk*16 + t.  With EPI the
-// canonical result is not stored: it feeds the ModDown epilogue, which writes the outputs.
+// canonical result is not stored: it feeds the ModDown epilogue, which writes the outputs.  The
+// epilogue's operands (accumulator, rotated c0, the ciphertext itself) are fetched before the
+// butterflies start so that their latency is hidden behind the arithmetic.
 template <bool WIDE, bool EPI>
 __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, const u64* tw, const u64* tw_sh, uint32_t tile,
                                            const ModConst& m, uint32_t mrec, const ModDownEpilogue& ep, uint32_t limb) {
@@ -161,6 +163,29 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
     u64 x[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = row[t + 16 * k];
+    // epilogue operands for the points e = t + 16k this thread will finally own
+    u64 ea[16], ec[16];
+    u64* out = nullptr;
+    u64 pinv = 0, pinv_sh = 0;
+    bool has_c0 = false, has_self = false;
+    const u64* self = nullptr;
+    if (EPI) {
+        const uint32_t pc = limb / ep.L1, r = limb - pc * ep.L1, job = pc >> 1, comp = pc & 1u;
+        pinv = ep.pinv[r]; pinv_sh = ep.pinv_sh[r];
+        const u64* acc = ep.acc + ((size_t)(pc * ep.R + r) << 16) + (size_t)b * 256;
+        out = (comp ? ep.out1[job] : ep.out0[job]) + ((size_t)r << 16) + (size_t)b * 256;
+        const u64* c0 = (comp == 0 && ep.c0[job]) ? ep.c0[job] + ((size_t)r << 16) : nullptr;
+        has_c0 = c0 != nullptr;
+        has_self = ep.add_self[job] != 0;
+        self = has_self ? (comp ? ep.c1[job] : ep.c0[job]) + ((size_t)r << 16) + (size_t)b * 256 : nullptr;
+        const uint32_t g = ep.g[job];
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const uint32_t e = t + 16 * k;
+            ea[k] = acc[e];
+            ec[k] = has_c0 ? c0[g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g)] : 0;
+        }
+    }
     fwd_block4<WIDE>(x, tw, tw_sh, 8, b, q, q4);
 #pragma unroll
     for (int k = 0; k < 16; k++) s[t + 17 * k] = x[k];
@@ -178,20 +203,13 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
 #pragma unroll
         for (int k = 0; k < 16; k++) row[t + 16 * k] = s[t + 17 * k];
     } else {
-        const uint32_t pc = limb / ep.L1, r = limb - pc * ep.L1, job = pc >> 1, comp = pc & 1u;
-        const u64 pinv = ep.pinv[r], pinv_sh = ep.pinv_sh[r];
-        const u64* acc = ep.acc + ((size_t)(pc * ep.R + r) << 16) + (size_t)b * 256;
-        u64* out = (comp ? ep.out1[job] : ep.out0[job]) + ((size_t)r << 16) + (size_t)b * 256;
-        const u64* c0 = (comp == 0 && ep.c0[job]) ? ep.c0[job] + ((size_t)r << 16) : nullptr;
-        const u64* self = ep.add_self[job] ? (comp ? ep.c1[job] : ep.c0[job]) + ((size_t)r << 16) + (size_t)b * 256 : nullptr;
-        const uint32_t g = ep.g[job];
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             const uint32_t e = t + 16 * k;
-            u64 v = shoup_mul(submod(acc[e], s[t + 17 * k], q), pinv, pinv_sh, q);
-            if (c0) v = addmod(v, c0[g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g)], q);
-            if (self) v = addmod(v, self[e], q);
-            out[e] = v;
+            // (acc - ntt) * P^-1 lazily in [0,4q), plus up to two canonical addends: below 6q
+            u64 v = shoup_lazy4(ea[k] + q - s[t + 17 * k], pinv, pinv_sh, q) + ec[k];
+            if (has_self) v += self[e];
+            out[e] = csub(csub(csub(v, q4), q2), q);
         }
     }
 }
