@@ -8,15 +8,58 @@
 #define CV_THREADS 256
 #define CV_MAX_TAPS 49
 
+#define CV_MAX_OUT_PER_LAUNCH 16
+
 struct MacTaps {
-    const u64* ct[CV_MAX_TAPS]; // rotated inputs [2][L1][N]
-    const u64* pt[CV_MAX_TAPS]; // filter plaintexts [L1][N]
-    uint32_t n;
+    const u64* ct[CV_MAX_TAPS];                          // rotated inputs [2][L1][N]
+    uint32_t n_taps, n_out;
+    u64* acc[CV_MAX_OUT_PER_LAUNCH];                     // one accumulator [2][L1][N] per output
+};
+struct MacWeights {
+    const u64* pt[CV_MAX_OUT_PER_LAUNCH * 9];            // [out][tap] filter plaintexts [L1][N] (9-tap fast path)
 };
 
-// MulFilter&Sum_f for one output ciphertext: acc_c[limb] = sum_t ct_t,c[limb] * pt_t[limb].
-// Products are summed in 128 bits and reduced once per 8 taps.  grid: (N/256, L1).
-__global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTaps taps, u64* __restrict__ acc, const ModConst* mc,
+// MulFilter&Sum_f for several output ciphertexts at once (9 taps or fewer): the rotated inputs of a
+// coefficient are loaded once and reused for every output, acc_o,c[limb] = sum_t ct_t,c[limb] *
+// pt_o,t[limb], summed in 128 bits and reduced once per 8 taps.  grid: (N/256, L1).
+__global__ __launch_bounds__(CV_THREADS) void mac_taps9_kernel(MacTaps taps, MacWeights w, const ModConst* mc, uint32_t logN,
+                                                               uint32_t L1) {
+    const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
+    const uint32_t limb = blockIdx.y;
+    const ModConst m = mc[limb];
+    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n;
+    u64 c0[9], c1[9];
+#pragma unroll
+    for (uint32_t t = 0; t < 9; t++) {
+        c0[t] = t < taps.n_taps ? taps.ct[t][o0] : 0;
+        c1[t] = t < taps.n_taps ? taps.ct[t][o1] : 0;
+    }
+    for (uint32_t o = 0; o < taps.n_out; o++) {
+        u128 a0 = 0, a1 = 0;
+#pragma unroll
+        for (uint32_t t = 0; t < 9; t++) {
+            if (t == 8) {
+                a0 = barrett128(a0, m.q, m.mu, m.bits);
+                a1 = barrett128(a1, m.q, m.mu, m.bits);
+            }
+            if (t < taps.n_taps) {
+                u64 p = w.pt[o * 9 + t][o0];
+                a0 += (u128)c0[t] * p;
+                a1 += (u128)c1[t] * p;
+            }
+        }
+        taps.acc[o][o0] = barrett128(a0, m.q, m.mu, m.bits);
+        taps.acc[o][o1] = barrett128(a1, m.q, m.mu, m.bits);
+    }
+}
+
+struct MacTapsAny {
+    const u64* ct[CV_MAX_TAPS];
+    const u64* pt[CV_MAX_TAPS];
+    uint32_t n;
+};
+// Any number of taps, one output per launch.
+__global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTapsAny taps, u64* __restrict__ acc, const ModConst* mc,
                                                               uint32_t logN, uint32_t L1) {
     const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
     const uint32_t limb = blockIdx.y;
@@ -74,39 +117,40 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         if (!plan->h_d_weights[i]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: weight plaintext %u is null", i);
     for (uint32_t o = 0; o < plan->n_out; o++)
         if (!h_d_ct_out[o]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: output %u is null", o);
-    // workspace: [key-switch engine region][rescale scratch][taps-1 rotated inputs][acc][n_out temporaries]
+    // workspace: [key-switch engine region][rescale scratch][taps-1 rotated inputs][n_out accumulators]
+    //            [n_out temporaries]
     const uint32_t lo = level - 1;                       // level after the rescale
     const uint32_t n_out = plan->n_out, n_ras = (uint32_t)ras_g.size();
     const size_t ct_e = (size_t)2 * L1 * N, ct_lo_e = (size_t)2 * level * N;
     const size_t ks_e = std::max(ks_engine_ws_elems(ctx, level, 1, taps - 1), ks_engine_ws_elems(ctx, lo, n_out, n_out));
-    const size_t rs_e = rescale_ws_elems(ctx, level);
-    const size_t total = ks_e + rs_e + (size_t)taps * ct_e + (size_t)n_out * ct_lo_e;
+    const size_t rs_e = rescale_ws_elems(ctx, level, n_out);
+    const size_t total = ks_e + rs_e + (size_t)(taps - 1 + n_out) * ct_e + (size_t)n_out * ct_lo_e;
     int32_t rc = he_ensure_ws(ctx, total * sizeof(u64));
     if (rc != HE_OK) return rc;
     u64* rs_ws = ctx->d_ws + ks_e;
     u64* slid = rs_ws + rs_e;
-    u64* acc = slid + (size_t)(taps - 1) * ct_e;
-    u64* tmp = acc + ct_e;                               // [n_out] ciphertexts at level lo
+    u64* acc = slid + (size_t)(taps - 1) * ct_e;         // [n_out] ciphertexts at `level`
+    u64* tmp = acc + (size_t)n_out * ct_e;               // [n_out] ciphertexts at level lo
     const u64* ct_in = (const u64*)d_ct_in;
 
     // Slide_f: one ModUp of c1 shared by all taps
-    MacTaps mt;
-    mt.n = taps;
+    std::vector<const u64*> tap_ct(taps);
     {
         KsSrc src = {ct_in, ct_in + (size_t)L1 * N};
         std::vector<KsJob> jobs;
         uint32_t nb = 0;
         for (uint32_t t = 0; t < taps; t++) {
-            if (tap_g[t] == 1) { mt.ct[t] = ct_in; continue; }
+            if (tap_g[t] == 1) { tap_ct[t] = ct_in; continue; }
             u64* out = slid + (size_t)nb++ * ct_e;
             jobs.push_back({0, tap_g[t], tap_key[t], out, out + (size_t)L1 * N, 0});
-            mt.ct[t] = out;
+            tap_ct[t] = out;
         }
         rc = ks_engine(ctx, level, &src, 1, jobs.data(), (uint32_t)jobs.size());
         if (rc != HE_OK) return rc;
     }
-    // MulFilter&Sum_f and Rescale per output.  The rotate-and-sum steps ping-pong between the
-    // caller's output buffers and the temporaries; start so that the last step lands in the output.
+    // MulFilter&Sum_f for all outputs, then Rescale of all outputs.  The rotate-and-sum steps
+    // ping-pong between the caller's output buffers and the temporaries; start so that the last
+    // step lands in the output.
     std::vector<u64*> cur(n_out), nxt(n_out);
     for (uint32_t o = 0; o < n_out; o++) {
         u64* a = (u64*)h_d_ct_out[o];
@@ -114,13 +158,35 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         cur[o] = (n_ras & 1u) ? b : a;
         nxt[o] = (n_ras & 1u) ? a : b;
     }
-    for (uint32_t o = 0; o < n_out; o++) {
-        for (uint32_t t = 0; t < taps; t++) mt.pt[t] = (const u64*)plan->h_d_weights[(size_t)o * taps + t];
+    {
         dim3 grid(N / CV_THREADS, L1), block(CV_THREADS);
-        hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc, ctx->d_mc, ctx->logN, L1);
-        HE_HIP(ctx, hipGetLastError());
-        ctx->cnt.mac += taps;
-        rc = rescale_impl(ctx, acc, level, cur[o], rs_ws);
+        if (taps <= 9) {
+            for (uint32_t o0 = 0; o0 < n_out; o0 += CV_MAX_OUT_PER_LAUNCH) {
+                MacTaps mt;
+                MacWeights mw;
+                mt.n_taps = taps;
+                mt.n_out = std::min<uint32_t>(CV_MAX_OUT_PER_LAUNCH, n_out - o0);
+                for (uint32_t t = 0; t < taps; t++) mt.ct[t] = tap_ct[t];
+                for (uint32_t o = 0; o < mt.n_out; o++) {
+                    mt.acc[o] = acc + (size_t)(o0 + o) * ct_e;
+                    for (uint32_t t = 0; t < taps; t++) mw.pt[o * 9 + t] = (const u64*)plan->h_d_weights[(size_t)(o0 + o) * taps + t];
+                }
+                hipLaunchKernelGGL(mac_taps9_kernel, grid, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, L1);
+                HE_HIP(ctx, hipGetLastError());
+            }
+        } else {
+            for (uint32_t o = 0; o < n_out; o++) {
+                MacTapsAny mt;
+                mt.n = taps;
+                for (uint32_t t = 0; t < taps; t++) { mt.ct[t] = tap_ct[t]; mt.pt[t] = (const u64*)plan->h_d_weights[(size_t)o * taps + t]; }
+                hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc + (size_t)o * ct_e, ctx->d_mc, ctx->logN, L1);
+                HE_HIP(ctx, hipGetLastError());
+            }
+        }
+        ctx->cnt.mac += (uint64_t)taps * n_out;
+        std::vector<const u64*> accs(n_out);
+        for (uint32_t o = 0; o < n_out; o++) accs[o] = acc + (size_t)o * ct_e;
+        rc = rescale_batch(ctx, accs.data(), cur.data(), n_out, level, rs_ws);
         if (rc != HE_OK) return rc;
     }
     // rotate-and-sum over the outermost channel dimension: every step is one batch over all

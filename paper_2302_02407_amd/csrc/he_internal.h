@@ -154,5 +154,5 @@ struct KsJob {
 // Runs every job: one ModUp per source, then inner product + ModDown per job, batched.
 int32_t ks_engine(he_ctx* ctx, uint32_t level, const KsSrc* srcs, uint32_t n_src, const KsJob* jobs, uint32_t n_jobs);
 size_t ks_engine_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_src, uint32_t n_jobs);
-size_t rescale_ws_elems(const he_ctx* c, uint32_t level);
-int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u64* ws);
+size_t rescale_ws_elems(const he_ctx* c, uint32_t level, uint32_t n);
+int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint32_t n, uint32_t level, u64* ws);

@@ -231,31 +231,35 @@ int32_t launch_moddown_final(he_ctx* c, const u64* conv, uint32_t n_jobs, const 
 }
 
 // ---------------------------------------------------------------- rescale kernels
-// grid: (N/256, level, 2).  t = coefficient-form limb `level` of component comp (tmp[comp][N]);
-// delta[comp][r] = (h mod q_r) - ((t + h mod q_l) mod q_r), h = floor(q_l/2).
+struct RescaleBatch {
+    const u64* ct[HE_MAX_KS_JOBS];   // [2][level+1][N]
+    u64* out[HE_MAX_KS_JOBS];        // [2][level][N]
+};
+
+// grid: (N/256, level, 2*n).  t = coefficient-form limb `level` of (job, comp) (tmp[job*2+comp][N]);
+// delta[job][comp][r] = (h mod q_r) - ((t + h mod q_l) mod q_r), h = floor(q_l/2).
 __global__ __launch_bounds__(KS_THREADS) void rescale_delta_kernel(const u64* __restrict__ tmp, u64* __restrict__ delta,
                                                                    const ModConst* mc, uint32_t logN, uint32_t level) {
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
-    const uint32_t r = blockIdx.y, comp = blockIdx.z;
+    const uint32_t r = blockIdx.y, jc = blockIdx.z;
     const ModConst ml = mc[level], mr = mc[r];
     u64 h = ml.q >> 1;
-    u64 t = addmod(tmp[((size_t)comp << logN) + n], h, ml.q);
+    u64 t = addmod(tmp[((size_t)jc << logN) + n], h, ml.q);
     u64 tr = barrett64(t, mr.q, mr.mu, mr.bits);
     u64 hr = barrett64(h, mr.q, mr.mu, mr.bits);
-    delta[((size_t)(comp * level + r) << logN) + n] = submod(hr, tr, mr.q);
+    delta[((size_t)(jc * level + r) << logN) + n] = submod(hr, tr, mr.q);
 }
 
-// grid: (N/256, level, 2).  out[comp][r] = (ct[comp][r] + delta[comp][r]) * q_l^-1 mod q_r.
-__global__ __launch_bounds__(KS_THREADS) void rescale_final_kernel(const u64* __restrict__ ct, const u64* __restrict__ delta,
-                                                                   u64* __restrict__ out, const ModConst* mc,
-                                                                   const u64* qlinv, const u64* qlinv_sh, uint32_t logN,
-                                                                   uint32_t level) {
+// grid: (N/256, level, 2*n).  out[comp][r] = (ct[comp][r] + delta[job][comp][r]) * q_l^-1 mod q_r.
+__global__ __launch_bounds__(KS_THREADS) void rescale_final_kernel(RescaleBatch rb, const u64* __restrict__ delta,
+                                                                   const ModConst* mc, const u64* qlinv, const u64* qlinv_sh,
+                                                                   uint32_t logN, uint32_t level) {
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
-    const uint32_t r = blockIdx.y, comp = blockIdx.z;
+    const uint32_t r = blockIdx.y, jc = blockIdx.z, job = jc >> 1, comp = jc & 1u;
     const u64 q = mc[r].q;
-    u64 a = ct[((size_t)(comp * (level + 1) + r) << logN) + n];
-    u64 d = delta[((size_t)(comp * level + r) << logN) + n];
-    out[((size_t)(comp * level + r) << logN) + n] = shoup_mul(addmod(a, d, q), qlinv[r], qlinv_sh[r], q);
+    u64 a = rb.ct[job][((size_t)(comp * (level + 1) + r) << logN) + n];
+    u64 d = delta[((size_t)(jc * level + r) << logN) + n];
+    rb.out[job][((size_t)(comp * level + r) << logN) + n] = shoup_mul(addmod(a, d, q), qlinv[r], qlinv_sh[r], q);
 }
 
 // ---------------------------------------------------------------- host: tables
@@ -593,33 +597,50 @@ int32_t ks_engine(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t n_src, 
 
 // ---------------------------------------------------------------- rescale
 
-size_t rescale_ws_elems(const he_ctx* c, uint32_t level) { return (size_t)(2 + 2 * level) * c->N; }
+// scratch for rescaling up to HE_MAX_KS_JOBS ciphertexts at once: tmp[2n][N] + delta[n][2][level][N]
+size_t rescale_ws_elems(const he_ctx* c, uint32_t level, uint32_t n) {
+    uint32_t nb = std::min<uint32_t>(n ? n : 1, HE_MAX_KS_JOBS);
+    return (size_t)nb * (2 + 2 * level) * c->N;
+}
 
-// ct [2][level+1][N] -> out [2][level][N]; ws: tmp[2][N] + delta[2][level][N]
-int32_t rescale_impl(he_ctx* ctx, const u64* d_ct, uint32_t level, u64* d_out, u64* ws) {
+// cts[i] [2][level+1][N] -> outs[i] [2][level][N] for i < n, batched HE_MAX_KS_JOBS at a time.
+int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint32_t n, uint32_t level, u64* ws) {
     const uint32_t N = ctx->N, L1 = level + 1;
-    u64* tmp = ws;
-    u64* delta = tmp + (size_t)2 * N;
-    uint32_t two[2] = {level, level};
-    uint16_t from[2] = {(uint16_t)level, (uint16_t)(L1 + level)};
-    TransformDesc t = {};
-    t.fwd = false; t.seg[0] = d_ct; t.n_seg = 1; t.dst = tmp; t.n = 2; t.mod_idx = two; t.src_limb = from;
-    int32_t rc = launch_transform(ctx, t);
-    if (rc != HE_OK) return rc;
-    dim3 grid(N / KS_THREADS, level, 2), block(KS_THREADS);
-    hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level);
-    HE_HIP(ctx, hipGetLastError());
-    std::vector<uint32_t> mods(2 * level);
-    for (uint32_t i = 0; i < 2 * level; i++) mods[i] = i % level;
-    for (uint32_t o = 0; o < 2 * level; o += HE_MAX_LAUNCH_LIMBS) {
-        uint32_t n = 2 * level - o < HE_MAX_LAUNCH_LIMBS ? 2 * level - o : HE_MAX_LAUNCH_LIMBS;
-        rc = launch_ntt(ctx, delta + (size_t)o * N, mods.data() + o, n);
+    for (uint32_t b0 = 0; b0 < n; b0 += HE_MAX_KS_JOBS) {
+        const uint32_t nb = std::min<uint32_t>(HE_MAX_KS_JOBS, n - b0);
+        u64* tmp = ws;
+        u64* delta = tmp + (size_t)2 * nb * N;
+        RescaleBatch rb;
+        std::vector<uint32_t> mods(2 * nb, level);
+        std::vector<uint8_t> seg(2 * nb);
+        std::vector<uint16_t> lim(2 * nb);
+        TransformDesc t = {};
+        t.fwd = false; t.n_seg = nb; t.dst = tmp; t.n = 2 * nb;
+        for (uint32_t i = 0; i < nb; i++) {
+            rb.ct[i] = cts[b0 + i]; rb.out[i] = outs[b0 + i];
+            t.seg[i] = cts[b0 + i];
+            seg[2 * i] = seg[2 * i + 1] = (uint8_t)i;
+            lim[2 * i] = (uint16_t)level; lim[2 * i + 1] = (uint16_t)(L1 + level);
+        }
+        t.mod_idx = mods.data(); t.src_seg = seg.data(); t.src_limb = lim.data();
+        int32_t rc = launch_transform(ctx, t);
         if (rc != HE_OK) return rc;
+        dim3 grid(N / KS_THREADS, level, 2 * nb), block(KS_THREADS);
+        hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level);
+        HE_HIP(ctx, hipGetLastError());
+        const uint32_t total = 2 * nb * level;
+        std::vector<uint32_t> dm(total);
+        for (uint32_t i = 0; i < total; i++) dm[i] = i % level;
+        for (uint32_t o = 0; o < total; o += HE_MAX_LAUNCH_LIMBS) {
+            uint32_t cnt = std::min<uint32_t>(HE_MAX_LAUNCH_LIMBS, total - o);
+            rc = launch_ntt(ctx, delta + (size_t)o * N, dm.data() + o, cnt);
+            if (rc != HE_OK) return rc;
+        }
+        hipLaunchKernelGGL(rescale_final_kernel, grid, block, 0, ctx->stream, rb, delta, ctx->d_mc,
+                           ctx->d_qlinv + (size_t)level * ctx->nq, ctx->d_qlinv_sh + (size_t)level * ctx->nq, ctx->logN, level);
+        HE_HIP(ctx, hipGetLastError());
+        ctx->cnt.rescale += nb;
     }
-    hipLaunchKernelGGL(rescale_final_kernel, grid, block, 0, ctx->stream, d_ct, delta, d_out, ctx->d_mc,
-                       ctx->d_qlinv + (size_t)level * ctx->nq, ctx->d_qlinv_sh + (size_t)level * ctx->nq, ctx->logN, level);
-    HE_HIP(ctx, hipGetLastError());
-    ctx->cnt.rescale += 1;
     return HE_OK;
 }
 
@@ -759,9 +780,11 @@ int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* 
     const size_t N = ctx->N;
     if (overlaps(d_out, 2 * level * N * sizeof(u64), d_ct, 2 * (level + 1) * N * sizeof(u64)))
         return he_fail(ctx, HE_ERR_BADARG, "he_rescale: output overlaps the input");
-    int32_t rc = he_ensure_ws(ctx, rescale_ws_elems(ctx, level) * sizeof(u64));
+    int32_t rc = he_ensure_ws(ctx, rescale_ws_elems(ctx, level, 1) * sizeof(u64));
     if (rc != HE_OK) return rc;
-    return rescale_impl(ctx, (const u64*)d_ct, level, (u64*)d_out, ctx->d_ws);
+    const u64* cts[1] = {(const u64*)d_ct};
+    u64* outs[1] = {(u64*)d_out};
+    return rescale_batch(ctx, cts, outs, 1, level, ctx->d_ws);
 }
 
 } // extern "C"
