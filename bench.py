@@ -25,6 +25,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_rotation_n65536_hbm_traffic.md")
+
+
+def measured_bytes_per_limb_pass():
+    """HBM bytes one limb pass of the transform kernels moved in the committed rocprofv3 --pmc runs
+    (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size), or None if absent."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("transform_bytes_per_limb_pass"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def uniform_dev(torch, gen, moduli, N, lead=()):
@@ -61,6 +74,13 @@ def main():
     ctx = HEContext.from_params(prm)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(prm.seed)
+
+    # a plain device copy of known size: the byte counters of a --pmc run are scaled by what they
+    # read for this dispatch
+    calib_src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    del calib_src, calib_dst
 
     steps15 = [1 << i for i in range(15)]
     keys = {}
@@ -115,14 +135,16 @@ def main():
     # its launches is credited an equal share
     alg_bytes = prof["transform_limb_passes"] * (2.0 * N * 8) / passes_per_transform
     achieved = alg_bytes / (prof["transform_ms"] * 1e-3) / 1e9
+    bplp = measured_bytes_per_limb_pass()
     roofline = {
-        "kernel": "ntt_tile_kernel",
+        "kernel": "ntt16_* (the four passes of the N=2^16 transform, incl. the fused ModDown epilogue)",
         "bound": "hbm",
         "achieved": round(achieved, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": None,
+        "traffic": None if bplp is None else round(bplp * prof["transform_limb_passes"] / max(1, prof["transform_launches"])),
+        "algorithmic_bytes_per_launch": round(alg_bytes / max(1, prof["transform_launches"])),
         "launches": prof["transform_launches"],
         "avg_launch_us": round(prof["transform_ms"] * 1e3 / max(1, prof["transform_launches"]), 2),
         "share_of_step": round(prof["transform_ms"] / ms_per_step, 3),
@@ -167,7 +189,7 @@ def main():
         import numpy as np
         from oracle.he_oracle import Oracle, num_threads
         orc = Oracle.from_params(prm)
-        n_cpu = 3
+        n_cpu = 8
         ct_h = cts[0].cpu().numpy()
         keys_h = [keys[s].cpu().numpy() for s in steps15[:n_cpu]]
         t0 = time.perf_counter()
