@@ -65,6 +65,14 @@ uint32_t h_galois_of_step(const he_ctx* ctx, int32_t step) {
     return (uint32_t)h_powmod(5, (u64)s, 2 * (u64)ctx->N);
 }
 
+void scale_entry(const he_ctx* c, ScaleList& sc, uint32_t i, uint32_t mi, u64 s) {
+    const u64 m = c->mod[mi];
+    sc.s[i] = s;
+    sc.s_sh[i] = h_shoup(s, m);
+    sc.w[i] = h_mulmod(s, c->itw1[mi], m);
+    sc.w_sh[i] = h_shoup(sc.w[i], m);
+}
+
 int32_t he_ensure_ws(he_ctx* ctx, size_t bytes) {
     if (bytes <= ctx->ws_bytes) return HE_OK;
     if (ctx->d_ws) {
@@ -144,6 +152,9 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
         mc.mu = (u64)(((u128)1 << (mc.bits + 63)) / m);
         mc.ninv = h_invmod(N % m, m);
         mc.ninv_sh = h_shoup(mc.ninv, m);
+        c->itw1[i] = h_powmod(ipsi, N / 2, m);
+        mc.ninv_w = h_mulmod(mc.ninv, c->itw1[i], m);
+        mc.ninv_w_sh = h_shoup(mc.ninv_w, m);
         mc.pad = 0;
     }
     size_t tb = (size_t)M * N * sizeof(u64);

@@ -21,6 +21,8 @@ struct ModConst {
     u64 mu;         // floor(2^(bits+63) / q): Barrett constant for inputs < 2^(bits+63)
     u64 ninv;       // N^-1 mod q
     u64 ninv_sh;    // Shoup companion floor(ninv * 2^64 / q)
+    u64 ninv_w;     // N^-1 * psi^-(N/2): scaling folded into the twiddle of the last inverse stage
+    u64 ninv_w_sh;
     uint32_t bits;  // bit length of q
     uint32_t pad;
 };
@@ -34,6 +36,8 @@ struct LimbList {
 struct ScaleList {
     u64 s[HE_MAX_MODULI];
     u64 s_sh[HE_MAX_MODULI];
+    u64 w[HE_MAX_MODULI];      // s * psi^-(N/2) mod q (the last inverse stage's twiddle, pre-scaled)
+    u64 w_sh[HE_MAX_MODULI];
 };
 
 struct ProfSpan {
@@ -47,6 +51,7 @@ struct he_ctx {
     int device;
     u64 mod[HE_MAX_MODULI];
     u64 psi[HE_MAX_MODULI];
+    u64 itw1[HE_MAX_MODULI];    // psi^-(N/2), the single twiddle of inverse stage 0
     ModConst h_mc[HE_MAX_MODULI];
     // device tables
     ModConst* d_mc;    // [M]
@@ -125,7 +130,11 @@ struct TransformDesc {
     const ScaleList* scale;      // inverse only: limb i is multiplied by scale[i % scale_period]
     uint32_t scale_period;       //   (must include N^-1); nullptr = plain N^-1
     const ModDownEpilogue* ep;   // forward only, or nullptr
+    bool lazy_out;               // forward only: outputs may stay unreduced (below 2^7 q) where the
+                                 // consumers' 128-bit accumulations leave room; internal buffers only
 };
+// fills w / w_sh of entry i from s (modulus index mi)
+void scale_entry(const he_ctx* c, ScaleList& sc, uint32_t i, uint32_t mi, u64 s);
 int32_t launch_transform(he_ctx* ctx, const TransformDesc& d);
 int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d);   // N = 2^16 fast path
 int32_t launch_moddown_final(he_ctx* ctx, const u64* conv, uint32_t n_jobs, const ModDownEpilogue& ep);

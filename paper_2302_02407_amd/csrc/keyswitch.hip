@@ -51,7 +51,10 @@ struct ConvBatch {
 // 30-bit halves, and so are the constants; the four partial sums of 8 products of 30-bit halves
 // stay below 2^63, so they are plain 32x32+64 multiply-add chains with no carry handling, and
 // the 128-bit sum is assembled once per output (all moduli are below 2^60).
-template <bool ONE_CHUNK>
+//
+// LAZY: outputs are left in [0, 5q) (congruent, not canonical); only for buffers whose sole consumer
+// is the N = 2^16 forward transform, whose lazy bounds absorb it.
+template <bool ONE_CHUNK, bool LAZY>
 __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const ModConst* mc, uint32_t logN) {
     __shared__ u64 s_hat[CONV_TGT_PER_BLOCK * 64];
     __shared__ uint32_t s_h0[CONV_TGT_PER_BLOCK * 8], s_h1[CONV_TGT_PER_BLOCK * 8];
@@ -104,7 +107,8 @@ __global__ __launch_bounds__(KS_THREADS) void baseconv_kernel(ConvBatch b, const
             }
             u128 sa = (u128)a00 + ((u128)(a01 + a10) << 30) + ((u128)a11 << 60);
             u128 sb = (u128)b00 + ((u128)(b01 + b10) << 30) + ((u128)b11 << 60);
-            ulonglong2 o = make_ulonglong2(barrett128(sa, q, mu, bits), barrett128(sb, q, mu, bits));
+            ulonglong2 o = LAZY ? make_ulonglong2(barrett128_lazy(sa, q, mu, bits), barrett128_lazy(sb, q, mu, bits))
+                                : make_ulonglong2(barrett128(sa, q, mu, bits), barrett128(sb, q, mu, bits));
             *reinterpret_cast<ulonglong2*>(dst + ((size_t)job.tgt_limb[t0 + tt] << logN) + n) = o;
         }
     } else {
@@ -350,8 +354,9 @@ void ks_free_tables(he_ctx* c) {
 static int32_t launch_baseconv(he_ctx* c, const ConvBatch& b, uint32_t nt_max, uint32_t ns_max) {
     dim3 grid((c->N + 2 * KS_THREADS - 1) / (2 * KS_THREADS), (nt_max + CONV_TGT_PER_BLOCK - 1) / CONV_TGT_PER_BLOCK,
               b.njobs * b.reps), block(KS_THREADS);
-    if (ns_max <= 8) hipLaunchKernelGGL(baseconv_kernel<true>, grid, block, 0, c->stream, b, c->d_mc, c->logN);
-    else hipLaunchKernelGGL(baseconv_kernel<false>, grid, block, 0, c->stream, b, c->d_mc, c->logN);
+    if (ns_max <= 8 && c->logN == 16) hipLaunchKernelGGL((baseconv_kernel<true, true>), grid, block, 0, c->stream, b, c->d_mc, c->logN);
+    else if (ns_max <= 8) hipLaunchKernelGGL((baseconv_kernel<true, false>), grid, block, 0, c->stream, b, c->d_mc, c->logN);
+    else hipLaunchKernelGGL((baseconv_kernel<false, false>), grid, block, 0, c->stream, b, c->d_mc, c->logN);
     HE_HIP(c, hipGetLastError());
     return HE_OK;
 }
@@ -385,9 +390,7 @@ static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t l
     for (uint32_t i = 0; i < L1; i++) {
         uint32_t j = i / al, lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1, sz = hi - lo;
         u64 qi = c->mod[i];
-        u64 s = h_mulmod(c->h_mc[i].ninv, c->h_up_invhat[(size_t)(j * al + (sz - 1)) * al + (i - lo)], qi);
-        sc.s[i] = s;
-        sc.s_sh[i] = h_shoup(s, qi);
+        scale_entry(c, sc, i, i, h_mulmod(c->h_mc[i].ninv, c->h_up_invhat[(size_t)(j * al + (sz - 1)) * al + (i - lo)], qi));
     }
     {
         std::vector<uint32_t> mods(cb * L1);
@@ -448,7 +451,11 @@ static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t l
             uint32_t ns = std::min(per_launch, cb - s0);
             rep.resize((size_t)ns * per_src);
             for (uint32_t s = 0; s < ns; s++) std::copy(mods.begin(), mods.end(), rep.begin() + (size_t)s * per_src);
-            int32_t rc = launch_ntt(c, raised + (size_t)s0 * per_src * N, rep.data(), ns * per_src);
+            TransformDesc t = {};
+            t.fwd = true; t.seg[0] = raised + (size_t)s0 * per_src * N; t.n_seg = 1; t.dst = raised + (size_t)s0 * per_src * N;
+            t.n = ns * per_src; t.mod_idx = rep.data();
+            t.lazy_out = true;      // raised digits are only ever multiplied into 128-bit sums of at most 8 terms
+            int32_t rc = launch_transform(c, t);
             if (rc != HE_OK) return rc;
         }
     } else {
@@ -498,9 +505,7 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
     ScaleList sc;
     for (uint32_t t = 0; t < k; t++) {
         u64 p = c->mod[c->nq + t];
-        u64 s = h_mulmod(c->h_mc[c->nq + t].ninv, c->h_dn_invhat[t], p);
-        sc.s[t] = s;
-        sc.s_sh[t] = h_shoup(s, p);
+        scale_entry(c, sc, t, c->nq + t, h_mulmod(c->h_mc[c->nq + t].ninv, c->h_dn_invhat[t], p));
     }
     {
         const uint32_t n = J * 2 * k;
@@ -542,6 +547,7 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
         for (uint32_t i = 0; i < n; i++) mods[i] = i % L1;
         TransformDesc t = {};
         t.fwd = true; t.seg[0] = conv; t.n_seg = 1; t.dst = conv; t.n = n; t.mod_idx = mods.data(); t.ep = &ep;
+        t.lazy_out = true;
         int32_t rc = launch_transform(c, t);
         if (rc != HE_OK) return rc;
     }

@@ -45,6 +45,13 @@ __device__ __forceinline__ u64 barrett128(u128 x, u64 q, u64 mu, uint32_t bits) 
     return csub(r, q);
 }
 
+// Same with the three-product quotient and no final correction: result in [0, 5q), congruent to x.
+__device__ __forceinline__ u64 barrett128_lazy(u128 x, u64 q, u64 mu, uint32_t bits) {
+    u64 x1 = (u64)(x >> (bits - 1));
+    u64 qh = mulhi64_approx(x1, mu);
+    return (u64)x - qh * q;
+}
+
 // x mod q for a single word x (any value), through the same Barrett constant.
 __device__ __forceinline__ u64 barrett64(u64 x, u64 q, u64 mu, uint32_t bits) { return barrett128((u128)x, q, mu, bits); }
 

@@ -19,7 +19,12 @@
 
 #define T16_THREADS 256
 
+// Forward outputs may stay unreduced (below 69q) when the modulus is below 2^63/552: then a sum of
+// 8 products of such a value with a canonical one still fits the 128-bit Barrett input range.
+#define LAZY_Q_MAX ((1ull << 63) / 552)
+
 struct Ntt16Args {
+    uint32_t lazy;      // forward, last pass: leave outputs unreduced where LAZY_Q_MAX allows
     u64* dst;           // limb i is written / transformed in place at dst + i*N
     const ModConst* mc;
     const u64* tw;      // [M][N] forward or inverse twiddles
@@ -112,6 +117,25 @@ __device__ __forceinline__ void inv_block4(u64 (&x)[16], const u64* __restrict__
     }
 }
 
+// Inverse stages 3, 2, 1 of the limb (the first three of the last register block); stage 0 is done by
+// the caller together with the output scaling.
+__device__ __forceinline__ void inv_block3(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh, u64 q, u64 q4) {
+#pragma unroll
+    for (int u = 3; u >= 1; u--) {
+        const int dist = 8 >> u;
+        const uint32_t base = 1u << u;
+#pragma unroll
+        for (int g = 0; g < (1 << u); g++) {
+            const u64 w = tw[base + g], w_sh = tw_sh[base + g];
+#pragma unroll
+            for (int k = 0; k < dist; k++) {
+                const int a = g * 2 * dist + k;
+                gs_bfly(x[a], x[a + dist], w, w_sh, q, q4);
+            }
+        }
+    }
+}
+
 // v mod q for v < 100q: a 7-bit quotient estimated from the top bits (never too large, at most 2
 // too small), then two conditional subtractions.
 __device__ __forceinline__ u64 reduce_small(u64 v, u64 q, uint32_t bits, uint32_t mrec) {
@@ -155,8 +179,9 @@ __device__ __forceinline__ uint32_t galois_src16(uint32_t j, uint32_t g) {
 // butterflies start so that their latency is hidden behind the arithmetic.
 template <bool WIDE, bool EPI>
 __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, const u64* tw, const u64* tw_sh, uint32_t tile,
-                                           const ModConst& m, uint32_t mrec, const ModDownEpilogue& ep, uint32_t limb) {
+                                           const ModConst& m, uint32_t mrec, const ModDownEpilogue& ep, uint32_t limb, bool lazy) {
     const u64 q = m.q, q2 = m.q2, q4 = 2 * m.q2;
+    const bool keep_lazy = !WIDE && lazy && q < LAZY_Q_MAX;
     const uint32_t blk = threadIdx.x >> 4, t = threadIdx.x & 15, b = tile * 16 + blk;
     u64* row = data + (size_t)b * 256;
     u64* s = sm + blk * 272;                            // 16 groups of 17: conflict-free both ways
@@ -193,8 +218,10 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
 #pragma unroll
     for (int j = 0; j < 16; j++) x[j] = s[17 * t + j];
     fwd_block4<WIDE>(x, tw, tw_sh, 12, 16 * b + t, q, q4);
+    if (!keep_lazy) {
 #pragma unroll
-    for (int j = 0; j < 16; j++) x[j] = WIDE ? csub(csub(csub(x[j], q4), q2), q) : reduce_small(x[j], q, m.bits, mrec);
+        for (int j = 0; j < 16; j++) x[j] = WIDE ? csub(csub(csub(x[j], q4), q2), q) : reduce_small(x[j], q, m.bits, mrec);
+    }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) s[17 * t + j] = x[j];
@@ -207,7 +234,8 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
         for (int k = 0; k < 16; k++) {
             const uint32_t e = t + 16 * k;
             // (acc - ntt) * P^-1 lazily in [0,4q), plus up to two canonical addends: below 6q
-            u64 v = shoup_lazy4(ea[k] + q - s[t + 17 * k], pinv, pinv_sh, q) + ec[k];
+            // the transform value is below 128q when left unreduced, canonical otherwise
+            u64 v = shoup_lazy4(ea[k] + (keep_lazy ? (q << 7) : q) - s[t + 17 * k], pinv, pinv_sh, q) + ec[k];
             if (has_self) v += self[e];
             out[e] = csub(csub(csub(v, q4), q2), q);
         }
@@ -239,10 +267,10 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_b_kernel(Ntt16Args a, L
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
     if (m.bits > 57) {
-        fwd_pass_b<true, EPI>(data, sm, tw, tw_sh, tile, m, 0, ep, limb);
+        fwd_pass_b<true, EPI>(data, sm, tw, tw_sh, tile, m, 0, ep, limb, false);
     } else {
         const uint32_t mrec = (1u << 24) / ((uint32_t)(m.q >> (m.bits - 8)) + 1);
-        fwd_pass_b<false, EPI>(data, sm, tw, tw_sh, tile, m, mrec, ep, limb);
+        fwd_pass_b<false, EPI>(data, sm, tw, tw_sh, tile, m, mrec, ep, limb, a.lazy != 0);
     }
 }
 
@@ -301,11 +329,20 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, L
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = sm[(t + 16 * k) * 16 + cl];
-    inv_block4(x, tw, tw_sh, 0, 0, q, q4);
-    const u64 scale = CUSTOM_SCALE ? sc.s[limb % scale_period] : m.ninv;
-    const u64 scale_sh = CUSTOM_SCALE ? sc.s_sh[limb % scale_period] : m.ninv_sh;
+    inv_block3(x, tw, tw_sh, q, q4);
+    // stage 0 (one twiddle for the whole limb) with the output scaling folded in: the sum is
+    // multiplied by the scale, the difference by scale * twiddle
+    const uint32_t si = CUSTOM_SCALE ? limb % scale_period : 0;
+    const u64 cs = CUSTOM_SCALE ? sc.s[si] : m.ninv, cs_sh = CUSTOM_SCALE ? sc.s_sh[si] : m.ninv_sh;
+    const u64 cw = CUSTOM_SCALE ? sc.w[si] : m.ninv_w, cw_sh = CUSTOM_SCALE ? sc.w_sh[si] : m.ninv_w_sh;
 #pragma unroll
-    for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(csub(shoup_lazy4(x[k], scale, scale_sh, q), q2), q);
+    for (int k = 0; k < 8; k++) {
+        const u64 X = x[k], Y = x[k + 8];
+        x[k] = shoup_lazy4(X + Y, cs, cs_sh, q);
+        x[k + 8] = shoup_lazy4((X + q4) - Y, cw, cw_sh, q);
+    }
+#pragma unroll
+    for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(csub(x[k], q2), q);
 }
 
 // ---------------------------------------------------------------- host
@@ -328,6 +365,7 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
     const bool fwd = d.fwd;
     Ntt16Args a;
     a.dst = d.dst; a.mc = ctx->d_mc;
+    a.lazy = (d.fwd && d.lazy_out) ? 1u : 0u;
     a.tw = fwd ? ctx->d_tw : ctx->d_itw;
     a.tw_sh = fwd ? ctx->d_tw_sh : ctx->d_itw_sh;
     dim3 grid(n * 16), block(T16_THREADS);
