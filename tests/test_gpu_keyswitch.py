@@ -101,6 +101,44 @@ def test_rotate_batch_matches_single_calls_and_oracle(cfg, level, n_ct, steps):
         assert (ref[(c, i)] == want).all()
 
 
+@pytest.mark.timeout(600)
+def test_config2_full_batch_as_benchmarked():
+    """Workload 2 at the size and launch configuration bench.py times: 64 uniform ciphertexts at level 23,
+    all 15 power-of-two steps through he_rotate_batch, singly and hoisted.  Every output of the two
+    modes agrees bit for bit, two runs agree (determinism), and sampled outputs equal the oracle."""
+    import torch
+    from gpu_util import dev, host, zeros
+    prm = config_params(2)
+    rng, orc, ctx, cl = _setup(prm, prm.seed)
+    N, level, B = prm.N, 23, 64
+    steps = [1 << i for i in range(15)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2)
+
+    def uniform(lead, moduli):
+        cols = [torch.randint(0, int(m), tuple(lead) + (1, N), dtype=torch.int64, device="cuda", generator=gen) for m in moduli]
+        return torch.cat(cols, dim=len(lead)).contiguous().view(torch.uint64)
+
+    keys = {s: uniform((prm.dnum, 2), prm.moduli) for s in steps}     # uniform keys: parity does not need real ones
+    for s in steps:
+        ctx.he_evk_register(ctx.galois_elt(s), keys[s])
+    cts = [uniform((2,), prm.q) for _ in range(B)]
+    out_h = [zeros(2, level + 1, N) for _ in range(B * 15)]
+    out_s = [zeros(2, level + 1, N) for _ in range(B * 15)]
+    ctx.he_rotate_batch(cts, level, steps, out_h, hoisted=True)
+    ctx.he_rotate_batch(cts, level, steps, out_s, hoisted=False)
+    torch.cuda.synchronize()
+    for a, b in zip(out_h, out_s):
+        assert torch.equal(a, b)
+    sums = [int(o.view(torch.int64).sum().item()) for o in out_h[::37]]
+    ctx.he_rotate_batch(cts, level, steps, out_h, hoisted=True)
+    torch.cuda.synchronize()
+    assert sums == [int(o.view(torch.int64).sum().item()) for o in out_h[::37]]
+    for c, i in ((0, 0), (17, 7), (63, 14)):
+        want = orc.rotate(host(cts[c]), level, orc.galois_elt(steps[i]), host(keys[steps[i]]))
+        assert (host(out_h[c * 15 + i]) == want).all(), (c, i)
+
+
 def test_wide_digits_generic_conversion_path():
     """alpha = 10 > 8 source limbs per digit: the conversion kernel's chunked path (and a 60-limb raised basis)."""
     from gpu_util import dev, host, zeros
