@@ -162,6 +162,19 @@ int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const ui
 /* AddCt: d_out = d_a + d_b on [2][level+1][N]; d_out may alias d_a or d_b. */
 int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out);
 
+/* MulCt (Section 2.1): ciphertext-ciphertext multiplication = slot-wise tensor product
+ * d0 = a0*b0, d1 = a0*b1 + a1*b0, d2 = a1*b1 followed by relinearisation of d2 with the key
+ * registered under Galois element 0 (s^2 -> s): out = (d0 + ks0, d1 + ks1).  d_a, d_b, d_out:
+ * [2][level+1][N]; d_out may alias d_a or d_b.  The level is unchanged (the caller rescales);
+ * the scale is the product of the input scales. */
+int32_t he_mulct(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out);
+/* Slot-wise affine map with constants: out_c[r] = ct_c[r]*h_mul[r] (+ h_add[r] at every position of
+ * c0; a constant polynomial has a constant NTT).  h_mul, h_add: level+1 canonical residues (host).
+ * Covers negation (q_r - 1), multiplication by an integer constant, and AddPt of a constant.
+ * d_out may alias d_ct. */
+int32_t he_affine(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const uint64_t* h_mul,
+                  const uint64_t* h_add, uint64_t* d_out);
+
 /* Rescale (Section 2.1): divide by q_level with exact rounding (half up) per coefficient and
  * drop that limb: d_ct [2][level+1][N] -> d_out [2][level][N], 1 <= level <= L. */
 int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out);

@@ -109,6 +109,14 @@ class Client:
         """evk for s' = sigma_g(s); a: uniform [dnum][nq+np][N], e: errors [dnum][N]."""
         return self.o.make_evk(self.s, automorph_signed(self.s, g), a, e)
 
+    def relin_key(self, a, e):
+        """evk for s' = s^2 (negacyclic square of the secret, exact integers)."""
+        N = self.o.N
+        full = np.convolve(self.s, self.s)                   # length 2N-1, exact in int64
+        s2 = full[:N].copy()
+        s2[:N - 1] -= full[N:]
+        return self.o.make_evk(self.s, s2, a, e)
+
     def encrypt(self, z, scale, level, a, e):
         m = encode(z, self.o.N, scale)
         return self.o.encrypt(m, self.s, a, e, level)
@@ -117,3 +125,19 @@ class Client:
         """Decrypt on limb 0 alone (valid while |Delta*z| << q_0/2) and decode."""
         ph = self.o.phase(ct, level, self.s, limbs=(0,))[0]
         return decode(centered(ph, self.o.q[0]), self.o.N, scale)
+
+    def decrypt_crt(self, ct, level, scale, limbs=2):
+        """Decrypt on the first `limbs` limbs with an exact CRT lift (for scales near or above q_0)."""
+        ph = self.o.phase(ct, level, self.s, limbs=tuple(range(limbs)))
+        qs = [self.o.q[i] for i in range(limbs)]
+        Q = 1
+        for q in qs:
+            Q *= q
+        m = np.empty(self.o.N, dtype=np.float64)
+        coef = [(Q // q) * pow(Q // q, -1, q) for q in qs]
+        for n in range(self.o.N):
+            v = sum(int(ph[i][n]) * coef[i] for i in range(limbs)) % Q
+            if v > Q // 2:
+                v -= Q
+            m[n] = float(v)
+        return decode(m, self.o.N, scale)

@@ -426,6 +426,52 @@ void orc_rescale(const orc_ctx* c, const u64* ct, uint32_t level, u64* out) {
     }
 }
 
+/* MulCt (paper Section 2.1): tensor product d0 = a0*b0, d1 = a0*b1 + a1*b0, d2 = a1*b1 (slot-wise,
+ * NTT form), then relinearisation of d2 with the key for s^2 -> s: out = (d0 + ks0, d1 + ks1).
+ * a, b, out: [2][level+1][N].  The level does not change; the caller rescales. */
+void orc_mulct(const orc_ctx* c, const u64* a, const u64* b, uint32_t level, const u64* rlk, u64* out) {
+    uint32_t N = c->N, L1 = level + 1;
+    size_t pe = (size_t)L1 * N;
+    u64* d2 = (u64*)malloc(pe * sizeof(u64));
+    u64* k0 = (u64*)malloc(pe * sizeof(u64));
+    u64* k1 = (u64*)malloc(pe * sizeof(u64));
+    for (uint32_t r = 0; r < L1; r++) {
+        u64 q = c->mod[r];
+        for (uint32_t n = 0; n < N; n++) {
+            size_t i = (size_t)r * N + n;
+            u64 a0 = a[i], a1 = a[pe + i], b0 = b[i], b1 = b[pe + i];
+            out[i] = orc_mulmod(a0, b0, q);
+            out[pe + i] = addmod(orc_mulmod(a0, b1, q), orc_mulmod(a1, b0, q), q);
+            d2[i] = orc_mulmod(a1, b1, q);
+        }
+    }
+    orc_keyswitch(c, d2, level, rlk, k0, k1);
+    for (uint32_t r = 0; r < L1; r++)
+        for (uint32_t n = 0; n < N; n++) {
+            size_t i = (size_t)r * N + n;
+            out[i] = addmod(out[i], k0[i], c->mod[r]);
+            out[pe + i] = addmod(out[pe + i], k1[i], c->mod[r]);
+        }
+    free(d2); free(k0); free(k1);
+}
+
+/* out_c[r] = ct_c[r] * mul[r]  (+ add[r] at every position of c0: a constant polynomial has a
+ * constant transform).  mul, add: canonical residues per limb.  Covers negation, multiplication by
+ * an integer constant and adding a constant to every slot. */
+void orc_affine(const orc_ctx* c, const u64* ct, uint32_t level, const u64* mul, const u64* add, u64* out) {
+    uint32_t N = c->N, L1 = level + 1;
+    for (uint32_t comp = 0; comp < 2; comp++)
+        for (uint32_t r = 0; r < L1; r++) {
+            u64 q = c->mod[r];
+            size_t off = ((size_t)comp * L1 + r) * N;
+            for (uint32_t n = 0; n < N; n++) {
+                u64 v = orc_mulmod(ct[off + n], mul[r], q);
+                if (comp == 0) v = addmod(v, add[r], q);
+                out[off + n] = v;
+            }
+        }
+}
+
 /* out = a + b on [2][level+1][N] */
 void orc_add(const orc_ctx* c, const u64* a, const u64* b, uint32_t level, u64* out) {
     uint32_t N = c->N, L1 = level + 1;

@@ -221,6 +221,27 @@ class Oracle:
         lib().orc_rescale(self._h, _p(ct), C.c_uint32(level), _p(out))
         return out
 
+    def mulct(self, a, b, level, rlk):
+        a, b, rlk = _u64(a), _u64(b), _u64(rlk)
+        assert a.shape == b.shape == (2, level + 1, self.N)
+        out = np.empty_like(a)
+        lib().orc_mulct(self._h, _p(a), _p(b), C.c_uint32(level), _p(rlk), _p(out))
+        return out
+
+    def affine(self, ct, level, mul, add):
+        """out_c[r] = ct_c[r]*mul[r] (+ add[r] on c0); mul/add are Python ints (any sign), reduced per limb."""
+        ct = _u64(ct)
+        m = np.array([int(mul[r]) % self.q[r] for r in range(level + 1)], dtype=np.uint64)
+        a = np.array([int(add[r]) % self.q[r] for r in range(level + 1)], dtype=np.uint64)
+        out = np.empty_like(ct)
+        lib().orc_affine(self._h, _p(ct), C.c_uint32(level), _p(m), _p(a), _p(out))
+        return out
+
+    @staticmethod
+    def drop_level(ct, level):
+        """Forget limb q_level (no rounding, scale unchanged): [2][level+1][N] -> [2][level][N]."""
+        return np.ascontiguousarray(_u64(ct)[:, :level, :])
+
     def add(self, a, b, level):
         a, b = _u64(a), _u64(b)
         out = np.empty_like(a)

@@ -136,7 +136,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
     // Slide_f: one ModUp of c1 shared by all taps
     std::vector<const u64*> tap_ct(taps);
     {
-        KsSrc src = {ct_in, ct_in + (size_t)L1 * N};
+        KsSrc src = {ct_in, ct_in + (size_t)L1 * N, nullptr, nullptr};
         std::vector<KsJob> jobs;
         uint32_t nb = 0;
         for (uint32_t t = 0; t < taps; t++) {
@@ -195,7 +195,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         std::vector<KsSrc> srcs(n_out);
         std::vector<KsJob> jobs(n_out);
         for (uint32_t o = 0; o < n_out; o++) {
-            srcs[o] = {cur[o], cur[o] + (size_t)level * N};
+            srcs[o] = {cur[o], cur[o] + (size_t)level * N, cur[o], cur[o] + (size_t)level * N};
             jobs[o] = {o, ras_g[s], ras_key[s], nxt[o], nxt[o] + (size_t)level * N, 1};
         }
         rc = ks_engine(ctx, lo, srcs.data(), n_out, jobs.data(), n_out);

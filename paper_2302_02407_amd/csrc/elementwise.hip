@@ -62,6 +62,42 @@ __global__ __launch_bounds__(EW_THREADS) void add_kernel(const u64* a, const u64
     out[o] = addmod(a[o], b[o], q);
 }
 
+// Tensor product of two ciphertexts (the first half of MulCt): d0 = a0*b0, d1 = a0*b1 + a1*b0,
+// d2 = a1*b1, slot-wise per limb.  grid: (N/256, level+1).
+__global__ __launch_bounds__(EW_THREADS) void tensor_kernel(const u64* __restrict__ a, const u64* __restrict__ b, u64* __restrict__ d,
+                                                            const ModConst* mc, uint32_t logN, uint32_t L1) {
+    const uint32_t n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const uint32_t limb = blockIdx.y;
+    const ModConst m = mc[limb];
+    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n, o2 = ((size_t)(limb + 2 * L1) << logN) + n;
+    const u64 a0 = a[o0], a1 = a[o1], b0 = b[o0], b1 = b[o1];
+    d[o0] = mulmod(a0, b0, m);
+    d[o1] = barrett128((u128)a0 * b1 + (u128)a1 * b0, m.q, m.mu, m.bits);
+    d[o2] = mulmod(a1, b1, m);
+}
+
+int32_t launch_tensor(he_ctx* ctx, const u64* a, const u64* b, uint32_t level, u64* d) {
+    dim3 grid(ctx->N / EW_THREADS, level + 1), block(EW_THREADS);
+    hipLaunchKernelGGL(tensor_kernel, grid, block, 0, ctx->stream, a, b, d, ctx->d_mc, ctx->logN, level + 1);
+    HE_HIP(ctx, hipGetLastError());
+    return HE_OK;
+}
+
+struct AffineArgs {
+    u64 mul[HE_MAX_MODULI], mul_sh[HE_MAX_MODULI], add[HE_MAX_MODULI];
+};
+// out_c[r] = ct_c[r] * mul[r] (+ add[r] on component 0).  grid: (N/256, 2*(level+1)).
+__global__ __launch_bounds__(EW_THREADS) void affine_kernel(const u64* __restrict__ ct, u64* __restrict__ out, AffineArgs aa,
+                                                            const ModConst* mc, uint32_t logN, uint32_t L1) {
+    const uint32_t n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const uint32_t r = blockIdx.y % L1, comp = blockIdx.y / L1;
+    const u64 q = mc[r].q;
+    const size_t o = ((size_t)blockIdx.y << logN) + n;
+    u64 v = shoup_mul(ct[o], aa.mul[r], aa.mul_sh[r], q);
+    if (comp == 0) v = addmod(v, aa.add[r], q);
+    out[o] = v;
+}
+
 int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g) {
     if (n_limbs == 0) return HE_OK;
     dim3 grid(ctx->N / EW_THREADS, n_limbs), block(EW_THREADS);
@@ -121,6 +157,23 @@ int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const ui
                        ctx->d_mc, ctx->logN, level + 1, init);
     HE_HIP(ctx, hipGetLastError());
     ctx->cnt.mac += 1;
+    return HE_OK;
+}
+
+int32_t he_affine(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const uint64_t* h_mul, const uint64_t* h_add, uint64_t* d_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_ct || !d_out || !h_mul || !h_add) return he_fail(ctx, HE_ERR_BADARG, "he_affine: null argument");
+    if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_affine: level %u above L=%u", level, ctx->nq - 1);
+    AffineArgs aa;
+    for (uint32_t r = 0; r <= level; r++) {
+        if (h_mul[r] >= ctx->mod[r] || h_add[r] >= ctx->mod[r]) return he_fail(ctx, HE_ERR_BADARG, "he_affine: constant of limb %u is not a canonical residue", r);
+        aa.mul[r] = h_mul[r];
+        aa.mul_sh[r] = h_shoup(h_mul[r], ctx->mod[r]);
+        aa.add[r] = h_add[r];
+    }
+    dim3 grid(ctx->N / EW_THREADS, 2 * (level + 1)), block(EW_THREADS);
+    hipLaunchKernelGGL(affine_kernel, grid, block, 0, ctx->stream, (const u64*)d_ct, (u64*)d_out, aa, ctx->d_mc, ctx->logN, level + 1);
+    HE_HIP(ctx, hipGetLastError());
     return HE_OK;
 }
 

@@ -102,18 +102,19 @@ uint32_t h_galois_of_step(const he_ctx* ctx, int32_t step);
 // (separate kernel on the generic path).  The launch covers J jobs x 2 components x L1 limbs:
 // limb i -> job i/(2*L1), component (i/L1)&1, limb r = i%L1;
 //   out_c[r] = (acc_c[r] - ntt) * P^-1  (+ c0[r] gathered by the Galois map of g for component 0)
-//              (+ the job's own c0[r] / c1[r], ungathered, when add_self: out = ct + Rot(ct)).
+//              (+ self_c[r], ungathered: the ciphertext itself for a rotate-and-sum step, the
+//                 tensor-product parts d0, d1 for a relinearisation).
 struct ModDownEpilogue {
     const u64* acc;      // [J][2][R][N]
     const u64* pinv;     // [nq]
     const u64* pinv_sh;
     uint32_t R, L1;
-    const u64* c0[HE_MAX_KS_JOBS];   // [L1][N] or nullptr (plain key switch)
-    const u64* c1[HE_MAX_KS_JOBS];   // [L1][N], read only when add_self
+    const u64* c0[HE_MAX_KS_JOBS];      // [L1][N] or nullptr (plain key switch)
+    const u64* self0[HE_MAX_KS_JOBS];   // [L1][N] or nullptr: added to out0 as is
+    const u64* self1[HE_MAX_KS_JOBS];   // [L1][N] or nullptr: added to out1 as is
     u64* out0[HE_MAX_KS_JOBS];
     u64* out1[HE_MAX_KS_JOBS];
     uint32_t g[HE_MAX_KS_JOBS];
-    uint8_t add_self[HE_MAX_KS_JOBS];
 };
 
 // One batched transform launch (both passes).  Limb i is read at seg[src_seg[i]] + src_limb[i]*N
@@ -143,14 +144,17 @@ int32_t launch_moddown_final(he_ctx* ctx, const u64* conv, uint32_t n_jobs, cons
 int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n);
 int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale);
 int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g);
+int32_t launch_tensor(he_ctx* ctx, const u64* a, const u64* b, uint32_t level, u64* d);   // d = [d0][d1][d2], each [level+1][N]
 int32_t launch_automorph_coef(he_ctx* ctx, const u64* in, u64* out, const uint32_t* mod_idx, uint32_t n, uint32_t g);
 
 // key switching engine (keyswitch.hip)
 int32_t ks_init_tables(he_ctx* ctx);
 void ks_free_tables(he_ctx* ctx);
 struct KsSrc {
-    const u64* c0;   // [level+1][N] or nullptr (plain key switch: nothing is added to out0)
+    const u64* c0;   // [level+1][N] or nullptr (plain key switch: nothing rotated is added to out0)
     const u64* c1;   // [level+1][N]: the polynomial that is raised and switched
+    const u64* s0;   // [level+1][N] or nullptr: addends for jobs with add_self
+    const u64* s1;
 };
 struct KsJob {
     uint32_t src;        // index into the sources
@@ -158,7 +162,7 @@ struct KsJob {
     const u64* evk;      // key used
     u64* out0;           // [level+1][N]
     u64* out1;
-    uint32_t add_self;   // out += the source ciphertext itself (rotate-and-sum step)
+    uint32_t add_self;   // out0 += src.s0, out1 += src.s1 (rotate-and-sum step, relinearisation)
 };
 // Runs every job: one ModUp per source, then inner product + ModDown per job, batched.
 int32_t ks_engine(he_ctx* ctx, uint32_t level, const KsSrc* srcs, uint32_t n_src, const KsJob* jobs, uint32_t n_jobs);

@@ -223,7 +223,8 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __
     u64 v = shoup_mul(submod(a, c, q), ep.pinv[r], ep.pinv_sh[r], q);
     const uint32_t g = ep.g[job];
     if (comp == 0 && ep.c0[job]) v = addmod(v, ep.c0[job][((size_t)r << logN) + (g == 1 ? n : galois_src_ks(n, g, logN))], q);
-    if (ep.add_self[job]) v = addmod(v, (comp ? ep.c1[job] : ep.c0[job])[((size_t)r << logN) + n], q);
+    const u64* self = comp ? ep.self1[job] : ep.self0[job];
+    if (self) v = addmod(v, self[((size_t)r << logN) + n], q);
     (comp ? ep.out1[job] : ep.out0[job])[((size_t)r << logN) + n] = v;
 }
 
@@ -537,9 +538,12 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
         ModDownEpilogue ep = {};
         ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
         for (uint32_t i = 0; i < J; i++) {
-            ep.c0[i] = srcs[jobs[i].src].c0; ep.c1[i] = srcs[jobs[i].src].c1;
+            const KsSrc& src = srcs[jobs[i].src];
+            ep.c0[i] = src.c0;
+            ep.self0[i] = jobs[i].add_self ? src.s0 : nullptr;
+            ep.self1[i] = jobs[i].add_self ? src.s1 : nullptr;
             ep.out0[i] = jobs[i].out0; ep.out1[i] = jobs[i].out1;
-            ep.g[i] = jobs[i].g; ep.add_self[i] = jobs[i].add_self ? 1 : 0;
+            ep.g[i] = jobs[i].g;
             if (ep.c0[i]) c->cnt.automorph += L1;
         }
         const uint32_t n = J * 2 * L1;
@@ -673,7 +677,7 @@ int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t
     if (rc != HE_OK) return rc;
     auto it = ctx->evk.find(galois_elt_of_key);
     if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_keyswitch: no key registered for Galois element %u", galois_elt_of_key);
-    KsSrc src = {nullptr, (const u64*)d_in};
+    KsSrc src = {nullptr, (const u64*)d_in, nullptr, nullptr};
     KsJob job = {0, 1, it->second, (u64*)d_out0, (u64*)d_out1, 0};
     return ks_engine(ctx, level, &src, 1, &job, 1);
 }
@@ -727,7 +731,7 @@ int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_c
             bool have_src = false;
             for (uint32_t s = 0; s < n_steps; s++) {
                 if (gs[s] == 1) continue;
-                if (!have_src) { srcs.push_back({ct, ct + (size_t)L1 * N}); have_src = true; }
+                if (!have_src) { srcs.push_back({ct, ct + (size_t)L1 * N, nullptr, nullptr}); have_src = true; }
                 u64* out = (u64*)h_d_out[(size_t)c * n_steps + s];
                 jobs.push_back({(uint32_t)srcs.size() - 1, gs[s], keys[s], out, out + (size_t)L1 * N, 0});
             }
@@ -739,7 +743,7 @@ int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_c
             for (uint32_t c = 0; c < n_ct; c++) {
                 const u64* ct = (const u64*)h_d_ct[c];
                 u64* out = (u64*)h_d_out[(size_t)c * n_steps + s];
-                srcs.push_back({ct, ct + (size_t)L1 * N});
+                srcs.push_back({ct, ct + (size_t)L1 * N, nullptr, nullptr});
                 jobs.push_back({(uint32_t)srcs.size() - 1, gs[s], keys[s], out, out + (size_t)L1 * N, 0});
             }
         }
@@ -774,8 +778,27 @@ int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t
     auto it = ctx->evk.find(g);
     if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_conjugate: no key registered for Galois element %u", g);
     const u64* ct = (const u64*)d_ct;
-    KsSrc src = {ct, ct + (size_t)L1 * N};
+    KsSrc src = {ct, ct + (size_t)L1 * N, nullptr, nullptr};
     KsJob job = {0, g, it->second, (u64*)d_out, (u64*)d_out + (size_t)L1 * N, 0};
+    return ks_engine(ctx, level, &src, 1, &job, 1);
+}
+
+int32_t he_mulct(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_a || !d_b || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_mulct: null argument");
+    int32_t rc = check_ks_ready(ctx, level, "he_mulct");
+    if (rc != HE_OK) return rc;
+    auto it = ctx->evk.find(0);
+    if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_mulct: no relinearisation key registered (Galois element 0)");
+    const uint32_t N = ctx->N, L1 = level + 1;
+    const size_t pe = (size_t)L1 * N, ks_e = ks_engine_ws_elems(ctx, level, 1, 1);
+    rc = he_ensure_ws(ctx, (ks_e + 3 * pe) * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    u64* d = ctx->d_ws + ks_e;      // d0, d1, d2 behind the engine's region
+    rc = launch_tensor(ctx, (const u64*)d_a, (const u64*)d_b, level, d);
+    if (rc != HE_OK) return rc;
+    KsSrc src = {nullptr, d + 2 * pe, d, d + pe};
+    KsJob job = {0, 1, it->second, (u64*)d_out, (u64*)d_out + pe, 1};
     return ks_engine(ctx, level, &src, 1, &job, 1);
 }
 

@@ -201,8 +201,9 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
         out = (comp ? ep.out1[job] : ep.out0[job]) + ((size_t)r << 16) + (size_t)b * 256;
         const u64* c0 = (comp == 0 && ep.c0[job]) ? ep.c0[job] + ((size_t)r << 16) : nullptr;
         has_c0 = c0 != nullptr;
-        has_self = ep.add_self[job] != 0;
-        self = has_self ? (comp ? ep.c1[job] : ep.c0[job]) + ((size_t)r << 16) + (size_t)b * 256 : nullptr;
+        const u64* sp = comp ? ep.self1[job] : ep.self0[job];
+        has_self = sp != nullptr;
+        self = has_self ? sp + ((size_t)r << 16) + (size_t)b * 256 : nullptr;
         const uint32_t g = ep.g[job];
 #pragma unroll
         for (int k = 0; k < 16; k++) {

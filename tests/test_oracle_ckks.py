@@ -84,3 +84,36 @@ def test_rotation_at_full_size_config2():
     # non-zero mean (-u, 0 <= u < k per coefficient); a constant-ish polynomial evaluates to
     # ~2N/pi at the slots whose root is nearest 1, so slot 0 carries ~k/2*(1+|s(zeta)|)*2N/pi/Delta.
     assert err.max() < 2e-5 and np.median(err) < 1e-7
+
+
+def test_mulct_tensor_relin_and_affine():
+    """MulCt: Dec(MulCt(Enc a, Enc b)) = a*b slot-wise, before the rescale (CRT lift at scale Delta^2)
+    and after it; affine map (negate, integer multiple, constant add) against its slot meaning."""
+    prm = toy_params(logN=5, q_bits=30, nq=6, p_bits=32, np_=2, dnum=3, scale=2.0 ** 25, hamming=8, seed=34)
+    rng = S.make_rng(34)
+    o, cl = _client(prm, rng)
+    N, level = prm.N, 5
+    za = rng.uniform(-1, 1, N // 2).astype(np.complex128)
+    zb = rng.uniform(-1, 1, N // 2).astype(np.complex128)
+    enc = lambda z: cl.encrypt(z, prm.scale, level, S.uniform_limbs(rng, prm.q[:level + 1], N)[0], S.gaussian_error(rng, N)[0])
+    ca, cb = enc(za), enc(zb)
+    rlk = cl.relin_key(S.uniform_limbs(rng, prm.moduli, N, prm.dnum), S.gaussian_error(rng, N, 3.2, prm.dnum))
+    prod = o.mulct(ca, cb, level, rlk)
+    res = o.rescale(prod, level)
+    scale = prm.scale * prm.scale / prm.q[level]
+    got = cl.decrypt(res, level - 1, scale)
+    assert np.max(np.abs(got - za * zb)) < 2e-3
+    # phase check of the relinearisation itself: Dec before rescale at scale Delta^2 with a CRT lift
+    got2 = cl.decrypt_crt(prod, level, prm.scale * prm.scale, limbs=3)
+    assert np.max(np.abs(got2 - za * zb)) < 2e-3
+    # affine: -ct, 3*ct, ct + 1.5
+    neg = o.affine(ca, level, [-1] * (level + 1), [0] * (level + 1))
+    assert np.max(np.abs(cl.decrypt(neg, level, prm.scale) + za)) < 1e-4
+    tri = o.affine(ca, level, [3] * (level + 1), [0] * (level + 1))
+    assert np.max(np.abs(cl.decrypt(tri, level, prm.scale) - 3 * za)) < 1e-4
+    k = int(round(1.5 * prm.scale))
+    plus = o.affine(ca, level, [1] * (level + 1), [k] * (level + 1))
+    assert np.max(np.abs(cl.decrypt(plus, level, prm.scale) - (za + 1.5))) < 1e-4
+    # dropping a limb keeps the message
+    low = o.drop_level(ca, level)
+    assert np.max(np.abs(cl.decrypt(low, level - 1, prm.scale) - za)) < 1e-4
