@@ -25,15 +25,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+# vector-ALU issue peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = one wave64 instruction per SIMD every
+# 4 cycles; the rate at which 32-bit integer multiplies, 64-bit adds and fp64 FMAs issue on this chip
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_rotation_n65536_hbm_traffic.md")
+VALU_FILE = os.path.join(ROOT, "profiles", "bench_rotation_n65536_valu_instructions.md")
 
 
-def measured_bytes_per_limb_pass():
-    """HBM bytes one limb pass of the transform kernels moved in the committed rocprofv3 --pmc runs
-    (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size), or None if absent."""
+def _profile_constant(path, key):
+    """A `key = integer` line of a committed rocprofv3 --pmc summary, or None if absent."""
     try:
-        for line in open(TRAFFIC_FILE):
-            if line.startswith("transform_bytes_per_limb_pass"):
+        for line in open(path):
+            if line.startswith(key):
                 return int(line.split("=")[1])
     except OSError:
         pass
@@ -135,20 +138,30 @@ def main():
     # its launches is credited an equal share
     alg_bytes = prof["transform_limb_passes"] * (2.0 * N * 8) / passes_per_transform
     achieved = alg_bytes / (prof["transform_ms"] * 1e-3) / 1e9
-    bplp = measured_bytes_per_limb_pass()
+    # per-limb-pass constants measured with rocprofv3 --pmc on this same command (profiles/)
+    bplp = _profile_constant(TRAFFIC_FILE, "transform_bytes_per_limb_pass")
+    ops = _profile_constant(VALU_FILE, "transform_valu_lane_ops_per_limb_pass")
+    t_s = prof["transform_ms"] * 1e-3
+    launches = max(1, prof["transform_launches"])
     roofline = {
         "kernel": "ntt16_* (the four passes of the N=2^16 transform, incl. the fused ModDown epilogue)",
         "bound": "hbm",
-        "achieved": round(achieved, 1),
+        "achieved": round(achieved, 1),          # algorithmic bytes (1 MiB per limb transform) / time
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": None if bplp is None else round(bplp * prof["transform_limb_passes"] / max(1, prof["transform_launches"])),
-        "algorithmic_bytes_per_launch": round(alg_bytes / max(1, prof["transform_launches"])),
+        "traffic": None if bplp is None else round(bplp * prof["transform_limb_passes"] / launches),
+        "algorithmic_bytes_per_launch": round(alg_bytes / launches),
+        "measured_GBps": None if bplp is None else round(bplp * prof["transform_limb_passes"] / t_s / 1e9, 1),
         "launches": prof["transform_launches"],
-        "avg_launch_us": round(prof["transform_ms"] * 1e3 / max(1, prof["transform_launches"]), 2),
+        "avg_launch_us": round(prof["transform_ms"] * 1e3 / launches, 2),
         "share_of_step": round(prof["transform_ms"] / ms_per_step, 3),
     }
+    if ops is not None:
+        # second roof: vector-ALU issue (64-bit modular arithmetic built from 32-bit multiplies)
+        a = ops * prof["transform_limb_passes"] / t_s / 1e12
+        roofline["alu"] = {"achieved": round(a, 2), "peak": round(ALU_PEAK_TOPS, 2), "unit": "T lane-op/s",
+                           "frac": round(a / ALU_PEAK_TOPS, 4)}
 
     extras = {
         "single_keyswitch_per_s": round(15 * B / (ms_single * 1e-3), 1),
