@@ -194,6 +194,21 @@ def main():
         conv_out = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
         ms_conv = timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, cts[0], conv_out), reps=2)
         extras["conv2d_ms"] = round(ms_conv, 3)
+        del weights, conv_out
+        # configs[4]: downsampling block, 16 -> 32 channels, stride 2: 3x3 and 1x1 CAConv (16 outputs each),
+        # one-hot merges, p(p(u)) with four ct x ct multiplies, shortcut add (constants are arbitrary here:
+        # the timing does not depend on values)
+        from paper_2302_02407_amd import block as blk
+        if 0 not in keys:
+            keys[0] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+            ctx.he_evk_register(0, keys[0])
+        w3 = [uniform_dev(torch, gen, prm.q, N) for _ in range(16 * 9)]
+        w1 = [uniform_dev(torch, gen, prm.q, N) for _ in range(16)]
+        masks = [uniform_dev(torch, gen, prm.q[:level], N) for _ in range(16)]
+        ms_blk = timed(lambda: blk.downsampling_block(ctx, 16, 32, 32, 2, level, cts[0], w3, w1, masks, masks,
+                                                      8192, [3 << 53, 3 << 55], 1 << 17), reps=2)
+        extras["downsampling_block_ms"] = round(ms_blk, 3)
+        del w3, w1, masks
 
     cpu = None
     if not args.no_cpu:

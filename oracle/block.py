@@ -1,0 +1,86 @@
+"""Downsampling residual block on the oracle.  TEST INFRASTRUCTURE ONLY.
+
+Shape of the paper's ResNet-20 first downsampling block (Section 4.1) built from the library
+operations of Section 2.1: 3x3 stride-2 CAConv (Section 3.1; stride by void packing, Section
+2.2), the n_out outputs merged into one ciphertext with one-hot channel-block plaintexts,
+the polynomial activation p(p(u)), p(u) = 1.5u - 0.5u^3, and the 1x1 stride-2 shortcut
+convolution (merged the same way) added to it.
+
+Scale plan (a reading; the paper leaves scale management to its library): with Delta = 2^40
+and 54-bit primes a ct x ct product rescales to 2^26 and would collapse on the next one, so
+the activation runs at a working scale near the prime size: the merged convolution output is
+multiplied by the integer round(q/Delta) (no level), each p is evaluated as u*(3 - u^2) with
+the factor one half carried in the scale (two levels), and the shortcut is brought onto
+exactly the resulting scale through the scale of its merge plaintexts and one integer factor.
+"""
+import numpy as np
+
+from . import conv2d as CV
+from .ckks_client import encode
+
+
+def block_scales(q, level, delta):
+    """Metadata only: (k_in, [k3 of step 1, k3 of step 2], scale of the block output, k_short,
+    scale of the shortcut's merge plaintexts)."""
+    lv = level - 2
+    k_in = int(round(q[lv] / delta))
+    s, k3 = delta * k_in, []
+    for L in (lv, lv - 2):
+        s2 = s * s / q[L]                      # scale of u^2 after its rescale
+        k3.append(int(round(3.0 * s2)))
+        s = 2.0 * s * s2 / q[L - 1]            # u*(3-u^2) = 2 p(u): halve by doubling the scale
+    k_short = int(round(s / delta))
+    return k_in, k3, s, k_short, q[level - 1] * s / (delta * k_short)
+
+
+def one_hot_masks(orc, geo, n, level, scale):
+    """Plaintext o (NTT form at `level`) is one on channel block o, zero elsewhere."""
+    mods = list(range(level + 1))
+    out = []
+    for o in range(n):
+        z = np.zeros((geo.C_a, geo.H * geo.W * geo.R))
+        z[o] = 1.0
+        out.append(orc.ntt(orc.reduce_signed(encode(z.reshape(-1).astype(np.complex128), orc.N, scale), mods), mods))
+    return out
+
+
+def merge(orc, outs, masks, level):
+    acc = None
+    for o in range(len(masks)):
+        acc = orc.ptct_mac(acc, outs[o], masks[o], level, init=(o == 0))
+    return orc.rescale(acc, level)
+
+
+def activation_step(orc, u, level, k3, rlk):
+    """u -> u*(3 - u^2): MulCt, Rescale, affine, MulCt with u one level down, Rescale."""
+    w = orc.rescale(orc.mulct(u, u, level, rlk), level)
+    w = orc.affine(w, level - 1, [-1] * level, [k3] * level)
+    return orc.rescale(orc.mulct(orc.drop_level(u, level), w, level - 1, rlk), level - 1)
+
+
+def downsampling_block(orc, g3, g1, ct, level, p3, p1, m_main, m_short, evks, rlk, k_in, k3, k_short, progress=None):
+    """Returns every stage: conv3, conv1 (lists), merged, u, a1, a2, short, out."""
+    st = {"conv3": CV.caconv(orc, g3, ct, level, p3, evks, progress=progress)}
+    st["conv1"] = CV.caconv(orc, g1, ct, level, p1, evks)
+    lv = level - 2
+    st["merged"] = merge(orc, st["conv3"], m_main, level - 1)
+    st["u"] = orc.affine(st["merged"], lv, [k_in] * (lv + 1), [0] * (lv + 1))
+    st["a1"] = activation_step(orc, st["u"], lv, k3[0], rlk)
+    st["a2"] = activation_step(orc, st["a1"], lv - 2, k3[1], rlk)
+    lo = lv - 4
+    sh = merge(orc, st["conv1"], m_short, level - 1)
+    for L in range(lv, lo, -1):
+        sh = orc.drop_level(sh, L)
+    st["short"] = orc.affine(sh, lo, [k_short] * (lo + 1), [0] * (lo + 1))
+    st["out"] = orc.add(st["a2"], st["short"], lo)
+    return st
+
+
+def block_float(x, w3, w1):
+    """float64 reference in the void-packed layout: [c_out][H][W], zero where the stride skips."""
+    keep = np.zeros((w3.shape[0],) + x.shape[1:])
+    keep[:, ::2, ::2] = 1.0
+
+    def p(v):
+        return 1.5 * v - 0.5 * v ** 3
+    return p(p(CV.conv2d_float(x, w3) * keep)) + CV.conv2d_float(x, w1) * keep

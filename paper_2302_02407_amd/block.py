@@ -1,0 +1,65 @@
+"""Downsampling residual block composed from the C-ABI calls (sequencing and buffers only).
+
+Shape of the paper's ResNet-20 first downsampling block (Section 4.1): a 3x3 stride-2
+channel-aligned convolution, the polynomial activation applied to its output, and the 1x1
+stride-2 shortcut convolution added to the result.  The stride lives in the weight
+plaintexts (void packing, Section 2.2): positions that the stride skips are multiplied by
+zero.  The n_out output ciphertexts of each convolution are brought into one ciphertext by
+multiplying output o with a plaintext that is one on channel block o and zero elsewhere and
+summing (one extra level).
+
+Every plaintext and every integer constant comes from the caller, who keeps the scale
+bookkeeping (Section 2.1: level and scale are metadata); nothing here touches a residue.
+The activation is p(p(u)), p(u) = 1.5u - 0.5u^3, evaluated as t = u*(3 - u^2) with the factor
+one half carried in the scale: two levels per application.
+"""
+import torch
+
+
+def _ct(level, N):
+    return torch.zeros((2, level + 1, N), dtype=torch.uint64, device="cuda")
+
+
+def merge_outputs(ctx, outs, masks, level):
+    """sum_o outs[o] (.) masks[o], rescaled: level -> level-1."""
+    acc = _ct(level, ctx.N)
+    for o, (ct, m) in enumerate(zip(outs, masks)):
+        ctx.he_ptct_mac(acc, ct, m, level, init=(o == 0))
+    return ctx.he_rescale(acc, level, _ct(level - 1, ctx.N))
+
+
+def activation_step(ctx, u, level, k3):
+    """u at `level` -> u*(3 - u^2) at level-2; k3 = the constant 3 at the scale of u^2 after its rescale."""
+    N = ctx.N
+    sq = ctx.he_mulct(u, u, level, _ct(level, N))
+    w = ctx.he_rescale(sq, level, _ct(level - 1, N))
+    ctx.he_affine(w, level - 1, [-1] * level, [k3] * level, w)
+    u_low = u[:, :level, :].contiguous()           # forget limb q_level (a slice, no arithmetic)
+    prod = ctx.he_mulct(u_low, w, level - 1, _ct(level - 1, N))
+    return ctx.he_rescale(prod, level - 1, _ct(level - 2, N))
+
+
+def downsampling_block(ctx, C_a, H, W, R, level, ct_in, w3, w1, masks_main, masks_short, k_in, k3, k_short,
+                       keep=False):
+    """ct_in at `level` -> block output at level-6.
+
+    w3 / w1: n_out*9 / n_out weight plaintexts at `level`; masks_*: n_out one-hot plaintexts at level-1;
+    k_in: integer that lifts the merged main path to the activation's working scale; k3: the two
+    constants of the activation steps; k_short: integer that lifts the merged shortcut to the scale
+    of the activation's output.  With keep=True returns (out, dict of every intermediate)."""
+    N, n_out = ctx.N, len(masks_main)
+    conv3 = ctx.he_conv2d(C_a, H, W, R, 3, level, w3, ct_in, [_ct(level - 1, N) for _ in range(n_out)])
+    conv1 = ctx.he_conv2d(C_a, H, W, R, 1, level, w1, ct_in, [_ct(level - 1, N) for _ in range(n_out)])
+    lv = level - 2
+    merged = merge_outputs(ctx, conv3, masks_main, level - 1)
+    u = ctx.he_affine(merged, lv, [k_in] * (lv + 1), [0] * (lv + 1), _ct(lv, N))
+    a1 = activation_step(ctx, u, lv, k3[0])
+    a2 = activation_step(ctx, a1, lv - 2, k3[1])
+    short = merge_outputs(ctx, conv1, masks_short, level - 1)
+    lo = lv - 4
+    s_low = short[:, :lo + 1, :].contiguous()
+    ctx.he_affine(s_low, lo, [k_short] * (lo + 1), [0] * (lo + 1), s_low)
+    out = ctx.he_add(a2, s_low, lo, _ct(lo, N))
+    if keep:
+        return out, {"conv3": conv3, "conv1": conv1, "merged": merged, "u": u, "a1": a1, "a2": a2, "short": s_low}
+    return out
