@@ -139,3 +139,86 @@ def conv2d_float(x, wt, stride=1):
                     w0, w1 = max(0, -dx), min(W, W - dx)
                     out[co, h0:h1, w0:w1] += wt[co, c, dy + half, dx + half] * x[c, h0 + dy:h1 + dy, w0 + dx:w1 + dx]
     return out[:, ::stride, ::stride] if stride > 1 else out
+
+
+# ---------------------------------------------------------------------------------------------
+# Replication-aligned convolution with reordered SISO (Section 3.1 "RAConv", Algorithm 2).
+#
+# Input: n_in ciphertexts in the format CAConv leaves (pi_RA): ciphertext i holds, in every one of
+# the C_a blocks, channel ch(i, r) = (i*R + r) mod c_in in replica position r.  Output: one
+# ciphertext in pi_CA whose block c' holds output channel c':
+#     out(c', h, w, r) = sum_i sum_taps Wt[c', ch(i, r), tap] * x_ch(i,r)(h+dy, w+dx),
+# i.e. for R = 1 the whole convolution and for R > 1 the partial sum over the input channels of
+# replica class r (the sum across the gap dimension belongs to gap packing, Section 3.2, and is
+# not part of Algorithm 2).
+#
+# Order of operations (Algorithm 2): MulFilter&Sum_ci first - for each tap, the products of all
+# inputs with filter plaintexts that were rotated the opposite way in advance, summed with
+# additions only - then Slide_1&Sum_f: one rotation per off-centre tap and additions (f^2-1
+# rotations in all, cost table of Section 3.1).  Reading: the single Rescale of the layer comes
+# last, after the sum (the paper fixes one level per SISO, Section 3.4, not its position);
+# rotating before the rescale divides the key-switching noise by q_l as well.
+class RAGeometry:
+    def __init__(self, N, C_a, H, W, c_in, f=3):
+        assert f % 2 == 1
+        self.N, self.C_a, self.H, self.W, self.c_in, self.f = N, C_a, H, W, c_in, f
+        slots = N // 2
+        assert slots % (C_a * H * W) == 0
+        self.R = slots // (C_a * H * W)
+        self.n_in = -(-c_in // self.R)
+        half = (f - 1) // 2
+        self.taps = [(dy, dx) for dy in range(-half, half + 1) for dx in range(-half, half + 1)]
+        self.tap_steps = [((dy * W + dx) * self.R) % slots for dy, dx in self.taps]
+
+    def in_channel(self, i, r):
+        return (i * self.R + r) % self.c_in
+
+    def filter_slots(self, wt, i, tap):
+        """The plaintext that would multiply the slid input in the usual order: Wt[c', ch(i,r), tap] at
+        slot (c', h, w, r) where the tap reads inside the image, else 0.  wt: [C_a][c_in][f][f]."""
+        dy, dx = self.taps[tap]
+        half = (self.f - 1) // 2
+        v = np.zeros((self.C_a, self.H, self.W, self.R), dtype=np.float64)
+        for r in range(self.R):
+            ci = self.in_channel(i, r)
+            for h in range(self.H):
+                if not 0 <= h + dy < self.H:
+                    continue
+                for w in range(self.W):
+                    if 0 <= w + dx < self.W:
+                        v[:, h, w, r] = wt[:, ci, dy + half, dx + half]
+        return v.reshape(-1)
+
+    def weight_slots(self, wt, i, tap):
+        """The same plaintext rotated the opposite way (Figure 'plaintexts inversely rotated'): it meets
+        the input before the rotation by the tap amount, so its entry for output slot s sits at s + step."""
+        return np.roll(self.filter_slots(wt, i, tap), self.tap_steps[tap])
+
+
+def encode_ra_weights(orc: Oracle, geo: RAGeometry, wt, level, pt_scale):
+    """uint64 [n_in][f^2][level+1][N], NTT form."""
+    mods = list(range(level + 1))
+    pts = np.empty((geo.n_in, len(geo.taps), level + 1, orc.N), dtype=np.uint64)
+    for i in range(geo.n_in):
+        for t in range(len(geo.taps)):
+            m = encode(geo.weight_slots(wt, i, t).astype(np.complex128), orc.N, pt_scale)
+            pts[i, t] = orc.ntt(orc.reduce_signed(m, mods), mods)
+    return pts
+
+
+def raconv(orc: Oracle, geo: RAGeometry, cts, level, pts, evks, keep=False):
+    """cts: n_in ciphertexts [2][level+1][N] -> one ciphertext [2][level][N]."""
+    inter = {"mac": [], "rot": []}
+    for t in range(len(geo.taps)):
+        acc = None
+        for i in range(geo.n_in):
+            acc = orc.ptct_mac(acc, cts[i], pts[i, t], level, init=(i == 0))
+        inter["mac"].append(acc)
+    total = None
+    for t, step in enumerate(geo.tap_steps):
+        term = inter["mac"][t] if step == 0 else orc.rotate(inter["mac"][t], level, orc.galois_elt(step), evks[step])
+        inter["rot"].append(term)
+        total = term if total is None else orc.add(total, term, level)
+    inter["sum"] = total
+    out = orc.rescale(total, level)
+    return (out, inter) if keep else out
