@@ -194,7 +194,12 @@ def main():
         conv_out = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
         ms_conv = timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, cts[0], conv_out), reps=2)
         extras["conv2d_ms"] = round(ms_conv, 3)
-        del weights, conv_out
+        # the layer that consumes those 8 outputs: reordered RAConv (Algorithm 2), 8 inputs x 9 taps at level 22
+        ra_w = [w[:level] for w in weights]
+        ra_out = torch.empty((2, level - 1, N), dtype=torch.uint64, device="cuda")
+        ms_ra = timed(lambda: ctx.he_raconv(32, 2, 3, level - 1, ra_w, conv_out, ra_out), reps=3)
+        extras["raconv_ms"] = round(ms_ra, 3)
+        del weights, conv_out, ra_w, ra_out
         # configs[4]: downsampling block, 16 -> 32 channels, stride 2: 3x3 and 1x1 CAConv (16 outputs each),
         # one-hot merges, p(p(u)) with four ct x ct multiplies, shortcut add (constants are arbitrary here:
         # the timing does not depend on values)

@@ -72,6 +72,19 @@ typedef struct {
     const uint64_t* const* h_d_weights; /* host array of n_out*f*f device pointers */
 } he_conv_plan;
 
+/* Operands of one replication-aligned convolution in its reordered form (Section 3.1 RAConv,
+ * Algorithm 2).  The n_in inputs are in the format CAConv leaves (every channel block holds
+ * the same image); h_d_weights[i*f*f + t] is the filter plaintext of input i and tap t,
+ * prepared rotated the opposite way to the tap (so that it can meet the input before the
+ * rotation), NTT form at `level`, [level+1][N].  Tap (dy,dx) rotates by (dy*W+dx)*R slots. */
+typedef struct {
+    uint32_t n_in;               /* number of input ciphertexts */
+    uint32_t W, R;               /* image row length and inner slot stride */
+    uint32_t f;                  /* odd filter width */
+    uint32_t level;              /* level of the inputs; the output is at level-1 */
+    const uint64_t* const* h_d_weights; /* host array of n_in*f*f device pointers */
+} he_raconv_plan;
+
 /* Create a context: ring degree 2^logN (8 <= logN <= 17), ciphertext primes q[0..nq),
  * special primes p[0..np) (np may be 0 if no key switching is used), decomposition number
  * dnum (alpha = ceil(nq/dnum) limbs per digit, needs np >= 1 for key switching).  Every
@@ -186,6 +199,14 @@ int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* 
  * h_d_ct_out[o] = device buffer [2][level][N].  Needs keys for every non-zero tap amount and
  * every rotate-and-sum amount.  Grows the context workspace on first use (allocates). */
 int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64_t* d_ct_in, uint64_t* const* h_d_ct_out);
+
+/* Replication-aligned convolution, reordered (Section 3.1; Algorithm 2): MulFilter&Sum_ci -
+ * for every tap the sum over the n_in inputs of input x inversely rotated filter plaintext
+ * (additions only) - then Slide_1&Sum_f - one rotation per off-centre tap (f^2-1 in all) and
+ * additions - then one Rescale.  h_d_ct_in[i] = device buffer [2][level+1][N]; d_ct_out
+ * [2][level][N], must not overlap an input.  Needs keys for every non-zero tap amount.
+ * Grows the context workspace on first use (allocates). */
+int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* d_ct_out);
 
 #ifdef __cplusplus
 }

@@ -173,6 +173,13 @@ class RAGeometry:
     def in_channel(self, i, r):
         return (i * self.R + r) % self.c_in
 
+    def pack_input(self, x, i):
+        """Slot vector of input ciphertext i: channel ch(i, r) of x[c_in][H][W] in replica r of every block."""
+        v = np.empty((self.C_a, self.H, self.W, self.R), dtype=np.float64)
+        for r in range(self.R):
+            v[:, :, :, r] = x[self.in_channel(i, r)][None, :, :]
+        return v.reshape(-1)
+
     def filter_slots(self, wt, i, tap):
         """The plaintext that would multiply the slid input in the usual order: Wt[c', ch(i,r), tap] at
         slot (c', h, w, r) where the tap reads inside the image, else 0.  wt: [C_a][c_in][f][f]."""

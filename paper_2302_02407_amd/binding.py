@@ -18,7 +18,7 @@ _STATUS = {0: "HE_OK", -1: "HE_ERR_BADARG", -2: "HE_ERR_LEVEL", -3: "HE_ERR_NOKE
 EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
-    "he_conjugate", "he_ptct_mac", "he_add", "he_mulct", "he_affine", "he_rescale", "he_conv2d",
+    "he_conjugate", "he_ptct_mac", "he_add", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
 ]
 
 
@@ -39,6 +39,11 @@ class Profile(C.Structure):
 class ConvPlan(C.Structure):
     _fields_ = [("C_a", C.c_uint32), ("H", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32),
                 ("n_out", C.c_uint32), ("level", C.c_uint32), ("h_d_weights", C.POINTER(C.c_void_p))]
+
+
+class RaConvPlan(C.Structure):
+    _fields_ = [("n_in", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32), ("level", C.c_uint32),
+                ("h_d_weights", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -78,6 +83,7 @@ def load():
         "he_mulct": [vp, vp, vp, u32, vp],
         "he_affine": [vp, vp, u32, u64p, u64p, vp],
         "he_conv2d": [vp, C.POINTER(ConvPlan), vp, C.POINTER(vp)],
+        "he_raconv": [vp, C.POINTER(RaConvPlan), C.POINTER(vp), vp],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -297,3 +303,20 @@ class HEContext:
         plan = ConvPlan(C_a, H, W, R, f, n_out, level, C.cast(wa, C.POINTER(C.c_void_p)))
         self._ck(self._lib.he_conv2d(self._h, C.byref(plan), _dev(ct_in), oa))
         return outs
+
+    def he_raconv(self, W, R, f, level, weights, cts_in, out):
+        """weights: list of n_in*f*f device tensors [level+1][N] (input-major); cts_in: n_in tensors
+        [2][level+1][N]; out: [2][level][N]."""
+        n_in = len(cts_in)
+        if len(weights) != n_in * f * f:
+            raise ValueError("need n_in*f*f weight plaintexts")
+        for c in cts_in:
+            _need(c, 2 * (level + 1) * self.N, "input")
+        for w in weights:
+            _need(w, (level + 1) * self.N, "weight plaintext")
+        _need(out, 2 * level * self.N, "out")
+        wa = (C.c_void_p * len(weights))(*[_dev(w).value for w in weights])
+        ia = (C.c_void_p * n_in)(*[_dev(c).value for c in cts_in])
+        plan = RaConvPlan(n_in, W, R, f, level, C.cast(wa, C.POINTER(C.c_void_p)))
+        self._ck(self._lib.he_raconv(self._h, C.byref(plan), ia, _dev(out)))
+        return out

@@ -1,6 +1,7 @@
 // Channel-aligned convolution CAConv (paper Section 3.1) assembled from Slide_f and
 // MulFilter&Sum_f (Algorithm 1), Rescale (Section 2.1) and rotate-and-sum over C_a
-// (Section 2.2), all enqueued on the context's stream with no host synchronisation.
+// (Section 2.2), and replication-aligned convolution RAConv in its reordered form
+// (Algorithm 2), all enqueued on the context's stream with no host synchronisation.
 #include <algorithm>
 
 #include "modarith.cuh"
@@ -203,4 +204,164 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         std::swap(cur, nxt);
     }
     return HE_OK;
+}
+
+// ---------------------------------------------------------------- RAConv (Algorithm 2)
+#define RA_IN_PER_LAUNCH 16
+
+struct RaMac {
+    const u64* ct[RA_IN_PER_LAUNCH];                     // input ciphertexts [2][L1][N]
+    const u64* pt[RA_IN_PER_LAUNCH * 9];                 // [input][tap] inversely rotated filter plaintexts [L1][N]
+    u64* acc[9];                                         // one accumulator ciphertext per tap
+    uint32_t n_in, n_taps, init;
+};
+
+// MulFilter&Sum_ci for up to 9 taps: every input coefficient is loaded once and multiplied into the
+// accumulator of each tap; 128-bit sums, one Barrett step per 8 inputs.  init = 0 continues from
+// the accumulators' current (canonical) contents.  grid: (N/256, L1).
+__global__ __launch_bounds__(CV_THREADS) void ra_mac9_kernel(RaMac a, const ModConst* mc, uint32_t logN, uint32_t L1) {
+    const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
+    const uint32_t limb = blockIdx.y;
+    const ModConst m = mc[limb];
+    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n;
+    u128 s0[9], s1[9];
+#pragma unroll
+    for (uint32_t t = 0; t < 9; t++) {
+        s0[t] = (!a.init && t < a.n_taps) ? a.acc[t][o0] : 0;
+        s1[t] = (!a.init && t < a.n_taps) ? a.acc[t][o1] : 0;
+    }
+    for (uint32_t i = 0; i < a.n_in; i++) {
+        if (i && (i & 7u) == 0) {
+#pragma unroll
+            for (uint32_t t = 0; t < 9; t++) {
+                s0[t] = barrett128(s0[t], m.q, m.mu, m.bits);
+                s1[t] = barrett128(s1[t], m.q, m.mu, m.bits);
+            }
+        }
+        const u64 c0 = a.ct[i][o0], c1 = a.ct[i][o1];
+#pragma unroll
+        for (uint32_t t = 0; t < 9; t++) {
+            if (t < a.n_taps) {
+                const u64 p = a.pt[i * 9 + t][o0];
+                s0[t] += (u128)c0 * p;
+                s1[t] += (u128)c1 * p;
+            }
+        }
+    }
+#pragma unroll
+    for (uint32_t t = 0; t < 9; t++) {
+        if (t < a.n_taps) {
+            a.acc[t][o0] = barrett128(s0[t], m.q, m.mu, m.bits);
+            a.acc[t][o1] = barrett128(s1[t], m.q, m.mu, m.bits);
+        }
+    }
+}
+
+struct SumList {
+    const u64* in[CV_MAX_TAPS];
+    uint32_t n;
+};
+// Sum_f: out = sum of n ciphertexts [2][L1][N] (AddCt only).  grid: (N/256, 2*L1).
+__global__ __launch_bounds__(CV_THREADS) void sum_cts_kernel(SumList l, u64* out, const ModConst* mc, uint32_t logN,
+                                                             uint32_t L1) {
+    const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
+    const uint32_t pl = blockIdx.y, limb = pl >= L1 ? pl - L1 : pl;
+    const u64 q = mc[limb].q;
+    const size_t o = ((size_t)pl << logN) + n;
+    u64 acc = l.in[0][o];
+    for (uint32_t k = 1; k < l.n; k++) acc = csub(acc + l.in[k][o], q);
+    out[o] = acc;
+}
+
+extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* d_ct_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!plan || !h_d_ct_in || !d_ct_out || !plan->h_d_weights) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: null argument");
+    const uint32_t N = ctx->N, slots = N / 2, level = plan->level, f = plan->f, taps = f * f, n_in = plan->n_in;
+    if (ctx->np == 0) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: context has no special primes");
+    if (level == 0 || level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_raconv: level %u outside 1..%u", level, ctx->nq - 1);
+    if ((f & 1u) == 0 || taps > CV_MAX_TAPS) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: filter width %u must be odd and at most 7", f);
+    if (n_in == 0) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: n_in is zero");
+    if (plan->W == 0 || plan->R == 0 || (u64)plan->W * plan->R * f > slots)
+        return he_fail(ctx, HE_ERR_BADARG, "he_raconv: row length %u x stride %u does not fit the slots", plan->W, plan->R);
+    const uint32_t L1 = level + 1;
+    std::vector<uint32_t> tap_g(taps);
+    std::vector<const u64*> tap_key(taps, nullptr);
+    const int32_t half = (int32_t)(f - 1) / 2;
+    uint32_t n_rot = 0;
+    for (uint32_t t = 0; t < taps; t++) {
+        int32_t dy = (int32_t)(t / f) - half, dx = (int32_t)(t % f) - half;
+        int64_t step = ((int64_t)dy * plan->W + dx) * plan->R;
+        step = ((step % (int64_t)slots) + slots) % slots;
+        tap_g[t] = h_galois_of_step(ctx, (int32_t)step);
+        if (tap_g[t] != 1) {
+            auto it = ctx->evk.find(tap_g[t]);
+            if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_raconv: no key for tap rotation %lld", (long long)step);
+            tap_key[t] = it->second;
+            n_rot++;
+        }
+    }
+    for (uint32_t i = 0; i < n_in; i++)
+        if (!h_d_ct_in[i]) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: input %u is null", i);
+    for (uint32_t i = 0; i < n_in * taps; i++)
+        if (!plan->h_d_weights[i]) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: weight plaintext %u is null", i);
+    // workspace: [key-switch engine region][rescale scratch][taps accumulators][n_rot rotated accumulators]
+    const size_t ct_e = (size_t)2 * L1 * N;
+    const size_t ks_e = n_rot ? ks_engine_ws_elems(ctx, level, n_rot, n_rot) : 0;
+    const size_t rs_e = rescale_ws_elems(ctx, level, 1);
+    int32_t rc = he_ensure_ws(ctx, (ks_e + rs_e + (size_t)(taps + n_rot) * ct_e) * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    u64* rs_ws = ctx->d_ws + ks_e;
+    u64* acc = rs_ws + rs_e;                              // [taps] ciphertexts at `level`
+    u64* rot = acc + (size_t)taps * ct_e;                 // [n_rot]
+
+    // MulFilter&Sum_ci: per tap, the sum over all inputs of input x inversely rotated filter
+    {
+        dim3 grid(N / CV_THREADS, L1), block(CV_THREADS);
+        for (uint32_t t0 = 0; t0 < taps; t0 += 9) {
+            for (uint32_t i0 = 0; i0 < n_in; i0 += RA_IN_PER_LAUNCH) {
+                RaMac a;
+                a.n_taps = std::min<uint32_t>(9, taps - t0);
+                a.n_in = std::min<uint32_t>(RA_IN_PER_LAUNCH, n_in - i0);
+                a.init = i0 == 0;
+                for (uint32_t t = 0; t < a.n_taps; t++) a.acc[t] = acc + (size_t)(t0 + t) * ct_e;
+                for (uint32_t i = 0; i < a.n_in; i++) {
+                    a.ct[i] = (const u64*)h_d_ct_in[i0 + i];
+                    for (uint32_t t = 0; t < a.n_taps; t++) a.pt[i * 9 + t] = (const u64*)plan->h_d_weights[(size_t)(i0 + i) * taps + t0 + t];
+                }
+                hipLaunchKernelGGL(ra_mac9_kernel, grid, block, 0, ctx->stream, a, ctx->d_mc, ctx->logN, L1);
+                HE_HIP(ctx, hipGetLastError());
+            }
+        }
+        ctx->cnt.mac += (uint64_t)taps * n_in;
+    }
+    // Slide_1&Sum_f: one rotation per off-centre tap (each accumulator is its own source), then additions
+    SumList sl;
+    sl.n = 0;
+    if (n_rot) {
+        std::vector<KsSrc> srcs;
+        std::vector<KsJob> jobs;
+        for (uint32_t t = 0; t < taps; t++) {
+            const u64* a = acc + (size_t)t * ct_e;
+            if (tap_g[t] == 1) { sl.in[sl.n++] = a; continue; }
+            u64* out = rot + (size_t)srcs.size() * ct_e;
+            jobs.push_back({(uint32_t)srcs.size(), tap_g[t], tap_key[t], out, out + (size_t)L1 * N, 0});
+            srcs.push_back({a, a + (size_t)L1 * N, nullptr, nullptr});
+            sl.in[sl.n++] = out;
+        }
+        rc = ks_engine(ctx, level, srcs.data(), (uint32_t)srcs.size(), jobs.data(), (uint32_t)jobs.size());
+        if (rc != HE_OK) return rc;
+    } else {
+        for (uint32_t t = 0; t < taps; t++) sl.in[sl.n++] = acc + (size_t)t * ct_e;
+    }
+    u64* total = acc;                                    // the sum overwrites the first accumulator (read before written per element)
+    if (sl.n > 1) {
+        hipLaunchKernelGGL(sum_cts_kernel, dim3(N / CV_THREADS, 2 * L1), dim3(CV_THREADS), 0, ctx->stream, sl, total, ctx->d_mc,
+                           ctx->logN, L1);
+        HE_HIP(ctx, hipGetLastError());
+    } else {
+        total = (u64*)sl.in[0];
+    }
+    const u64* rin = total;
+    u64* rout = (u64*)d_ct_out;
+    return rescale_batch(ctx, &rin, &rout, 1, level, rs_ws);
 }

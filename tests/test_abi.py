@@ -30,7 +30,7 @@ def test_header_functions_are_exported_and_bound():
 def test_header_compiles_as_plain_c(tmp_path):
     import subprocess
     src = tmp_path / "t.c"
-    src.write_text('#include "he_mi355x.h"\nint main(void) { he_counters_t c; he_conv_plan p; (void)c; (void)p; return HE_OK; }\n')
+    src.write_text('#include "he_mi355x.h"\nint main(void) { he_counters_t c; he_conv_plan p; he_raconv_plan r; (void)c; (void)p; (void)r; return HE_OK; }\n')
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), "-c", str(src), "-o", str(tmp_path / "t.o")])
 
 

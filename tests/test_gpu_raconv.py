@@ -1,0 +1,79 @@
+"""GPU parity for the reordered replication-aligned convolution (Algorithm 2): he_raconv against the oracle bit
+for bit, the decrypted result against a float64 convolution, and the rotation count of the paper's cost table."""
+import sys
+
+import numpy as np
+import pytest
+
+from he_inputs import sampling as S
+from he_inputs.params import config_params, toy_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, file=sys.__stdout__, flush=True)
+
+
+def _case(prm, C_a, H, W, c_in, f, level, w_std, seed):
+    from gpu_util import dev, host, zeros
+    from oracle import ckks_client as K
+    from oracle import conv2d as CV
+    from oracle.he_oracle import Oracle
+    from paper_2302_02407_amd.binding import HEContext
+    rng = S.make_rng(seed)
+    orc, ctx = Oracle.from_params(prm), HEContext.from_params(prm)
+    cl = K.Client(orc, S.ternary_secret(rng, prm.N, prm.hamming))
+    N = prm.N
+    geo = CV.RAGeometry(N, C_a, H, W, c_in, f=f)
+    x = rng.uniform(-1.0, 1.0, size=(c_in, H, W))
+    wt = rng.normal(0.0, w_std, size=(C_a, c_in, f, f))
+    steps = sorted(set(s for s in geo.tap_steps if s))
+    evks = {st: cl.rotation_key(orc.galois_elt(st), S.uniform_limbs(rng, prm.moduli, N, prm.dnum),
+                                S.gaussian_error(rng, N, prm.sigma, prm.dnum)) for st in steps}
+    cts = [cl.encrypt(geo.pack_input(x, i).astype(np.complex128), prm.scale, level,
+                      S.uniform_limbs(rng, prm.q[:level + 1], N)[0], S.gaussian_error(rng, N, prm.sigma)[0])
+           for i in range(geo.n_in)]
+    _say("raconv: encoding %d filter plaintexts" % (geo.n_in * f * f))
+    pts = CV.encode_ra_weights(orc, geo, wt, level, float(prm.q[level]))
+    _say("raconv: running the oracle")
+    want = CV.raconv(orc, geo, cts, level, pts, evks)
+    for st, k in evks.items():
+        ctx.he_evk_register(ctx.galois_elt(st), dev(k))
+    weights = [dev(pts[i, t]) for i in range(geo.n_in) for t in range(f * f)]
+    out = zeros(2, level, N)
+    ctx.he_counters_reset()
+    ctx.he_raconv(W, geo.R, f, level, weights, [dev(c) for c in cts], out)
+    cnt = ctx.he_counters()
+    got = host(out)
+    assert (got == want).all()
+    assert cnt["keyswitch"] == f * f - 1 and cnt["rescale"] == 1 and cnt["mac"] == geo.n_in * f * f
+    z = cl.decrypt(got, level - 1, prm.scale).real.reshape(C_a, H, W, geo.R)
+    ref = CV.conv2d_float(x, wt)
+    assert np.max(np.abs(z.sum(axis=-1) - ref)) < 1e-3
+    for r in range(geo.R):
+        chans = [c for c in range(c_in) if c % geo.R == r]
+        assert np.max(np.abs(z[..., r] - CV.conv2d_float(x[chans], wt[:, chans]))) < 1e-3
+
+
+def test_raconv_small_ring():
+    prm = toy_params(logN=10, q_bits=40, nq=4, p_bits=41, np_=2, dnum=2, scale=2.0 ** 30, hamming=32, seed=95)
+    _case(prm, C_a=8, H=8, W=8, c_in=8, f=3, level=3, w_std=0.2, seed=95)      # one channel per ciphertext
+    _case(prm, C_a=4, H=8, W=8, c_in=8, f=3, level=2, w_std=0.2, seed=96)      # two channels per ciphertext
+    _case(prm, C_a=8, H=8, W=8, c_in=40, f=1, level=1, w_std=0.2, seed=97)     # 1x1, 40 inputs: several launches, no rotation
+    _case(prm, C_a=8, H=8, W=8, c_in=3, f=5, level=3, w_std=0.1, seed=98)      # 25 taps: three tap groups
+
+
+@pytest.mark.timeout(900)
+def test_raconv_after_resnet20_layer():
+    """The consumer of workload 3's output: 8 ciphertexts of 2 channels each (16 channels, 32x32) at level 22
+    -> one channel-aligned ciphertext, N = 2^16."""
+    prm = config_params(3)
+    _case(prm, C_a=16, H=32, W=32, c_in=16, f=3, level=22, w_std=(2.0 / (9 * 16)) ** 0.5, seed=3)
+
+
+@pytest.mark.timeout(900)
+def test_raconv_32_inputs():
+    """One channel per ciphertext at N = 2^16: 32 inputs x 9 taps (288 filter plaintexts, two input chunks per tap)."""
+    prm = config_params(3)
+    _case(prm, C_a=32, H=32, W=32, c_in=32, f=3, level=22, w_std=(2.0 / (9 * 32)) ** 0.5, seed=5)
