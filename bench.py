@@ -199,14 +199,18 @@ def main():
         ra_out = torch.empty((2, level - 1, N), dtype=torch.uint64, device="cuda")
         ms_ra = timed(lambda: ctx.he_raconv(32, 2, 3, level - 1, ra_w, conv_out, ra_out), reps=3)
         extras["raconv_ms"] = round(ms_ra, 3)
-        del weights, conv_out, ra_w, ra_out
-        # configs[4]: downsampling block, 16 -> 32 channels, stride 2: 3x3 and 1x1 CAConv (16 outputs each),
-        # one-hot merges, p(p(u)) with four ct x ct multiplies, shortcut add (constants are arbitrary here:
-        # the timing does not depend on values)
+        # CAConv -> Square -> RAConv, the unit of the paper's fused block (Algorithm 3), level 23 -> 20
         from paper_2302_02407_amd import block as blk
         if 0 not in keys:
             keys[0] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
             ctx.he_evk_register(0, keys[0])
+        ra_w2 = [w[:level - 1] for w in weights]
+        ms_unit = timed(lambda: blk.ca_square_ra(ctx, 16, 32, 32, 2, level, cts[0], weights, ra_w2, 8192, 8), reps=2)
+        extras["ca_square_ra_ms"] = round(ms_unit, 3)
+        del weights, conv_out, ra_w, ra_out, ra_w2
+        # configs[4]: downsampling block, 16 -> 32 channels, stride 2: 3x3 and 1x1 CAConv (16 outputs each),
+        # one-hot merges, p(p(u)) with four ct x ct multiplies, shortcut add (constants are arbitrary here:
+        # the timing does not depend on values)
         w3 = [uniform_dev(torch, gen, prm.q, N) for _ in range(16 * 9)]
         w1 = [uniform_dev(torch, gen, prm.q, N) for _ in range(16)]
         masks = [uniform_dev(torch, gen, prm.q[:level], N) for _ in range(16)]

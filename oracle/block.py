@@ -84,3 +84,20 @@ def block_float(x, w3, w1):
     def p(v):
         return 1.5 * v - 0.5 * v ** 3
     return p(p(CV.conv2d_float(x, w3) * keep)) + CV.conv2d_float(x, w1) * keep
+
+
+# ---------------------------------------------------------------------------------------------
+# CAConv -> Square -> RAConv (the unit of Algorithm 3).  Algorithm 3 forwards each CAConv output
+# through Square into the RAConv accumulators as soon as it exists, to bound the number of live
+# ciphertexts; the values it computes are those of the plain sequence below (modular sums do not
+# depend on the order of accumulation).  Scale plan as above: the CAConv outputs are lifted to a
+# scale near the prime size by an integer factor before the square.
+def ca_square_ra(orc, g_ca, g_ra, ct, level, p_ca, p_ra, evks, rlk, k_in, progress=None):
+    """ct at `level` -> (output ciphertext at level-3, list of squared intermediates at level-2)."""
+    mids = CV.caconv(orc, g_ca, ct, level, p_ca, evks, progress=progress)
+    lv = level - 1
+    sq = []
+    for m in mids:
+        u = orc.affine(m, lv, [k_in] * (lv + 1), [0] * (lv + 1))
+        sq.append(orc.rescale(orc.mulct(u, u, lv, rlk), lv))
+    return CV.raconv(orc, g_ra, sq, lv - 1, p_ra, evks), sq

@@ -63,3 +63,21 @@ def downsampling_block(ctx, C_a, H, W, R, level, ct_in, w3, w1, masks_main, mask
     if keep:
         return out, {"conv3": conv3, "conv1": conv1, "merged": merged, "u": u, "a1": a1, "a2": a2, "short": s_low}
     return out
+
+
+def ca_square_ra(ctx, C_a, H, W, R, level, ct_in, w_ca, w_ra, k_in, n_mid, keep=False):
+    """CAConv -> Square -> RAConv, the unit of the paper's fused block (Algorithm 3): ct_in at `level` ->
+    one channel-aligned ciphertext at level-3.  w_ca: n_mid*9 plaintexts at `level`; w_ra: n_mid*9 inversely
+    rotated plaintexts at level-2; k_in lifts the CAConv outputs to the working scale of the square.
+    All n_mid intermediates are processed as one batch per stage (Algorithm 3 forwards them one by one
+    to save memory; the values are the same)."""
+    N = ctx.N
+    lv = level - 1
+    mids = ctx.he_conv2d(C_a, H, W, R, 3, level, w_ca, ct_in, [_ct(lv, N) for _ in range(n_mid)])
+    sq = []
+    for m in mids:
+        ctx.he_affine(m, lv, [k_in] * (lv + 1), [0] * (lv + 1), m)
+        ctx.he_mulct(m, m, lv, m)
+        sq.append(ctx.he_rescale(m, lv, _ct(lv - 1, N)))
+    out = ctx.he_raconv(W, R, 3, lv - 1, w_ra, sq, _ct(lv - 2, N))
+    return (out, sq) if keep else out

@@ -77,3 +77,61 @@ def test_raconv_32_inputs():
     """One channel per ciphertext at N = 2^16: 32 inputs x 9 taps (288 filter plaintexts, two input chunks per tap)."""
     prm = config_params(3)
     _case(prm, C_a=32, H=32, W=32, c_in=32, f=3, level=22, w_std=(2.0 / (9 * 32)) ** 0.5, seed=5)
+
+
+def _fused_case(prm, C_a, H, W, c, level, std, seed):
+    """CAConv -> Square -> RAConv (the unit of Algorithm 3) against the same sequence on the oracle and float64."""
+    from gpu_util import dev, host
+    from oracle import block as OB
+    from oracle import ckks_client as K
+    from oracle import conv2d as CV
+    from oracle.he_oracle import Oracle
+    from paper_2302_02407_amd import block as B
+    from paper_2302_02407_amd.binding import HEContext
+    rng = S.make_rng(seed)
+    orc, ctx = Oracle.from_params(prm), HEContext.from_params(prm)
+    cl = K.Client(orc, S.ternary_secret(rng, prm.N, prm.hamming))
+    N, q = prm.N, prm.q
+    g1, g2 = CV.ConvGeometry(N, C_a, H, W, c, f=3), CV.RAGeometry(N, C_a, H, W, c, f=3)
+    x, w1 = S.conv_tensors(rng, C_a, c, H, W, 3, std)
+    w2 = rng.normal(0.0, std, size=(C_a, c, 3, 3))
+    steps = sorted(set(s for s in g1.tap_steps if s) | set(g1.ras_steps))
+    evks = {st: cl.rotation_key(orc.galois_elt(st), S.uniform_limbs(rng, prm.moduli, N, prm.dnum),
+                                S.gaussian_error(rng, N, prm.sigma, prm.dnum)) for st in steps}
+    rlk = cl.relin_key(S.uniform_limbs(rng, prm.moduli, N, prm.dnum), S.gaussian_error(rng, N, prm.sigma, prm.dnum))
+    ct = cl.encrypt(g1.pack_input(x).astype(np.complex128), prm.scale, level,
+                    S.uniform_limbs(rng, q[:level + 1], N)[0], S.gaussian_error(rng, N, prm.sigma)[0])
+    k_in = int(round(q[level - 1] / prm.scale))
+    s_out = (prm.scale * k_in) ** 2 / q[level - 1]
+    p1 = CV.encode_weights(orc, g1, w1, level, float(q[level]))
+    p2 = CV.encode_ra_weights(orc, g2, w2, level - 2, float(q[level - 2]))
+    _say("fused unit: running the oracle")
+    want, want_sq = OB.ca_square_ra(orc, g1, g2, ct, level, p1, p2, evks, rlk, k_in, progress=None)
+    for st, k in evks.items():
+        ctx.he_evk_register(ctx.galois_elt(st), dev(k))
+    ctx.he_evk_register(0, dev(rlk))
+    d1 = [dev(p1[o, t]) for o in range(g1.n_out) for t in range(9)]
+    d2 = [dev(p2[i, t]) for i in range(g2.n_in) for t in range(9)]
+    out, sq = B.ca_square_ra(ctx, C_a, H, W, g1.R, level, dev(ct), d1, d2, k_in, g1.n_out, keep=True)
+    for i in range(g1.n_out):
+        assert (host(sq[i]) == want_sq[i]).all(), i
+    got = host(out)
+    assert (got == want).all()
+    ref = CV.conv2d_float(CV.conv2d_float(x, w1) ** 2, w2)
+    z = cl.decrypt_crt(got, level - 3, s_out, limbs=2).real.reshape(C_a, H, W, g1.R).sum(axis=-1)
+    err = np.max(np.abs(z - ref) / np.maximum(1.0, np.abs(ref)))
+    _say("fused unit: max |y| %.3g, worst error relative to max(1,|y|) %.3g" % (np.abs(ref).max(), err))
+    assert err < 1e-3
+
+
+def test_ca_square_ra_small_ring():
+    prm = toy_params(logN=10, q_bits=40, nq=5, p_bits=41, np_=2, dnum=3, scale=2.0 ** 30, hamming=32, seed=99)
+    _fused_case(prm, C_a=8, H=8, W=8, c=8, level=4, std=0.2, seed=99)
+    _fused_case(prm, C_a=4, H=8, W=8, c=8, level=4, std=0.2, seed=100)
+
+
+@pytest.mark.timeout(900)
+def test_ca_square_ra_resnet20_layer_pair():
+    """16 -> 16 -> 16 channels on 32x32 at N = 2^16, level 23 -> 20: 40 + 8 + 8 key switches."""
+    prm = config_params(3)
+    _fused_case(prm, C_a=16, H=32, W=32, c=16, level=23, std=(2.0 / (9 * 16)) ** 0.5, seed=6)
