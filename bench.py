@@ -50,6 +50,39 @@ def uniform_dev(torch, gen, moduli, N, lead=()):
     return torch.cat(cols, dim=len(lead)).contiguous().view(torch.uint64)
 
 
+def run_only(args, torch, ctx, prm, gen):
+    """One extra workload in isolation: configs[1] NTT round trip or configs[3] CAConv."""
+    N, level = prm.N, len(prm.q) - 1
+    if args.only == "ntt":
+        idx = list(range(level + 1)) * 16
+        data = uniform_dev(torch, gen, prm.q, N, lead=(16,))
+
+        def fn():
+            ctx.he_ntt(data, idx)
+            ctx.he_intt(data, idx)
+    else:
+        for s in sorted(set(((dy * 32 + dx) * 2) % (N // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0}
+                        | {2048, 4096, 8192, 16384}):
+            key = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+            ctx.he_evk_register(ctx.galois_elt(s), key)
+            ctx.keep = getattr(ctx, "keep", []) + [key]
+        ct = uniform_dev(torch, gen, prm.q, N, lead=(2,))
+        weights = [uniform_dev(torch, gen, prm.q, N) for _ in range(8 * 9)]
+        outs = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
+
+        def fn():
+            ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, ct, outs)
+    for _ in range(args.warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fn()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    print(json.dumps({"workload": args.only, "steps": args.steps, "warmup": args.warmup, "ms": round(ms, 4)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +91,8 @@ def main():
     ap.add_argument("--batch", type=int, default=64, help="ciphertexts per step (configs[2] names 64)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the NTT and conv2d extra measurements")
+    ap.add_argument("--only", choices=["ntt", "conv2d"], help="run just this extra workload --steps times (for profiling "
+                    "it in isolation) and print its own small JSON line instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -84,6 +119,10 @@ def main():
     calib_dst = torch.empty_like(calib_src)
     calib_dst.copy_(calib_src)
     del calib_src, calib_dst
+
+    if args.only:
+        run_only(args, torch, ctx, prm, gen)
+        return
 
     steps15 = [1 << i for i in range(15)]
     keys = {}
