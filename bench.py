@@ -61,11 +61,11 @@ def run_only(args, torch, ctx, prm, gen):
             ctx.he_ntt(data, idx)
             ctx.he_intt(data, idx)
     else:
+        held = []                                        # the library keeps pointers to the keys, not copies
         for s in sorted(set(((dy * 32 + dx) * 2) % (N // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0}
                         | {2048, 4096, 8192, 16384}):
-            key = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
-            ctx.he_evk_register(ctx.galois_elt(s), key)
-            ctx.keep = getattr(ctx, "keep", []) + [key]
+            held.append(uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2)))
+            ctx.he_evk_register(ctx.galois_elt(s), held[-1])
         ct = uniform_dev(torch, gen, prm.q, N, lead=(2,))
         weights = [uniform_dev(torch, gen, prm.q, N) for _ in range(8 * 9)]
         outs = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]

@@ -157,11 +157,13 @@ __device__ __forceinline__ void fwd_pass_a(const u64* __restrict__ src, u64* __r
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = src[(size_t)(t + 16 * k) * 256 + c];
     fwd_block4<WIDE>(x, tw, tw_sh, 0, 0, q, q4);
+    // row r of the tile sits at (r + (r >> 4)) * 16: one spare row per 16 keeps the four row groups
+    // that a wavefront reads back at once on different banks
 #pragma unroll
-    for (int k = 0; k < 16; k++) sm[(t + 16 * k) * 16 + cl] = x[k];
+    for (int k = 0; k < 16; k++) sm[(t + 17 * k) * 16 + cl] = x[k];
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 16; j++) x[j] = sm[(16 * t + j) * 16 + cl];
+    for (int j = 0; j < 16; j++) x[j] = sm[(17 * t + j) * 16 + cl];
     fwd_block4<WIDE>(x, tw, tw_sh, 4, t, q, q4);
 #pragma unroll
     for (int j = 0; j < 16; j++) dst[(size_t)(16 * t + j) * 256 + c] = x[j];
@@ -244,7 +246,7 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
 }
 
 __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_a_kernel(Ntt16Args a, LimbList ll, SrcList sl) {
-    __shared__ u64 sm[4096];
+    __shared__ u64 sm[272 * 16];
     const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
     const uint32_t mi = ll.mod[limb];
     if (mi == 0xFFu) return;
