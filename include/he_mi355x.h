@@ -5,9 +5,10 @@
  * NTT/iNTT over 64-bit RNS limbs.
  *
  * The paper (HyPHEN, arXiv 2302.02407) states the problem as sequences of RNS-CKKS
- * operations - CRot, MulPt, AddCt, Rescale (Section 2.1, Table 1), assembled into SISO
- * convolution (Algorithm 1), rotate-and-sum (Section 2.2) and channel-aligned convolution
- * CAConv (Section 3.1) - and takes the operations themselves from an RNS-CKKS library with
+ * operations - CRot, MulPt, MulCt, AddCt, Rescale (Section 2.1, Table 1), assembled into SISO
+ * convolution (Algorithm 1), rotate-and-sum (Section 2.2), channel-aligned convolution
+ * CAConv (Section 3.1) and replication-aligned convolution RAConv in its reordered form
+ * (Algorithm 2) - and takes the operations themselves from an RNS-CKKS library with
  * hybrid key switching (decomposition number dnum; Appendix, parameter sets).  Each entry
  * point below is one of those operations or one stage inside CRot.
  *
