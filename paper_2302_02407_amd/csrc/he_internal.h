@@ -115,6 +115,23 @@ struct ModDownEpilogue {
     u64* out0[HE_MAX_KS_JOBS];
     u64* out1[HE_MAX_KS_JOBS];
     uint32_t g[HE_MAX_KS_JOBS];
+    // N = 2^16 path only.  fused != 0: the q-limbs of acc are never materialised; the epilogue computes
+    // acc_c[r] = sum_j digit_j[r] (gathered by the Galois map) * evk_j,c[r] itself, digit j's own limbs
+    // taken from the switched polynomial.  beta <= 8.
+    uint32_t fused, beta, alpha, M;
+    const u64* raised[HE_MAX_KS_JOBS];  // [beta][R][N]
+    const u64* own[HE_MAX_KS_JOBS];     // [L1][N]
+    const u64* evk[HE_MAX_KS_JOBS];     // [dnum][2][M][N]
+};
+
+// Key-switch inner product of the special-prime limbs computed by the first pass of their inverse transform
+// (N = 2^16 path): limb i of the launch is job i/(2k), component (i/k)&1, special prime i%k; its input value at
+// position n is sum_j raised_j[L1 + i%k][galois(n)] * evk_j,comp[nq + i%k][n] and is never stored.  beta <= 8.
+struct IpPrologue {
+    const u64* raised[HE_MAX_KS_JOBS];  // [beta][R][N]
+    const u64* evk[HE_MAX_KS_JOBS];     // [dnum][2][M][N]
+    uint32_t g[HE_MAX_KS_JOBS];
+    uint32_t beta, R, M, L1, k, nq;
 };
 
 // One batched transform launch (both passes).  Limb i is read at seg[src_seg[i]] + src_limb[i]*N
@@ -131,6 +148,7 @@ struct TransformDesc {
     const ScaleList* scale;      // inverse only: limb i is multiplied by scale[i % scale_period]
     uint32_t scale_period;       //   (must include N^-1); nullptr = plain N^-1
     const ModDownEpilogue* ep;   // forward only, or nullptr
+    const IpPrologue* ip;        // inverse on the N = 2^16 path only, or nullptr: inputs are computed, not read
     bool lazy_out;               // forward only: outputs may stay unreduced (below 2^7 q) where the
                                  // consumers' 128-bit accumulations leave room; internal buffers only
 };

@@ -489,7 +489,15 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
             groups++;
         }
     }
-    {
+    // On the N = 2^16 path no accumulator is materialised: the special-prime limbs of the inner product are
+    // computed by the first pass of their inverse transform, the q-limbs inside the ModDown epilogue (they would
+    // only be written here and read back there).  Other rings run the stand-alone kernel.
+    const bool fused = c->logN == 16 && beta <= 8;
+    IpPrologue ip = {};
+    if (fused) {
+        ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq;
+        for (uint32_t i = 0; i < J; i++) { ip.raised[i] = raised_of[i]; ip.evk[i] = jobs[i].evk; ip.g[i] = jobs[i].g; }
+    } else {
         dim3 grid(N / KS_THREADS, R, groups), block(KS_THREADS);
         if (beta <= 4)
             hipLaunchKernelGGL(inner_product_kernel<4>, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M, level,
@@ -520,6 +528,7 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
         TransformDesc t = {};
         t.fwd = false; t.seg[0] = acc; t.n_seg = 1; t.dst = tmp_dn; t.n = n;
         t.mod_idx = mods.data(); t.src_limb = lim.data(); t.scale = &sc; t.scale_period = k;
+        t.ip = fused ? &ip : nullptr;
         int32_t rc = launch_transform(c, t);
         if (rc != HE_OK) return rc;
     }
@@ -537,8 +546,10 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
     {
         ModDownEpilogue ep = {};
         ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
+        ep.fused = fused ? 1u : 0u; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M;
         for (uint32_t i = 0; i < J; i++) {
             const KsSrc& src = srcs[jobs[i].src];
+            ep.raised[i] = raised_of[i]; ep.own[i] = src.c1; ep.evk[i] = jobs[i].evk;
             ep.c0[i] = src.c0;
             ep.self0[i] = jobs[i].add_self ? src.s0 : nullptr;
             ep.self1[i] = jobs[i].add_self ? src.s1 : nullptr;

@@ -179,7 +179,10 @@ __device__ __forceinline__ uint32_t galois_src16(uint32_t j, uint32_t g) {
 // canonical result is not stored: it feeds the ModDown epilogue, which writes the outputs.  The
 // epilogue's operands (accumulator, rotated c0, the ciphertext itself) are fetched before the
 // butterflies start so that their latency is hidden behind the arithmetic.
-template <bool WIDE, bool EPI>
+// EPI: 0 = plain transform; 1 = ModDown epilogue with the accumulator read from memory; 2 = ModDown epilogue
+// that also computes the accumulator (the key-switch inner product of this limb) from the raised digits and
+// the key, so that the q-limbs of the accumulator never exist in memory.
+template <bool WIDE, int EPI>
 __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, const u64* tw, const u64* tw_sh, uint32_t tile,
                                            const ModConst& m, uint32_t mrec, const ModDownEpilogue& ep, uint32_t limb, bool lazy) {
     const u64 q = m.q, q2 = m.q2, q4 = 2 * m.q2;
@@ -191,27 +194,32 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = row[t + 16 * k];
     // epilogue operands for the points e = t + 16k this thread will finally own
-    u64 ea[16], ec[16];
+    u64 ea[EPI == 1 ? 16 : 1], ec[EPI == 1 ? 16 : 1];
     u64* out = nullptr;
     u64 pinv = 0, pinv_sh = 0;
     bool has_c0 = false, has_self = false;
     const u64* self = nullptr;
+    const u64* c0 = nullptr;
+    uint32_t g = 1, r = 0, job = 0, comp = 0;
     if (EPI) {
-        const uint32_t pc = limb / ep.L1, r = limb - pc * ep.L1, job = pc >> 1, comp = pc & 1u;
+        const uint32_t pc = limb / ep.L1;
+        r = limb - pc * ep.L1; job = pc >> 1; comp = pc & 1u;
         pinv = ep.pinv[r]; pinv_sh = ep.pinv_sh[r];
-        const u64* acc = ep.acc + ((size_t)(pc * ep.R + r) << 16) + (size_t)b * 256;
         out = (comp ? ep.out1[job] : ep.out0[job]) + ((size_t)r << 16) + (size_t)b * 256;
-        const u64* c0 = (comp == 0 && ep.c0[job]) ? ep.c0[job] + ((size_t)r << 16) : nullptr;
+        c0 = (comp == 0 && ep.c0[job]) ? ep.c0[job] + ((size_t)r << 16) : nullptr;
         has_c0 = c0 != nullptr;
         const u64* sp = comp ? ep.self1[job] : ep.self0[job];
         has_self = sp != nullptr;
         self = has_self ? sp + ((size_t)r << 16) + (size_t)b * 256 : nullptr;
-        const uint32_t g = ep.g[job];
+        g = ep.g[job];
+        if (EPI == 1) {
+            const u64* acc = ep.acc + ((size_t)(pc * ep.R + r) << 16) + (size_t)b * 256;
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            const uint32_t e = t + 16 * k;
-            ea[k] = acc[e];
-            ec[k] = has_c0 ? c0[g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g)] : 0;
+            for (int k = 0; k < 16; k++) {
+                const uint32_t e = t + 16 * k;
+                ea[k] = acc[e];
+                ec[k] = has_c0 ? c0[g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g)] : 0;
+            }
         }
     }
     fwd_block4<WIDE>(x, tw, tw_sh, 8, b, q, q4);
@@ -229,18 +237,67 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
 #pragma unroll
     for (int j = 0; j < 16; j++) s[17 * t + j] = x[j];
     __syncthreads();
-    if (!EPI) {
+    // (acc - ntt) * P^-1 lazily in [0,4q), plus up to two canonical addends: below 6q; the transform value is
+    // below 128q when left unreduced, canonical otherwise
+    const u64 bias = keep_lazy ? (q << 7) : q;
+    if (EPI == 0) {
 #pragma unroll
         for (int k = 0; k < 16; k++) row[t + 16 * k] = s[t + 17 * k];
-    } else {
+    } else if (EPI == 1) {
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             const uint32_t e = t + 16 * k;
-            // (acc - ntt) * P^-1 lazily in [0,4q), plus up to two canonical addends: below 6q
-            // the transform value is below 128q when left unreduced, canonical otherwise
-            u64 v = shoup_lazy4(ea[k] + (keep_lazy ? (q << 7) : q) - s[t + 17 * k], pinv, pinv_sh, q) + ec[k];
+            u64 v = shoup_lazy4(ea[k] + bias - s[t + 17 * k], pinv, pinv_sh, q) + ec[k];
             if (has_self) v += self[e];
             out[e] = csub(csub(csub(v, q4), q2), q);
+        }
+    } else {
+        // digit j of limb r is the switched polynomial itself where limb r belongs to digit j, else the raised
+        // digit; four points at a time so that their loads are in flight together
+        const uint32_t beta = ep.beta, own_j = r / ep.alpha;
+        const u64* own = ep.own[job] + ((size_t)r << 16);
+        const u64* raised = ep.raised[job] + ((size_t)r << 16);
+        const u64* key = ep.evk[job] + ((size_t)(comp * ep.M + r) << 16) + (size_t)b * 256;
+        const size_t dig_stride = (size_t)ep.R << 16, key_stride = (size_t)(2 * ep.M) << 16;
+#pragma unroll
+        for (int k0 = 0; k0 < 16; k0 += 4) {
+            u128 sum[4];
+            uint32_t src[4];
+            u64 cv[4], sv[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const uint32_t e = t + 16 * (k0 + k);
+                src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
+                sum[k] = 0;
+                cv[k] = has_c0 ? c0[src[k]] : 0;
+                sv[k] = has_self ? self[e] : 0;
+            }
+            for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
+                u64 dv[4][4], kv[4][4];
+#pragma unroll
+                for (uint32_t jj = 0; jj < 4; jj++) {
+                    const uint32_t j = j0 + jj;
+                    const bool live = j < beta;
+                    const u64* dj = j == own_j ? own : raised + (live ? j : 0) * dig_stride;
+                    const u64* kj = key + (live ? j : 0) * key_stride;
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        dv[jj][k] = live ? dj[src[k]] : 0;
+                        kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
+                    }
+                }
+#pragma unroll
+                for (uint32_t jj = 0; jj < 4; jj++)
+#pragma unroll
+                    for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const uint32_t e = t + 16 * (k0 + k);
+                const u64 a = barrett128(sum[k], q, m.mu, m.bits);
+                const u64 v = shoup_lazy4(a + bias - s[e + k0 + k], pinv, pinv_sh, q) + cv[k] + sv[k];
+                out[e] = csub(csub(csub(v, q4), q2), q);
+            }
         }
     }
 }
@@ -259,7 +316,7 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_a_kernel(Ntt16Args a, L
     else fwd_pass_a<false>(src, dst, sm, tw, tw_sh, tile, m.q, 2 * m.q2);
 }
 
-template <bool EPI>
+template <int EPI>
 __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_b_kernel(Ntt16Args a, LimbList ll, RowSched rs, ModDownEpilogue ep) {
     __shared__ u64 sm[16 * 272];
     uint32_t limb, tile;
@@ -279,7 +336,10 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_b_kernel(Ntt16Args a, L
 
 // ---------------------------------------------------------------- inverse
 // Pass B (rows) first: stages 15..12 on contiguous points, exchange, stages 11..8 on strided points.
-__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, LimbList ll, SrcList sl, RowSched rs) {
+// With IP the inputs are not read: they are the key-switch inner product of the special-prime limbs, computed
+// here from the raised digits and the key (four points at a time so that their loads are in flight together).
+template <bool IP>
+__global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, LimbList ll, SrcList sl, RowSched rs, IpPrologue ip) {
     __shared__ u64 sm[16 * 272];
     uint32_t limb, tile;
     if (!row_sched_decode(rs, limb, tile)) return;
@@ -293,8 +353,48 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
     u64* out = a.dst + ((size_t)limb << 16) + (size_t)b * 256;
     u64* s = sm + blk * 272;
     u64 x[16];
+    if (!IP) {
 #pragma unroll
-    for (int k = 0; k < 16; k++) s[t + 17 * k] = in[t + 16 * k];
+        for (int k = 0; k < 16; k++) s[t + 17 * k] = in[t + 16 * k];
+    } else {
+        const uint32_t pc = limb / ip.k, tp = limb - pc * ip.k, job = pc >> 1, comp = pc & 1u;
+        const uint32_t g = ip.g[job], beta = ip.beta;
+        const u64* raised = ip.raised[job] + ((size_t)(ip.L1 + tp) << 16);
+        const u64* key = ip.evk[job] + ((size_t)(comp * ip.M + ip.nq + tp) << 16) + (size_t)b * 256;
+        const size_t dig_stride = (size_t)ip.R << 16, key_stride = (size_t)(2 * ip.M) << 16;
+#pragma unroll
+        for (int k0 = 0; k0 < 16; k0 += 4) {
+            u128 sum[4];
+            uint32_t src[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const uint32_t e = t + 16 * (k0 + k);
+                src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
+                sum[k] = 0;
+            }
+            for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
+                u64 dv[4][4], kv[4][4];
+#pragma unroll
+                for (uint32_t jj = 0; jj < 4; jj++) {
+                    const uint32_t j = j0 + jj;
+                    const bool live = j < beta;
+                    const u64* dj = raised + (live ? j : 0) * dig_stride;
+                    const u64* kj = key + (live ? j : 0) * key_stride;
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        dv[jj][k] = live ? dj[src[k]] : 0;
+                        kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
+                    }
+                }
+#pragma unroll
+                for (uint32_t jj = 0; jj < 4; jj++)
+#pragma unroll
+                    for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) s[t + 17 * (k0 + k)] = barrett128(sum[k], q, m.mu, m.bits);
+        }
+    }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) x[j] = s[17 * t + j];
@@ -396,9 +496,11 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
         }
         if (fwd && pass == 0) hipLaunchKernelGGL(ntt16_fwd_a_kernel, grid, block, 0, ctx->stream, a, ll, sl);
-        else if (fwd && d.ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<true>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
-        else if (fwd) { ModDownEpilogue none = {}; hipLaunchKernelGGL(ntt16_fwd_b_kernel<false>, grid_rows, block, 0, ctx->stream, a, ll, rs, none); }
-        else if (pass == 0) hipLaunchKernelGGL(ntt16_inv_b_kernel, grid_rows, block, 0, ctx->stream, a, ll, sl, rs);
+        else if (fwd && d.ep && d.ep->fused) hipLaunchKernelGGL(ntt16_fwd_b_kernel<2>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
+        else if (fwd && d.ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<1>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
+        else if (fwd) { ModDownEpilogue none = {}; hipLaunchKernelGGL(ntt16_fwd_b_kernel<0>, grid_rows, block, 0, ctx->stream, a, ll, rs, none); }
+        else if (pass == 0 && d.ip) hipLaunchKernelGGL(ntt16_inv_b_kernel<true>, grid_rows, block, 0, ctx->stream, a, ll, sl, rs, *d.ip);
+        else if (pass == 0) { IpPrologue none = {}; hipLaunchKernelGGL(ntt16_inv_b_kernel<false>, grid_rows, block, 0, ctx->stream, a, ll, sl, rs, none); }
         else if (d.scale) hipLaunchKernelGGL(ntt16_inv_a_kernel<true>, grid, block, 0, ctx->stream, a, ll, *d.scale, d.scale_period);
         else { ScaleList none; hipLaunchKernelGGL(ntt16_inv_a_kernel<false>, grid, block, 0, ctx->stream, a, ll, none, 1u); }
         HE_HIP(ctx, hipGetLastError());
