@@ -173,9 +173,11 @@ def main():
     step()
     prof = ctx.he_profile_end()
     passes_per_transform = 2 if prm.logN > 11 else 1
-    # algorithmic bytes: a limb transform must read and write the limb once (2*N*8 B); each of
-    # its launches is credited an equal share
-    alg_bytes = prof["transform_limb_passes"] * (2.0 * N * 8) / passes_per_transform
+    # algorithmic bytes: a limb transform must read and write the limb once (2*N*8 B), each of its
+    # launches credited an equal share; the passes that also compute the key-switch inner product
+    # must in addition read the raised digits once (N*8 B per digit limb; keys not counted)
+    alg_bytes = (prof["transform_limb_passes"] * (2.0 * N * 8) / passes_per_transform
+                 + prof["inner_product_digit_limbs"] * (N * 8.0))
     achieved = alg_bytes / (prof["transform_ms"] * 1e-3) / 1e9
     # per-limb-pass constants measured with rocprofv3 --pmc on this same command (profiles/)
     bplp = _profile_constant(TRAFFIC_FILE, "transform_bytes_per_limb_pass")
@@ -183,9 +185,9 @@ def main():
     t_s = prof["transform_ms"] * 1e-3
     launches = max(1, prof["transform_launches"])
     roofline = {
-        "kernel": "ntt16_* (the four passes of the N=2^16 transform, incl. the fused ModDown epilogue)",
+        "kernel": "ntt16_* (the four passes of the N=2^16 transform, incl. the fused inner product and ModDown epilogue)",
         "bound": "hbm",
-        "achieved": round(achieved, 1),          # algorithmic bytes (1 MiB per limb transform) / time
+        "achieved": round(achieved, 1),          # algorithmic bytes (1 MiB per limb transform + digit reads) / time
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),

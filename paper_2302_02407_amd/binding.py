@@ -33,7 +33,8 @@ class Counters(C.Structure):
 
 
 class Profile(C.Structure):
-    _fields_ = [("transform_launches", C.c_uint64), ("transform_limb_passes", C.c_uint64), ("transform_ms", C.c_double)]
+    _fields_ = [("transform_launches", C.c_uint64), ("transform_limb_passes", C.c_uint64),
+                ("inner_product_digit_limbs", C.c_uint64), ("transform_ms", C.c_double)]
 
 
 class ConvPlan(C.Structure):

@@ -244,12 +244,14 @@ int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out) {
     HE_HIP(ctx, hipStreamSynchronize(ctx->stream));
     h_out->transform_launches = 0;
     h_out->transform_limb_passes = 0;
+    h_out->inner_product_digit_limbs = 0;
     h_out->transform_ms = 0.0;
     for (auto& s : ctx->prof_events) {
         float ms = 0.f;
         HE_HIP(ctx, hipEventElapsedTime(&ms, s.e0, s.e1));
         h_out->transform_launches += 1;
         h_out->transform_limb_passes += s.limbs;
+        h_out->inner_product_digit_limbs += s.digit_limbs;
         h_out->transform_ms += ms;
         (void)hipEventDestroy(s.e0);
         (void)hipEventDestroy(s.e1);

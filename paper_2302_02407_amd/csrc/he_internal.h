@@ -43,6 +43,7 @@ struct ScaleList {
 struct ProfSpan {
     hipEvent_t e0, e1;
     uint32_t limbs;   // limbs transformed by the launch between the two events
+    uint32_t digit_limbs; // raised-digit limbs a pass that carries the key-switch inner product has to read
 };
 
 struct he_ctx {

@@ -506,7 +506,11 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
         HE_HIP(ctx, hipGetLastError());
         if (ctx->prof_on) {
             HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
-            ctx->prof_events.push_back({e0, e1, live});
+            // the two components of a job share the gathered digit limbs: beta per pair of limbs
+            uint32_t dig = 0;
+            if (!fwd && pass == 0 && d.ip) dig = d.ip->beta * (live / 2);
+            if (fwd && pass == 1 && d.ep && d.ep->fused) dig = d.ep->beta * (live / 2);
+            ctx->prof_events.push_back({e0, e1, live, dig});
         }
     }
     if (fwd) ctx->cnt.ntt_limbs += live; else ctx->cnt.intt_limbs += live;
