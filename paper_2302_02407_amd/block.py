@@ -17,7 +17,8 @@ import torch
 
 
 def _ct(level, N):
-    return torch.zeros((2, level + 1, N), dtype=torch.uint64, device="cuda")
+    """Uninitialised ciphertext buffer (every use below overwrites it completely)."""
+    return torch.empty((2, level + 1, N), dtype=torch.uint64, device="cuda")
 
 
 def merge_outputs(ctx, outs, masks, level):
