@@ -261,3 +261,35 @@ def test_mac_add_rescale(cfg, level):
     out = zeros(2, level, N)
     ctx.he_rescale(acc, level, out)
     assert (host(out) == orc.rescale(w, level)).all()
+
+
+@pytest.mark.parametrize("q_bits,nq,p_bits,np_,dnum,levels", [
+    (40, 12, 41, 1, 12, (11, 8, 5, 0)),     # alpha 1, one special prime; 12 and 9 digits take the unfused inner product
+    (50, 6, 60, 3, 2, (5, 3, 2)),           # alpha 3 with 60-bit special primes, partial and single digits
+    (57, 4, 58, 2, 2, (3, 1)),              # widest narrow-path primes (57 bits) and wide-path special primes
+])
+def test_n65536_other_decompositions(q_bits, nq, p_bits, np_, dnum, levels):
+    """The N = 2^16 kernels away from the benchmark's parameter set: other digit widths and counts (fused and
+    unfused inner product), other prime sizes (lazy-reduction bounds), rotations singly, hoisted and summed."""
+    from gpu_util import dev, host, zeros
+    prm = toy_params(logN=16, q_bits=q_bits, nq=nq, p_bits=p_bits, np_=np_, dnum=dnum, hamming=64, seed=63)
+    rng, orc, ctx, cl = _setup(prm, 63)
+    N = prm.N
+    steps = [1, 300]
+    keys = {s: _key(prm, rng, cl, orc.galois_elt(s)) for s in steps}
+    for s, k in keys.items():
+        ctx.he_evk_register(ctx.galois_elt(s), dev(k))
+    for level in levels:
+        ct = _rand_ct(prm, rng, level)
+        outs = [zeros(2, level + 1, N) for _ in steps]
+        ctx.he_rotate_hoisted(dev(ct), level, steps, outs)
+        for s, o in zip(steps, outs):
+            want = orc.rotate(ct, level, orc.galois_elt(s), keys[s])
+            assert (host(o) == want).all(), (level, s)
+        single = zeros(2, level + 1, N)
+        ctx.he_rotate(dev(ct), level, 300, single)
+        assert (host(single) == host(outs[1])).all(), level
+        o0, o1 = zeros(level + 1, N), zeros(level + 1, N)
+        ctx.he_keyswitch(dev(ct[1]), level, ctx.galois_elt(1), o0, o1)
+        w0, w1 = orc.keyswitch(ct[1], level, keys[1])
+        assert (host(o0) == w0).all() and (host(o1) == w1).all(), level
