@@ -260,6 +260,21 @@ def main():
         extras["downsampling_block_ms"] = round(ms_blk, 3)
         del w3, w1, masks
 
+    if not args.no_extras:
+        # configs[0]: tiny CAConv, N = 2^12, 4 -> 4 channels on 8x8, R = 8, level 2 (latency in microseconds)
+        prm0 = config_params(0)
+        ctx0 = HEContext.from_params(prm0)
+        N0, lv0 = prm0.N, len(prm0.q) - 1
+        keys0 = []
+        for s in sorted(set(((dy * 8 + dx) * 8) % (N0 // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0} | {512, 1024}):
+            keys0.append(uniform_dev(torch, gen, prm0.moduli, N0, lead=(prm0.dnum, 2)))
+            ctx0.he_evk_register(ctx0.galois_elt(s), keys0[-1])
+        ct0 = uniform_dev(torch, gen, prm0.q, N0, lead=(2,))
+        w0 = [uniform_dev(torch, gen, prm0.q, N0) for _ in range(9)]
+        out0 = [torch.empty((2, lv0, N0), dtype=torch.uint64, device="cuda")]
+        extras["conv2d_config0_us"] = round(1e3 * timed(lambda: ctx0.he_conv2d(4, 8, 8, 8, 3, lv0, w0, ct0, out0), reps=20), 1)
+        del ctx0
+
     cpu = None
     if not args.no_cpu:
         # the oracle as it stands, on the host cores, on a bounded sample of the same workload:

@@ -105,7 +105,7 @@ int32_t he_counters_reset(he_ctx* ctx);
 /* Timing of the transform kernels (the dominant kernels of every entry point) with a HIP event
  * pair around each launch on the context's stream.  he_profile_begin starts collecting;
  * he_profile_end synchronises the stream, sums the spans and stops.  transform_limb_passes
- * counts limbs per launch (a full NTT of one limb at N > 2^11 is two launches = two passes).
+ * counts limbs per launch (a full NTT of one limb at N > 2^12 is two launches = two passes).
  * inner_product_digit_limbs counts the raised-digit limbs that passes carrying the key-switch
  * inner product have to read besides their own limb (N = 2^16 path; 0 elsewhere). */
 typedef struct {

@@ -6,16 +6,17 @@
 // [0,4q), inverse in [0,2q)) and multiply by twiddles with Shoup's precomputed quotients;
 // only the last pass canonicalises.
 //
-// A limb of N = 2^16 coefficients (512 KiB) does not fit in one workgroup's LDS, so a
-// transform is two passes over tiles of 2^11 elements staged in LDS:
-//   pass A ("strided"): the first logN-11 stages; a tile is ROWS = 2^(logN-11) rows of
-//                       COLS = 2048/ROWS adjacent columns of the 2048-wide row-major view;
-//   pass B ("contiguous"): the last 11 stages; a tile is 2048 consecutive elements.
+// This file serves every ring size except N = 2^16 (which has its own two-launch kernels).  Rings up
+// to N = 2^12 are one pass with the whole limb (at most 32 KiB) staged in LDS; larger rings take two
+// passes over tiles of 2^12 elements:
+//   pass A ("strided"): the first logN-12 stages; a tile is ROWS = 2^(logN-12) rows of
+//                       COLS = 4096/ROWS adjacent columns of the 4096-wide row-major view;
+//   pass B ("contiguous"): the last 12 stages; a tile is 4096 consecutive elements.
 // Both passes run the same butterfly loop on the tile-local index space.
 #include "modarith.cuh"
 
-#define NTT_THREADS 256
-#define NTT_LOG_TILE_MAX 11
+#define NTT_THREADS 1024
+#define NTT_LOG_TILE_MAX 12
 
 struct NttArgs {
     u64* data;
@@ -23,7 +24,7 @@ struct NttArgs {
     const u64* tw;     // [M][N] forward or inverse table
     const u64* tw_sh;  // Shoup companions
     uint32_t logN;
-    uint32_t log_tile; // min(logN, 11)
+    uint32_t log_tile; // min(logN, 12)
     uint32_t s_begin;  // stages [s_begin, s_end) of this pass, ascending stage index
     uint32_t s_end;
     uint32_t strided;  // 1 = pass A layout, 0 = pass B layout
@@ -38,8 +39,16 @@ __device__ __forceinline__ uint32_t tile_global_index(uint32_t e, uint32_t tile,
     return (r << log_tile) + (tile << log_cols) + c;
 }
 
+// Where the first pass of a transform reads limb i: segment (limb[i] >> 12) at limb offset (limb[i] & 0xFFF);
+// the result always lands at data + i*N, and a second pass works in place there.
+struct TileSrc {
+    const u64* seg[HE_MAX_SEGS];
+    uint16_t limb[HE_MAX_LAUNCH_LIMBS];
+};
+
 template <bool FWD, bool CUSTOM_SCALE>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbList ll, ScaleList sc, uint32_t scale_period) {
+__global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbList ll, ScaleList sc, uint32_t scale_period, TileSrc ts,
+                                                               uint32_t gather) {
     __shared__ u64 sm[1u << NTT_LOG_TILE_MAX];
     const uint32_t tile_elems = 1u << a.log_tile;
     const uint32_t tiles_per_limb = 1u << (a.logN - a.log_tile);
@@ -54,8 +63,13 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbLi
     const u64* tw_sh = a.tw_sh + (size_t)mi * N;
     const uint32_t log_rows = a.logN - a.log_tile; // rows of the strided view
 
+    const u64* in = base;
+    if (gather) {
+        const uint32_t sl = ts.limb[limb];
+        in = ts.seg[sl >> 12] + (size_t)(sl & 0xFFFu) * N;
+    }
     for (uint32_t e = threadIdx.x; e < tile_elems; e += NTT_THREADS)
-        sm[e] = base[tile_global_index(e, tile, a.log_tile, log_rows, a.strided)];
+        sm[e] = in[tile_global_index(e, tile, a.log_tile, log_rows, a.strided)];
     __syncthreads();
 
     const uint32_t half = tile_elems >> 1;
@@ -114,7 +128,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_tile_kernel(NttArgs a, LimbLi
 }
 
 template <bool FWD>
-static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale, uint32_t scale_period) {
+static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale, uint32_t scale_period,
+                             const TileSrc& ts) {
     if (n == 0) return HE_OK;
     if (n > HE_MAX_LAUNCH_LIMBS) return he_fail(ctx, HE_ERR_BADARG, "transform: too many limbs in one launch");
     LimbList ll;
@@ -136,6 +151,7 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
     uint32_t sA = ctx->logN - a.log_tile; // number of strided stages
     dim3 grid(n << (ctx->logN - a.log_tile)), block(NTT_THREADS);
     // forward: pass A (stages 0..sA) then pass B; inverse: pass B then pass A
+    uint32_t gather = 1;                                 // only the first pass that runs reads the sources
     for (int pass = 0; pass < 2; pass++) {
         bool strided = FWD ? (pass == 0) : (pass == 1);
         if (strided && sA == 0) continue;
@@ -150,10 +166,12 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
         }
         if (scale)
-            hipLaunchKernelGGL((ntt_tile_kernel<FWD, true>), grid, block, 0, ctx->stream, a, ll, sc, scale_period ? scale_period : 1u);
+            hipLaunchKernelGGL((ntt_tile_kernel<FWD, true>), grid, block, 0, ctx->stream, a, ll, sc, scale_period ? scale_period : 1u, ts,
+                               gather);
         else
-            hipLaunchKernelGGL((ntt_tile_kernel<FWD, false>), grid, block, 0, ctx->stream, a, ll, sc, 1u);
+            hipLaunchKernelGGL((ntt_tile_kernel<FWD, false>), grid, block, 0, ctx->stream, a, ll, sc, 1u, ts, gather);
         HE_HIP(ctx, hipGetLastError());
+        gather = 0;
         if (ctx->prof_on) {
             HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
             ctx->prof_events.push_back({e0, e1, live, 0u});
@@ -163,23 +181,18 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
     return HE_OK;
 }
 
-// Generic ring sizes: gather the source limbs with device copies, transform in place, and run the
-// ModDown epilogue as its own kernel.
+// Generic ring sizes: the first pass reads the source limbs where they are; the ModDown epilogue runs as
+// its own kernel.
 static int32_t launch_transform_generic(he_ctx* ctx, const TransformDesc& d) {
-    const size_t N = ctx->N;
-    for (uint32_t i = 0; i < d.n;) {
-        if (d.mod_idx[i] == 0xFFu) { i++; continue; }
-        const u64* base = d.seg[d.src_seg ? d.src_seg[i] : 0];
-        uint32_t sl = d.src_limb ? d.src_limb[i] : i;
-        uint32_t j = i + 1;     // extend over a run of consecutive source limbs of the same segment
-        while (j < d.n && d.mod_idx[j] != 0xFFu && (d.src_seg ? d.src_seg[j] : 0) == (d.src_seg ? d.src_seg[i] : 0) &&
-               (d.src_limb ? d.src_limb[j] : j) == sl + (j - i)) j++;
-        if (base + (size_t)sl * N != d.dst + (size_t)i * N)
-            HE_HIP(ctx, hipMemcpyAsync(d.dst + i * N, base + (size_t)sl * N, (j - i) * N * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream));
-        i = j;
+    TileSrc ts;
+    for (uint32_t s = 0; s < HE_MAX_SEGS; s++) ts.seg[s] = s < d.n_seg ? d.seg[s] : d.seg[0];
+    for (uint32_t i = 0; i < d.n; i++) {
+        uint32_t seg = d.src_seg ? d.src_seg[i] : 0, lim = d.src_limb ? d.src_limb[i] : i;
+        if (seg >= HE_MAX_SEGS || seg >= d.n_seg || lim >= 4096) return he_fail(ctx, HE_ERR_BADARG, "transform: source limb out of range");
+        ts.limb[i] = (uint16_t)((seg << 12) | lim);
     }
-    int32_t rc = d.fwd ? run_transform<true>(ctx, d.dst, d.mod_idx, d.n, nullptr, 1)
-                       : run_transform<false>(ctx, d.dst, d.mod_idx, d.n, d.scale, d.scale_period);
+    int32_t rc = d.fwd ? run_transform<true>(ctx, d.dst, d.mod_idx, d.n, nullptr, 1, ts)
+                       : run_transform<false>(ctx, d.dst, d.mod_idx, d.n, d.scale, d.scale_period, ts);
     if (rc != HE_OK) return rc;
     if (d.fwd && d.ep) return launch_moddown_final(ctx, d.dst, d.n / (2 * d.ep->L1), *d.ep);
     return HE_OK;

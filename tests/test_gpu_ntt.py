@@ -15,7 +15,7 @@ def mods():
     return Oracle, HEContext
 
 
-@pytest.mark.parametrize("logN", [8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("logN", [8, 9, 10, 11, 12, 13, 14, 15, 17])
 def test_ntt_small_rings_all_limbs(mods, logN):
     from gpu_util import dev, host
     Oracle, HEContext = mods
