@@ -172,7 +172,7 @@ def main():
     ctx.he_profile_begin()
     step()
     prof = ctx.he_profile_end()
-    passes_per_transform = 2 if prm.logN > 11 else 1
+    passes_per_transform = 2 if prm.logN > 12 else 1
     # algorithmic bytes: a limb transform must read and write the limb once (2*N*8 B), each of its
     # launches credited an equal share; the passes that also compute the key-switch inner product
     # must in addition read the raised digits once (N*8 B per digit limb; keys not counted)
