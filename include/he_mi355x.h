@@ -146,7 +146,7 @@ int32_t he_evk_register(he_ctx* ctx, uint32_t galois_elt, const uint64_t* d_evk)
  * key registered under galois_elt_of_key.  Steps: ModUp of each digit (iNTT, fast basis
  * conversion without overflow correction, NTT), inner product with the key over
  * q_0..q_level,p_*, ModDown (conversion of the p-part without rounding term, times P^-1).
- * No automorphism is applied. */
+ * No automorphism is applied.  The outputs must not overlap the input or each other. */
 int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t galois_elt_of_key,
                      uint64_t* d_out0, uint64_t* d_out1);
 

@@ -688,6 +688,12 @@ int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t
     if (rc != HE_OK) return rc;
     auto it = ctx->evk.find(galois_elt_of_key);
     if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_keyswitch: no key registered for Galois element %u", galois_elt_of_key);
+    {
+        // the last kernel still reads the input while it writes the outputs
+        const size_t pb = (size_t)(level + 1) * ctx->N * sizeof(u64);
+        if (overlaps(d_in, pb, d_out0, pb) || overlaps(d_in, pb, d_out1, pb) || overlaps(d_out0, pb, d_out1, pb))
+            return he_fail(ctx, HE_ERR_BADARG, "he_keyswitch: the outputs overlap the input or each other");
+    }
     KsSrc src = {nullptr, (const u64*)d_in, nullptr, nullptr};
     KsJob job = {0, 1, it->second, (u64*)d_out0, (u64*)d_out1, 0};
     return ks_engine(ctx, level, &src, 1, &job, 1);

@@ -173,6 +173,10 @@ def test_counters_and_errors():
         ctx.he_rotate(ct, level, 1, ct)                     # output overlaps input
     with pytest.raises(HEError):
         ctx.he_rescale(ct, 0, out)                          # cannot rescale at level 0
+    with pytest.raises(HEError):
+        ctx.he_keyswitch(ct[1], level, ctx.galois_elt(1), ct[1], out[1])   # output 0 is the input
+    with pytest.raises(HEError):
+        ctx.he_keyswitch(ct[1], level, ctx.galois_elt(1), out[0], out[0])  # the two outputs coincide
     ctx.he_counters_reset()
     ctx.he_rotate_hoisted(ct, level, [1, 0, 1], [zeros(2, level + 1, N) for _ in range(3)])
     c = ctx.he_counters()
