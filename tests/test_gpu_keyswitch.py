@@ -297,3 +297,42 @@ def test_n65536_other_decompositions(q_bits, nq, p_bits, np_, dnum, levels):
         ctx.he_keyswitch(dev(ct[1]), level, ctx.galois_elt(1), o0, o1)
         w0, w1 = orc.keyswitch(ct[1], level, keys[1])
         assert (host(o0) == w0).all() and (host(o1) == w1).all(), level
+
+
+@pytest.mark.parametrize("cfg", ["toy", 2])
+def test_extreme_residues(cfg):
+    """Worst cases for the lazy-reduction and 128-bit accumulation bounds: every residue of the ciphertext and of
+    the key at m-1, at 0/m-1 alternating, and a ciphertext that is zero except for one coefficient; transforms,
+    a hoisted rotation and a rescale must still equal the oracle bit for bit."""
+    from gpu_util import dev, host, zeros
+    prm = toy_params(logN=9, q_bits=30, nq=6, p_bits=32, np_=2, dnum=3, hamming=16, seed=64) if cfg == "toy" else config_params(cfg)
+    rng, orc, ctx, cl = _setup(prm, 64)
+    N, L1 = prm.N, len(prm.q)
+    level = L1 - 1
+    top = np.array(prm.moduli, dtype=np.uint64) - np.uint64(1)
+    key = np.broadcast_to(top[None, None, :, None], (prm.dnum, 2, len(prm.moduli), N)).copy()
+    key[:, :, :, 1::3] = 0
+    g = orc.galois_elt(7)
+    ctx.he_evk_register(g, dev(key))
+    qtop = top[:L1]
+    full = np.broadcast_to(qtop[None, :, None], (2, L1, N)).copy()
+    alt = full.copy()
+    alt[:, :, ::2] = 0
+    spike = np.zeros((2, L1, N), dtype=np.uint64)
+    spike[:, :, N - 1] = qtop[None, :]
+    idx = list(range(L1)) * 2
+    for name, ct in (("full", full), ("alternating", alt), ("spike", spike)):
+        d = dev(ct.reshape(2 * L1, N))
+        ctx.he_ntt(d, idx)
+        assert (host(d) == orc.ntt(ct.reshape(2 * L1, N), idx)).all(), name
+        ctx.he_intt(d, idx)
+        assert (host(d) == ct.reshape(2 * L1, N)).all(), name
+        d = dev(ct.reshape(2 * L1, N))
+        ctx.he_intt(d, idx)
+        assert (host(d) == orc.intt(ct.reshape(2 * L1, N), idx)).all(), name
+        out = zeros(2, L1, N)
+        ctx.he_rotate(dev(ct), level, 7, out)
+        assert (host(out) == orc.rotate(ct, level, g, key)).all(), name
+        res = zeros(2, level, N)
+        ctx.he_rescale(dev(ct), level, res)
+        assert (host(res) == orc.rescale(ct, level)).all(), name
