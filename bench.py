@@ -248,6 +248,7 @@ def main():
         ra_w2 = [w[:level - 1] for w in weights]
         ms_unit = timed(lambda: blk.ca_square_ra(ctx, 16, 32, 32, 2, level, cts[0], weights, ra_w2, 8192, 8), reps=2)
         extras["ca_square_ra_ms"] = round(ms_unit, 3)
+        conv_weights_h = weights if not args.no_cpu else None
         del weights, conv_out, ra_w, ra_out, ra_w2
         # configs[4]: downsampling block, 16 -> 32 channels, stride 2: 3x3 and 1x1 CAConv (16 outputs each),
         # one-hot merges, p(p(u)) with four ct x ct multiplies, shortcut add (constants are arbitrary here:
@@ -295,6 +296,20 @@ def main():
         dt_cpu = time.perf_counter() - t0
         cpu = {"value": round(30 * n_ct / dt_cpu, 3), "unit": "keyswitch/s", "cores": num_threads(), "kind": "oracle",
                "sample": "%d ciphertexts x 15 steps, singly + hoisted (%d key switches, %.1f s)" % (n_ct, 30 * n_ct, dt_cpu)}
+        if not args.no_extras:
+            # the other workloads of the line above, once each on the oracle
+            from oracle import conv2d as ocv
+            a_h = np.stack([c.cpu().numpy().reshape(2 * L1, N) for c in cts[:8]]).reshape(16 * L1, N)
+            idx_h = list(range(L1)) * 16
+            t0 = time.perf_counter()
+            orc.intt(orc.ntt(a_h, idx_h), idx_h)
+            cpu["ntt_roundtrip_ms"] = round((time.perf_counter() - t0) * 1e3, 1)
+            geo = ocv.ConvGeometry(N, 16, 32, 32, 16)
+            ev = {st: keys[st].cpu().numpy() for st in set(geo.tap_steps) | set(geo.ras_steps) if st}
+            pts = np.stack([w.cpu().numpy() for w in conv_weights_h]).reshape(8, 9, L1, N)
+            t0 = time.perf_counter()
+            ocv.caconv(orc, geo, cts_h[0], level, pts, ev)
+            cpu["conv2d_ms"] = round((time.perf_counter() - t0) * 1e3, 1)
 
     out = {
         "metric": "HRot keyswitches/s", "value": round(value, 1), "unit": "keyswitch/s", "n_gpus": 1,
