@@ -177,6 +177,16 @@ def test_counters_and_errors():
         ctx.he_keyswitch(ct[1], level, ctx.galois_elt(1), ct[1], out[1])   # output 0 is the input
     with pytest.raises(HEError):
         ctx.he_keyswitch(ct[1], level, ctx.galois_elt(1), out[0], out[0])  # the two outputs coincide
+    # empty batches are no-ops
+    ctx.he_counters_reset()
+    ctx.he_rotate_hoisted(ct, level, [], [])
+    ctx.he_rotate_batch([], level, [1], [])
+    ctx.he_rotate_batch([ct], level, [], [], hoisted=False)
+    assert ctx.he_counters()["keyswitch"] == 0 and ctx.he_counters()["modup"] == 0
+    # only the zero step: plain copies, no key switch
+    cp = zeros(2, level + 1, N)
+    ctx.he_rotate_hoisted(ct, level, [0], [cp])
+    assert (cp == ct).all() and ctx.he_counters()["keyswitch"] == 0
     ctx.he_counters_reset()
     ctx.he_rotate_hoisted(ct, level, [1, 0, 1], [zeros(2, level + 1, N) for _ in range(3)])
     c = ctx.he_counters()
