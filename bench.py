@@ -224,6 +224,19 @@ def main():
         extras["ntt_roundtrip_ms"] = round(ms_rt, 4)
         extras["ntt_limb_GBps"] = round(384 * N * 8 * 2 * 2 / (ms_rt * 1e-3) / 1e9, 1)
         del data
+        # the streaming operations on one ciphertext at level 23, as GB/s of the bytes they must move
+        ct_bytes = 2 * L1 * N * 8
+        pt = uniform_dev(torch, gen, prm.q, N)
+        acc = torch.empty_like(cts[0])
+        ms = timed(lambda: ctx.he_ptct_mac(acc, cts[0], pt, level, False), reps=20)
+        extras["ptct_mac_GBps"] = round((3 * ct_bytes + ct_bytes // 2) / (ms * 1e-3) / 1e9, 1)     # acc r+w, ct r, pt r
+        ms = timed(lambda: ctx.he_automorph(cts[0].view(2 * L1, N), acc.view(2 * L1, N), list(range(L1)) * 2, 5, True), reps=20)
+        extras["automorph_GBps"] = round(2 * ct_bytes / (ms * 1e-3) / 1e9, 1)
+        ms = timed(lambda: ctx.he_add(cts[0], cts[1 % B], level, acc), reps=20)
+        extras["add_GBps"] = round(3 * ct_bytes / (ms * 1e-3) / 1e9, 1)
+        res = torch.empty((2, level, N), dtype=torch.uint64, device="cuda")
+        extras["rescale_us"] = round(1e3 * timed(lambda: ctx.he_rescale(cts[0], level, res), reps=20), 1)
+        del pt, acc, res
         # configs[3]: ResNet-20-shaped CAConv, 16 -> 16 channels on 32x32, R = 2, level 23
         conv_steps = sorted(set(((dy * 32 + dx) * 2) % (N // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0}
                             | {2048, 4096, 8192, 16384})
