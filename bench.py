@@ -253,8 +253,15 @@ def main():
         ra_out = torch.empty((2, level - 1, N), dtype=torch.uint64, device="cuda")
         ms_ra = timed(lambda: ctx.he_raconv(32, 2, 3, level - 1, ra_w, conv_out, ra_out), reps=3)
         extras["raconv_ms"] = round(ms_ra, 3)
-        # CAConv -> Square -> RAConv, the unit of the paper's fused block (Algorithm 3), level 23 -> 20
+        # sum across the gap and re-replication after that RAConv (two channels per ciphertext): 2 rotations,
+        # one mask multiplication, one rescale, level 21 -> 20
         from paper_2302_02407_amd import block as blk
+        for s in (1, N // 2 - 1):
+            if s not in keys:
+                keys[s] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+                ctx.he_evk_register(ctx.galois_elt(s), keys[s])
+        extras["gap_sum_replicate_ms"] = round(timed(lambda: blk.gap_sum_replicate(ctx, ra_out, level - 2, 2, ra_w[0]), reps=3), 3)
+        # CAConv -> Square -> RAConv, the unit of the paper's fused block (Algorithm 3), level 23 -> 20
         if 0 not in keys:
             keys[0] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
             ctx.he_evk_register(0, keys[0])

@@ -101,3 +101,35 @@ def ca_square_ra(orc, g_ca, g_ra, ct, level, p_ca, p_ra, evks, rlk, k_in, progre
         u = orc.affine(m, lv, [k_in] * (lv + 1), [0] * (lv + 1))
         sq.append(orc.rescale(orc.mulct(u, u, lv, rlk), lv))
     return CV.raconv(orc, g_ra, sq, lv - 1, p_ra, evks), sq
+
+
+# ---------------------------------------------------------------------------------------------
+# Sum across the gap dimension and re-replication after RAConv when each input ciphertext carried
+# R > 1 channels (cost table of Section 3.1: RaS_g and IR_g, log2(m) rotations each; Section 3.4:
+# one level for the multiplication with the mask).  RAConv leaves, in replica position r of every
+# pixel, the partial sum over the input channels of class r.  RaS_g: w += Rot(w, 2^t), t < log2 R,
+# gathers the total into position r = 0; a plaintext that is one at r = 0 and zero elsewhere
+# (MulPt, Rescale) removes what the other positions picked up from neighbouring pixels; IR_g:
+# w += Rot(w, -2^t) copies the total back into positions 1..R-1.  The result is a channel-aligned
+# ciphertext with R equal replicas: the input format of the next CAConv.
+def gap_mask(orc, geo, level, scale):
+    z = np.zeros((geo.C_a * geo.H * geo.W, geo.R))
+    z[:, 0] = 1.0
+    mods = list(range(level + 1))
+    return orc.ntt(orc.reduce_signed(encode(z.reshape(-1).astype(np.complex128), orc.N, scale), mods), mods)
+
+
+def gap_sum_replicate(orc, ct, level, R, mask, evks):
+    """ct [2][level+1][N] -> [2][level][N]; evks: slot-step -> key for steps 2^t and N/2 - 2^t, t < log2 R."""
+    slots = orc.N // 2
+    w = ct
+    t = 1
+    while t < R:
+        w = orc.add(w, orc.rotate(w, level, orc.galois_elt(t), evks[t]), level)
+        t <<= 1
+    w = orc.rescale(orc.ptct_mac(None, w, mask, level, init=True), level)
+    t = 1
+    while t < R:
+        w = orc.add(w, orc.rotate(w, level - 1, orc.galois_elt(slots - t), evks[slots - t]), level - 1)
+        t <<= 1
+    return w

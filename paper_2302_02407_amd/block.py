@@ -82,3 +82,25 @@ def ca_square_ra(ctx, C_a, H, W, R, level, ct_in, w_ca, w_ra, k_in, n_mid, keep=
         sq.append(ctx.he_rescale(m, lv, _ct(lv - 1, N)))
     out = ctx.he_raconv(W, R, 3, lv - 1, w_ra, sq, _ct(lv - 2, N))
     return (out, sq) if keep else out
+
+
+def gap_sum_replicate(ctx, ct, level, R, mask):
+    """After RAConv with R > 1 channels per input ciphertext: sum the R partial results of every pixel
+    (log2 R rotations towards position 0), keep position 0 (MulPt with `mask`, Rescale), copy it back into
+    the other R-1 positions (log2 R rotations the other way).  ct at `level` -> level-1, channel-aligned with
+    R equal replicas (the input format of the next CAConv).  Needs keys for steps 2^t and N/2 - 2^t."""
+    N, slots = ctx.N, ctx.N // 2
+    w = ct
+    t = 1
+    while t < R:
+        rot = ctx.he_rotate(w, level, t, _ct(level, N))
+        w = ctx.he_add(w, rot, level, rot)
+        t <<= 1
+    acc = ctx.he_ptct_mac(_ct(level, N), w, mask, level, True)
+    w = ctx.he_rescale(acc, level, _ct(level - 1, N))
+    t = 1
+    while t < R:
+        rot = ctx.he_rotate(w, level - 1, slots - t, _ct(level - 1, N))
+        w = ctx.he_add(w, rot, level - 1, rot)
+        t <<= 1
+    return w

@@ -135,3 +135,64 @@ def test_ca_square_ra_resnet20_layer_pair():
     """16 -> 16 -> 16 channels on 32x32 at N = 2^16, level 23 -> 20: 40 + 8 + 8 key switches."""
     prm = config_params(3)
     _fused_case(prm, C_a=16, H=32, W=32, c=16, level=23, std=(2.0 / (9 * 16)) ** 0.5, seed=6)
+
+
+def _cycle_case(prm, C_a, H, W, c, level, std, seed):
+    """CAConv -> RAConv -> sum across the gap and re-replication: one full turn of the two data formats, every
+    stage bit-exact against the oracle, the decrypted result equal to the replicated packing of conv(conv(x))."""
+    from gpu_util import dev, host, zeros
+    from oracle import block as OB
+    from oracle import ckks_client as K
+    from oracle import conv2d as CV
+    from oracle.he_oracle import Oracle
+    from paper_2302_02407_amd import block as B
+    from paper_2302_02407_amd.binding import HEContext
+    rng = S.make_rng(seed)
+    orc, ctx = Oracle.from_params(prm), HEContext.from_params(prm)
+    cl = K.Client(orc, S.ternary_secret(rng, prm.N, prm.hamming))
+    N, q, slots = prm.N, prm.q, prm.N // 2
+    g1, g2 = CV.ConvGeometry(N, C_a, H, W, c, f=3), CV.RAGeometry(N, C_a, H, W, c, f=3)
+    R = g2.R
+    gap_steps = [s for t in range(R.bit_length() - 1) for s in (1 << t, slots - (1 << t))]
+    x, w1 = S.conv_tensors(rng, C_a, c, H, W, 3, std)
+    w2 = rng.normal(0.0, std, size=(C_a, c, 3, 3))
+    steps = sorted(set(s for s in g1.tap_steps if s) | set(g1.ras_steps) | set(gap_steps))
+    evks = {st: cl.rotation_key(orc.galois_elt(st), S.uniform_limbs(rng, prm.moduli, N, prm.dnum),
+                                S.gaussian_error(rng, N, prm.sigma, prm.dnum)) for st in steps}
+    ct = cl.encrypt(g1.pack_input(x).astype(np.complex128), prm.scale, level,
+                    S.uniform_limbs(rng, q[:level + 1], N)[0], S.gaussian_error(rng, N, prm.sigma)[0])
+    p1 = CV.encode_weights(orc, g1, w1, level, float(q[level]))
+    p2 = CV.encode_ra_weights(orc, g2, w2, level - 1, float(q[level - 1]))
+    mask = OB.gap_mask(orc, g2, level - 2, float(q[level - 2]))
+    _say("cycle: running the oracle")
+    w_mid = CV.caconv(orc, g1, ct, level, p1, evks)
+    w_ra = CV.raconv(orc, g2, w_mid, level - 1, p2, evks)
+    w_fin = OB.gap_sum_replicate(orc, w_ra, level - 2, R, mask, evks)
+    for st, k in evks.items():
+        ctx.he_evk_register(ctx.galois_elt(st), dev(k))
+    mids = ctx.he_conv2d(C_a, H, W, R, 3, level, [dev(p1[o, t]) for o in range(g1.n_out) for t in range(9)], dev(ct),
+                         [zeros(2, level, N) for _ in range(g1.n_out)])
+    for o in range(g1.n_out):
+        assert (host(mids[o]) == w_mid[o]).all(), o
+    ra = ctx.he_raconv(W, R, 3, level - 1, [dev(p2[i, t]) for i in range(g2.n_in) for t in range(9)], mids, zeros(2, level - 1, N))
+    assert (host(ra) == w_ra).all()
+    fin = B.gap_sum_replicate(ctx, ra, level - 2, R, dev(mask))
+    got = host(fin)
+    assert (got == w_fin).all()
+    ref = CV.conv2d_float(CV.conv2d_float(x, w1), w2)
+    err = np.max(np.abs(cl.decrypt(got, level - 3, prm.scale).real - g1.pack_input(ref)))
+    _say("cycle: max |dec - packed conv(conv(x))| = %.3g" % err)
+    assert err < 1e-3
+
+
+def test_format_cycle_small_ring():
+    prm = toy_params(logN=10, q_bits=40, nq=5, p_bits=41, np_=2, dnum=3, scale=2.0 ** 30, hamming=32, seed=101)
+    _cycle_case(prm, C_a=4, H=8, W=8, c=8, level=4, std=0.2, seed=101)       # two channels per ciphertext
+    _cycle_case(prm, C_a=2, H=8, W=8, c=8, level=4, std=0.2, seed=102)       # four: two rotations each way
+
+
+@pytest.mark.timeout(900)
+def test_format_cycle_resnet20_layers():
+    """16 -> 16 -> 16 channels on 32x32 with a 2x duplicate, N = 2^16, level 23 -> 20."""
+    prm = config_params(3)
+    _cycle_case(prm, C_a=16, H=32, W=32, c=16, level=23, std=(2.0 / (9 * 16)) ** 0.5, seed=7)

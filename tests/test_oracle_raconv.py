@@ -69,3 +69,29 @@ def test_reordered_equals_usual_order():
     assert np.max(np.abs(usual - cl.decrypt(out, 1, prm.scale))) < 1e-4
     # the count the paper gives: f^2-1 rotations for the reordered form against n_in*(f^2-1)
     assert sum(1 for s in g2.tap_steps if s) == 8
+
+
+def test_gap_sum_and_replication_closes_the_cycle():
+    """CAConv -> RAConv with two channels per ciphertext -> sum across the gap and re-replication: the result is
+    the channel-aligned, replicated packing of conv(conv(x)), i.e. a valid input of the next CAConv."""
+    from oracle import block as OB
+    prm = toy_params(logN=10, q_bits=40, nq=5, p_bits=41, np_=2, dnum=3, scale=2.0 ** 30, hamming=32, seed=101)
+    rng = S.make_rng(101)
+    orc = Oracle.from_params(prm)
+    cl = K.Client(orc, S.ternary_secret(rng, prm.N, prm.hamming))
+    N, q, slots = prm.N, prm.q, prm.N // 2
+    C_a, H, W, c, level = 4, 8, 8, 8, 4
+    g1, g2 = CV.ConvGeometry(N, C_a, H, W, c, f=3), CV.RAGeometry(N, C_a, H, W, c, f=3)
+    assert g2.R == 2
+    x, w1 = S.conv_tensors(rng, C_a, c, H, W, 3, 0.2)
+    w2 = rng.normal(0.0, 0.2, size=(C_a, c, 3, 3))
+    steps = sorted(set(s for s in g1.tap_steps if s) | set(g1.ras_steps) | {1, slots - 1})
+    evks = {st: cl.rotation_key(orc.galois_elt(st), S.uniform_limbs(rng, prm.moduli, N, prm.dnum),
+                                S.gaussian_error(rng, N, prm.sigma, prm.dnum)) for st in steps}
+    ct = cl.encrypt(g1.pack_input(x).astype(np.complex128), prm.scale, level,
+                    S.uniform_limbs(rng, q[:level + 1], N)[0], S.gaussian_error(rng, N, prm.sigma)[0])
+    mid = CV.caconv(orc, g1, ct, level, CV.encode_weights(orc, g1, w1, level, float(q[level])), evks)
+    out = CV.raconv(orc, g2, mid, level - 1, CV.encode_ra_weights(orc, g2, w2, level - 1, float(q[level - 1])), evks)
+    fin = OB.gap_sum_replicate(orc, out, level - 2, g2.R, OB.gap_mask(orc, g2, level - 2, float(q[level - 2])), evks)
+    ref = CV.conv2d_float(CV.conv2d_float(x, w1), w2)
+    assert np.max(np.abs(cl.decrypt(fin, level - 3, prm.scale).real - g1.pack_input(ref))) < 1e-3
