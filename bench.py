@@ -204,6 +204,14 @@ def main():
         roofline["alu"] = {"achieved": round(a, 2), "peak": round(ALU_PEAK_TOPS, 2), "unit": "T lane-op/s",
                            "frac": round(a / ALU_PEAK_TOPS, 4)}
 
+    # the whole key switch against the HBM roof: compulsory bytes of one key switch with its own key =
+    # input 24 + key 192 + outputs 48 limbs of N*8 B (what a fully fused pipeline would have to move)
+    ks_bytes = (L1 + 2 * prm.dnum * (L1 + k) + 2 * L1) * N * 8
+    roofline["keyswitch"] = {
+        "compulsory_bytes": ks_bytes,
+        "frac_single": round(15 * B / (ms_single * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
+        "frac_hoisted": round(15 * B / (ms_hoisted * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
+    }
     extras = {
         "single_keyswitch_per_s": round(15 * B / (ms_single * 1e-3), 1),
         "hoisted_keyswitch_per_s": round(15 * B / (ms_hoisted * 1e-3), 1),
