@@ -4,7 +4,10 @@
 //   ModUp   : digit limbs -> coefficient form (iNTT with the factor (Q_j/q_i)^-1 folded into
 //             the N^-1 scaling) -> fast basis conversion to every other limb of
 //             {q_0..q_l, p_*} (128-bit accumulation, one Barrett step) -> NTT.
-//   inner   : acc_c[r] = sum_j sigma_g(raised_j)[r] * evk_j,c[r]   (sigma_g as a gather).
+//   inner   : acc_c[r] = sum_j sigma_g(raised_j)[r] * evk_j,c[r]   (sigma_g as a gather).  At N = 2^16 this
+//             sum is evaluated inside the transforms of ModDown that consume it (special-prime limbs as
+//             the first inverse pass loads its rows, q-limbs in the epilogue of the last forward pass)
+//             and acc is never stored; other ring sizes run the stand-alone kernels below.
 //   ModDown : p-limbs -> coefficient form (iNTT with (P/p_t)^-1 folded in) -> conversion to
 //             q_0..q_l -> NTT -> (acc - conv) * P^-1 (+ sigma_g(c0) for a rotation).
 // Neither conversion corrects the overflow multiple; each term is a canonical residue and
