@@ -482,6 +482,16 @@ void orc_add(const orc_ctx* c, const u64* a, const u64* b, uint32_t level, u64* 
         }
 }
 
+/* AddPt (Section 2.1): the plaintext is added to c0 slot-wise per limb; c1 is copied. */
+void orc_addpt(const orc_ctx* c, const u64* ct, const u64* pt, uint32_t level, u64* out) {
+    uint32_t N = c->N, L1 = level + 1;
+    for (uint32_t r = 0; r < L1; r++)
+        for (uint32_t n = 0; n < N; n++) {
+            out[(size_t)r * N + n] = addmod(ct[(size_t)r * N + n], pt[(size_t)r * N + n], c->mod[r]);
+            out[((size_t)L1 + r) * N + n] = ct[((size_t)L1 + r) * N + n];
+        }
+}
+
 /* ---------------------------------------------------------------- client side (tests only) */
 
 /* Signed coefficients -> canonical residues of the listed moduli, coefficient form. */

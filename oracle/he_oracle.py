@@ -248,6 +248,12 @@ class Oracle:
         lib().orc_add(self._h, _p(a), _p(b), C.c_uint32(level), _p(out))
         return out
 
+    def addpt(self, ct, pt, level):
+        ct, pt = _u64(ct), _u64(pt)
+        out = np.empty_like(ct)
+        lib().orc_addpt(self._h, _p(ct), _p(pt), C.c_uint32(level), _p(out))
+        return out
+
     # ---- client side
     def reduce_signed(self, m, mod_idx):
         m = np.ascontiguousarray(m, dtype=np.int64)

@@ -117,3 +117,27 @@ def test_mulct_tensor_relin_and_affine():
     # dropping a limb keeps the message
     low = o.drop_level(ca, level)
     assert np.max(np.abs(cl.decrypt(low, level - 1, prm.scale) - za)) < 1e-4
+
+
+def test_addpt_adds_slots_and_prot_rotates_a_plaintext():
+    """AddPt: Dec(AddPt(Enc z, Encode b)) = z + b.  PRot: the automorphism applied to an NTT-form plaintext
+    is the encoding of the rotated vector (it equals encoding the rolled vector up to rounding)."""
+    prm = toy_params(logN=6)
+    rng = S.make_rng(35)
+    o, cl = _client(prm, rng)
+    N, level = prm.N, 3
+    mods = list(range(level + 1))
+    z = rng.uniform(-1, 1, N // 2)
+    b = rng.uniform(-1, 1, N // 2)
+    ct = cl.encrypt(z.astype(np.complex128), prm.scale, level, S.uniform_limbs(rng, prm.q[:level + 1], N)[0],
+                    S.gaussian_error(rng, N, prm.sigma)[0])
+    pt = o.ntt(o.reduce_signed(K.encode(b.astype(np.complex128), N, prm.scale), mods), mods)
+    out = o.addpt(ct, pt, level)
+    assert (out[1] == ct[1]).all()
+    assert np.max(np.abs(cl.decrypt(out, level, prm.scale) - (z + b))) < 1e-3
+    # PRot by r: sigma_{5^r} on the plaintext; multiplying by it acts on the slots rolled left by r
+    r = 5
+    rot = o.automorph_ntt(pt, o.galois_elt(r))
+    want = o.ntt(o.reduce_signed(K.encode(np.roll(b, -r).astype(np.complex128), N, prm.scale), mods), mods)
+    diff = K.centered(o.intt(rot, mods)[0], prm.q[0]) - K.centered(o.intt(want, mods)[0], prm.q[0])
+    assert np.max(np.abs(diff)) <= 2             # same polynomial up to the rounding of the two encodings
