@@ -244,7 +244,21 @@ def main():
         extras["add_GBps"] = round(3 * ct_bytes / (ms * 1e-3) / 1e9, 1)
         res = torch.empty((2, level, N), dtype=torch.uint64, device="cuda")
         extras["rescale_us"] = round(1e3 * timed(lambda: ctx.he_rescale(cts[0], level, res), reps=20), 1)
-        del pt, acc, res
+        # the paper's Table 1 operations, one ciphertext per call at level 23, in milliseconds
+        if 0 not in keys:
+            keys[0] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+            ctx.he_evk_register(0, keys[0])
+        t1 = {}
+        t1["AddPt"] = timed(lambda: ctx.he_addpt(cts[0], pt, level, acc), reps=20)
+        t1["AddCt"] = timed(lambda: ctx.he_add(cts[0], cts[1 % B], level, acc), reps=20)
+        t1["MulPt"] = timed(lambda: ctx.he_ptct_mac(acc, cts[0], pt, level, True), reps=20)
+        t1["MulCt"] = timed(lambda: ctx.he_mulct(cts[0], cts[1 % B], level, acc), reps=10)
+        t1["Rescale"] = timed(lambda: ctx.he_rescale(cts[0], level, res), reps=20)
+        pt_rot = torch.empty_like(pt)
+        t1["PRot"] = timed(lambda: ctx.he_automorph(pt, pt_rot, list(range(L1)), 5, True), reps=20)
+        t1["CRot"] = timed(lambda: ctx.he_rotate(cts[0], level, 1, acc), reps=10)
+        extras["table1_ms"] = {k_: round(v, 4) for k_, v in t1.items()}
+        del pt, acc, res, pt_rot
         # configs[3]: ResNet-20-shaped CAConv, 16 -> 16 channels on 32x32, R = 2, level 23
         conv_steps = sorted(set(((dy * 32 + dx) * 2) % (N // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0}
                             | {2048, 4096, 8192, 16384})

@@ -179,6 +179,10 @@ int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const ui
 /* AddCt: d_out = d_a + d_b on [2][level+1][N]; d_out may alias d_a or d_b. */
 int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out);
 
+/* AddPt (Section 2.1): d_out.c0 = d_ct.c0 + d_pt slot-wise per limb, d_out.c1 = d_ct.c1.  d_ct, d_out
+ * [2][level+1][N]; d_pt [level+1][N] at the scale of the ciphertext; d_out may alias d_ct. */
+int32_t he_addpt(he_ctx* ctx, const uint64_t* d_ct, const uint64_t* d_pt, uint32_t level, uint64_t* d_out);
+
 /* MulCt (Section 2.1): ciphertext-ciphertext multiplication = slot-wise tensor product
  * d0 = a0*b0, d1 = a0*b1 + a1*b0, d2 = a1*b1 followed by relinearisation of d2 with the key
  * registered under Galois element 0 (s^2 -> s): out = (d0 + ks0, d1 + ks1).  d_a, d_b, d_out:

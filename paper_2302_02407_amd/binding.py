@@ -18,7 +18,7 @@ _STATUS = {0: "HE_OK", -1: "HE_ERR_BADARG", -2: "HE_ERR_LEVEL", -3: "HE_ERR_NOKE
 EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
-    "he_conjugate", "he_ptct_mac", "he_add", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
+    "he_conjugate", "he_ptct_mac", "he_add", "he_addpt", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
 ]
 
 
@@ -80,6 +80,7 @@ def load():
         "he_conjugate": [vp, vp, u32, vp],
         "he_ptct_mac": [vp, vp, vp, vp, u32, i32],
         "he_add": [vp, vp, vp, u32, vp],
+        "he_addpt": [vp, vp, vp, u32, vp],
         "he_rescale": [vp, vp, u32, vp],
         "he_mulct": [vp, vp, vp, u32, vp],
         "he_affine": [vp, vp, u32, u64p, u64p, vp],
@@ -265,6 +266,13 @@ class HEContext:
         for t, w in ((a, "a"), (b, "b"), (out, "out")):
             _need(t, 2 * (level + 1) * self.N, w)
         self._ck(self._lib.he_add(self._h, _dev(a), _dev(b), level, _dev(out)))
+        return out
+
+    def he_addpt(self, ct, pt, level, out):
+        _need(ct, 2 * (level + 1) * self.N, "ct")
+        _need(pt, (level + 1) * self.N, "pt")
+        _need(out, 2 * (level + 1) * self.N, "out")
+        self._ck(self._lib.he_addpt(self._h, _dev(ct), _dev(pt), level, _dev(out)))
         return out
 
     def he_mulct(self, a, b, level, out):

@@ -62,6 +62,16 @@ __global__ __launch_bounds__(EW_THREADS) void add_kernel(const u64* a, const u64
     out[o] = addmod(a[o], b[o], q);
 }
 
+// AddPt: out.c0 = ct.c0 + pt, out.c1 = ct.c1.  grid: (N/256, 2*(level+1)).
+__global__ __launch_bounds__(EW_THREADS) void addpt_kernel(const u64* ct, const u64* __restrict__ pt, u64* out, const ModConst* mc,
+                                                           uint32_t logN, uint32_t n_limbs) {
+    uint32_t n = blockIdx.x * EW_THREADS + threadIdx.x;
+    size_t o = ((size_t)blockIdx.y << logN) + n;
+    u64 v = ct[o];
+    if (blockIdx.y < n_limbs) v = addmod(v, pt[o], mc[blockIdx.y].q);
+    out[o] = v;
+}
+
 // Tensor product of two ciphertexts (the first half of MulCt): d0 = a0*b0, d1 = a0*b1 + a1*b0,
 // d2 = a1*b1, slot-wise per limb.  grid: (N/256, level+1).
 __global__ __launch_bounds__(EW_THREADS) void tensor_kernel(const u64* __restrict__ a, const u64* __restrict__ b, u64* __restrict__ d,
@@ -183,6 +193,17 @@ int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t l
     if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_add: level %u above L=%u", level, ctx->nq - 1);
     dim3 grid(ctx->N / EW_THREADS, 2 * (level + 1)), block(EW_THREADS);
     hipLaunchKernelGGL(add_kernel, grid, block, 0, ctx->stream, (const u64*)d_a, (const u64*)d_b, (u64*)d_out, ctx->d_mc,
+                       ctx->logN, level + 1);
+    HE_HIP(ctx, hipGetLastError());
+    return HE_OK;
+}
+
+int32_t he_addpt(he_ctx* ctx, const uint64_t* d_ct, const uint64_t* d_pt, uint32_t level, uint64_t* d_out) {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_ct || !d_pt || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_addpt: null argument");
+    if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_addpt: level %u above L=%u", level, ctx->nq - 1);
+    dim3 grid(ctx->N / EW_THREADS, 2 * (level + 1)), block(EW_THREADS);
+    hipLaunchKernelGGL(addpt_kernel, grid, block, 0, ctx->stream, (const u64*)d_ct, (const u64*)d_pt, (u64*)d_out, ctx->d_mc,
                        ctx->logN, level + 1);
     HE_HIP(ctx, hipGetLastError());
     return HE_OK;

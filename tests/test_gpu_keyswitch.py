@@ -272,6 +272,12 @@ def test_mac_add_rescale(cfg, level):
     s = zeros(2, level + 1, N)
     ctx.he_add(dev(ct), dev(ct2), level, s)
     assert (host(s) == orc.add(ct, ct2, level)).all()
+    ap = zeros(2, level + 1, N)
+    ctx.he_addpt(dev(ct), dev(pt), level, ap)
+    assert (host(ap) == orc.addpt(ct, pt, level)).all()
+    inplace = dev(ct)
+    ctx.he_addpt(inplace, dev(pt2), level, inplace)
+    assert (host(inplace) == orc.addpt(ct, pt2, level)).all()
     out = zeros(2, level, N)
     ctx.he_rescale(acc, level, out)
     assert (host(out) == orc.rescale(w, level)).all()
