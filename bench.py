@@ -257,7 +257,12 @@ def main():
         pt_rot = torch.empty_like(pt)
         t1["PRot"] = timed(lambda: ctx.he_automorph(pt, pt_rot, list(range(L1)), 5, True), reps=20)
         t1["CRot"] = timed(lambda: ctx.he_rotate(cts[0], level, 1, acc), reps=10)
+        # the paper's networks work at levels <= 6: the same rotation on a 6-limb ciphertext
+        lo_ct = cts[0][:, :6, :].contiguous()
+        lo_out = torch.empty_like(lo_ct)
+        t1["CRot_level5"] = timed(lambda: ctx.he_rotate(lo_ct, 5, 1, lo_out), reps=10)
         extras["table1_ms"] = {k_: round(v, 4) for k_, v in t1.items()}
+        del lo_ct, lo_out
         del pt, acc, res, pt_rot
         # configs[3]: ResNet-20-shaped CAConv, 16 -> 16 channels on 32x32, R = 2, level 23
         conv_steps = sorted(set(((dy * 32 + dx) * 2) % (N // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0}
