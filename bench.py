@@ -275,6 +275,12 @@ def main():
         conv_out = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
         ms_conv = timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, cts[0], conv_out), reps=2)
         extras["conv2d_ms"] = round(ms_conv, 3)
+        # the same layer on a 6-limb ciphertext (level 5, where the paper's networks run their convolutions)
+        lo_w = [w[:6] for w in weights]
+        lo_in = cts[0][:, :6, :].contiguous()
+        lo_outs = [torch.empty((2, 5, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
+        extras["conv2d_level5_ms"] = round(timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, 5, lo_w, lo_in, lo_outs), reps=5), 3)
+        del lo_w, lo_in, lo_outs
         # the layer that consumes those 8 outputs: reordered RAConv (Algorithm 2), 8 inputs x 9 taps at level 22
         ra_w = [w[:level] for w in weights]
         ra_out = torch.empty((2, level - 1, N), dtype=torch.uint64, device="cuda")
