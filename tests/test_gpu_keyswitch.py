@@ -352,3 +352,40 @@ def test_extreme_residues(cfg):
         res = zeros(2, level, N)
         ctx.he_rescale(dev(ct), level, res)
         assert (host(res) == orc.rescale(ct, level)).all(), name
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_random_parameter_sets_match_oracle(case):
+    """Seeded random ring sizes, prime counts, digit counts, special-prime counts and levels on the generic
+    kernels: key switch, hoisted rotations with an add, rescale and ct x ct multiply, bit for bit."""
+    from gpu_util import dev, host, zeros
+    rng = S.make_rng(2000 + case)
+    logN = int(rng.integers(8, 13))
+    nq = int(rng.integers(2, 9))
+    dnum = int(rng.integers(1, nq + 1))
+    alpha = -(-nq // dnum)
+    np_ = int(rng.integers(alpha, alpha + 3))
+    level = int(rng.integers(0, nq))
+    prm = toy_params(logN=logN, q_bits=int(rng.integers(28, 50)), nq=nq, p_bits=int(rng.integers(50, 60)), np_=np_, dnum=dnum,
+                     hamming=16, seed=2000 + case)
+    _, orc, ctx, cl = _setup(prm, 2000 + case)
+    N = prm.N
+    steps = [int(rng.integers(1, N // 2)) for _ in range(3)]
+    keys = {s: _key(prm, rng, cl, orc.galois_elt(s)) for s in set(steps)}
+    for s, k in keys.items():
+        ctx.he_evk_register(ctx.galois_elt(s), dev(k))
+    rlk = cl.relin_key(S.uniform_limbs(rng, prm.moduli, N, prm.dnum), S.gaussian_error(rng, N, prm.sigma, prm.dnum))
+    ctx.he_evk_register(0, dev(rlk))
+    ct, ct2 = _rand_ct(prm, rng, level), _rand_ct(prm, rng, level)
+    outs = [zeros(2, level + 1, N) for _ in steps]
+    ctx.he_rotate_hoisted(dev(ct), level, steps, outs)
+    for s, o in zip(steps, outs):
+        assert (host(o) == orc.rotate(ct, level, orc.galois_elt(s), keys[s])).all(), (logN, nq, dnum, np_, level, s)
+    prod = zeros(2, level + 1, N)
+    ctx.he_mulct(dev(ct), dev(ct2), level, prod)
+    want = orc.mulct(ct, ct2, level, rlk)
+    assert (host(prod) == want).all(), (logN, nq, dnum, np_, level)
+    if level >= 1:
+        res = zeros(2, level, N)
+        ctx.he_rescale(prod, level, res)
+        assert (host(res) == orc.rescale(want, level)).all()
