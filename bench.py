@@ -161,11 +161,6 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    ms_single = timed(lambda: ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=False), reps=2)
-    ms_hoisted = timed(lambda: ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=True), reps=2)
-    # one ciphertext at a time through the plain entry points (latency-oriented callers)
-    ms_one_single = timed(lambda: [ctx.he_rotate(cts[0], level, s, outs[i]) for i, s in enumerate(steps15)])
-    ms_one_hoisted = timed(lambda: ctx.he_rotate_hoisted(cts[0], level, steps15, outs[:15]))
 
     # roofline of the dominant kernel: one more, identical step with an event pair around every
     # transform launch (kept out of the timed steps so the events do not perturb `value`)
@@ -204,20 +199,28 @@ def main():
         roofline["alu"] = {"achieved": round(a, 2), "peak": round(ALU_PEAK_TOPS, 2), "unit": "T lane-op/s",
                            "frac": round(a / ALU_PEAK_TOPS, 4)}
 
-    # the whole key switch against the HBM roof: compulsory bytes of one key switch with its own key =
-    # input 24 + key 192 + outputs 48 limbs of N*8 B (what a fully fused pipeline would have to move)
-    ks_bytes = (L1 + 2 * prm.dnum * (L1 + k) + 2 * L1) * N * 8
-    roofline["keyswitch"] = {
-        "compulsory_bytes": ks_bytes,
-        "frac_single": round(15 * B / (ms_single * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
-        "frac_hoisted": round(15 * B / (ms_hoisted * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
-    }
-    extras = {
-        "single_keyswitch_per_s": round(15 * B / (ms_single * 1e-3), 1),
-        "hoisted_keyswitch_per_s": round(15 * B / (ms_hoisted * 1e-3), 1),
-        "one_ct_single_keyswitch_per_s": round(15 / (ms_one_single * 1e-3), 1),
-        "one_ct_hoisted_keyswitch_per_s": round(15 / (ms_one_hoisted * 1e-3), 1),
-    }
+    extras = {}
+    if not args.no_extras:
+        # the two halves of the step on their own, and one ciphertext at a time through the plain entry points
+        # (latency-oriented callers)
+        ms_single = timed(lambda: ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=False), reps=2)
+        ms_hoisted = timed(lambda: ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=True), reps=2)
+        ms_one_single = timed(lambda: [ctx.he_rotate(cts[0], level, s, outs[i]) for i, s in enumerate(steps15)])
+        ms_one_hoisted = timed(lambda: ctx.he_rotate_hoisted(cts[0], level, steps15, outs[:15]))
+        # the whole key switch against the HBM roof: compulsory bytes of one key switch with its own key =
+        # input 24 + key 192 + outputs 48 limbs of N*8 B (what a fully fused pipeline would have to move)
+        ks_bytes = (L1 + 2 * prm.dnum * (L1 + k) + 2 * L1) * N * 8
+        roofline["keyswitch"] = {
+            "compulsory_bytes": ks_bytes,
+            "frac_single": round(15 * B / (ms_single * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
+            "frac_hoisted": round(15 * B / (ms_hoisted * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
+        }
+        extras.update({
+            "single_keyswitch_per_s": round(15 * B / (ms_single * 1e-3), 1),
+            "hoisted_keyswitch_per_s": round(15 * B / (ms_hoisted * 1e-3), 1),
+            "one_ct_single_keyswitch_per_s": round(15 / (ms_one_single * 1e-3), 1),
+            "one_ct_hoisted_keyswitch_per_s": round(15 / (ms_one_hoisted * 1e-3), 1),
+        })
     if not args.no_extras:
         # configs[1]: NTT + iNTT round trip of 16 polys x 24 limbs; limb-GB/s counts the limb read and
         # written once per transform
