@@ -23,7 +23,8 @@
  *    NTT form unless a call says otherwise.
  *  - Modulus index space: 0..nq-1 = q_0..q_L (ciphertext primes), nq..nq+np-1 = special primes.
  *  - Every call returns HE_OK (0) or a negative he_status; he_last_error() gives the text.
- *    Calls never abort and never throw.  Work is enqueued on the context's HIP stream and is
+ *    Calls never abort and never throw (a failed host allocation inside a call comes back as
+ *    HE_ERR_ALLOC).  Work is enqueued on the context's HIP stream and is
  *    NOT synchronised on return unless stated.
  *  - A context is not thread-safe; calls on one context must not overlap (they share its
  *    workspace).
@@ -119,6 +120,16 @@ int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out);
 /* Block until everything enqueued on the context's stream has finished. */
 int32_t he_sync(he_ctx* ctx);
 
+/* Workspace.  The context owns one device workspace.  It is sized at creation for every call that works
+ * on one ciphertext at the top level (he_keyswitch, he_rotate, he_conjugate, he_rotate_hoisted, he_mulct,
+ * he_rescale); the batched calls and the convolutions may need more and then grow it on entry, which
+ * synchronises the stream, frees and reallocates.  To keep that out of a timed or latency-critical
+ * region, ask the matching he_ws_query_* for the size (bytes, host output) and call he_ws_reserve once
+ * beforehand.  he_ws_reserve never shrinks the workspace; he_ws_bytes reports its current size.
+ * The queries return HE_ERR_LEVEL / HE_ERR_BADARG for shapes the call itself would refuse. */
+int32_t he_ws_bytes(const he_ctx* ctx, uint64_t* h_bytes);
+int32_t he_ws_reserve(he_ctx* ctx, uint64_t bytes);
+
 /* Forward / inverse negacyclic NTT of n_limbs limbs in place (ring of Section 2.1).
  * d_data: [n_limbs][N]; h_mod_idx[i] = modulus index of limb i.  he_ntt: coefficient form in,
  * NTT form out; he_intt the inverse (including the factor N^-1).  Inputs must be canonical;
@@ -166,6 +177,8 @@ int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, con
  * it.  No output may overlap an input or another output.  Workspace grows with the batch. */
 int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level,
                         const int32_t* h_steps, uint32_t n_steps, uint64_t* const* h_d_out, int32_t hoisted);
+int32_t he_ws_query_rotate_batch(const he_ctx* ctx, uint32_t level, uint32_t n_ct, uint32_t n_steps, int32_t hoisted,
+                                 uint64_t* h_bytes);
 /* CRot(ct; step): identical bits to he_rotate_hoisted with n_steps = 1. */
 int32_t he_rotate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, int32_t step, uint64_t* d_out);
 /* Slot-wise complex conjugation (Galois element 2N-1, key registered under 2N-1). */
@@ -207,6 +220,7 @@ int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* 
  * h_d_ct_out[o] = device buffer [2][level][N].  Needs keys for every non-zero tap amount and
  * every rotate-and-sum amount.  Grows the context workspace on first use (allocates). */
 int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64_t* d_ct_in, uint64_t* const* h_d_ct_out);
+int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* plan, uint64_t* h_bytes);
 
 /* Replication-aligned convolution, reordered (Section 3.1; Algorithm 2): MulFilter&Sum_ci -
  * for every tap the sum over the n_in inputs of input x inversely rotated filter plaintext

@@ -19,6 +19,7 @@ EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_addpt", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
+    "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d",
 ]
 
 
@@ -86,6 +87,10 @@ def load():
         "he_affine": [vp, vp, u32, u64p, u64p, vp],
         "he_conv2d": [vp, C.POINTER(ConvPlan), vp, C.POINTER(vp)],
         "he_raconv": [vp, C.POINTER(RaConvPlan), C.POINTER(vp), vp],
+        "he_ws_bytes": [vp, u64p],
+        "he_ws_reserve": [vp, C.c_uint64],
+        "he_ws_query_rotate_batch": [vp, u32, u32, u32, i32, u64p],
+        "he_ws_query_conv2d": [vp, C.POINTER(ConvPlan), u64p],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -185,6 +190,26 @@ class HEContext:
 
     def galois_elt(self, step):
         return pow(5, step % (self.N // 2), 2 * self.N)
+
+    # ---- workspace
+    def he_ws_bytes(self):
+        v = C.c_uint64()
+        self._ck(self._lib.he_ws_bytes(self._h, C.byref(v)))
+        return v.value
+
+    def he_ws_reserve(self, nbytes):
+        self._ck(self._lib.he_ws_reserve(self._h, int(nbytes)))
+
+    def he_ws_query_rotate_batch(self, level, n_ct, n_steps, hoisted=True):
+        v = C.c_uint64()
+        self._ck(self._lib.he_ws_query_rotate_batch(self._h, level, n_ct, n_steps, 1 if hoisted else 0, C.byref(v)))
+        return v.value
+
+    def he_ws_query_conv2d(self, C_a, H, W, R, f, level, n_out):
+        v = C.c_uint64()
+        plan = ConvPlan(C_a, H, W, R, f, n_out, level, None)
+        self._ck(self._lib.he_ws_query_conv2d(self._h, C.byref(plan), C.byref(v)))
+        return v.value
 
     # ---- transforms
     def he_ntt(self, data, mod_idx):

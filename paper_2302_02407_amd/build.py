@@ -1,20 +1,20 @@
-"""Build the HIP library in-tree: python -m paper_2302_02407_amd.build"""
+"""Build the HIP library in-tree: python -m paper_2302_02407_amd.build [--incremental]"""
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhe_mi355x.so")
 SOURCES = ["ctx.hip", "ntt.hip", "ntt16.hip", "elementwise.hip", "keyswitch.hip", "conv2d.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fgpu-rdc" if False else "-fno-gpu-rdc",
+HEADERS = ["he_internal.h", "modarith.h", os.path.join("..", "..", "include", "he_mi355x.h")]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
-def build_library(verbose: bool = True) -> str:
-    """Compile every HIP source for gfx950 into one shared library next to this file."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -23,9 +23,28 @@ def build_library(verbose: bool = True) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out:
         print(out)
+
+
+def build_library(verbose: bool = True, incremental: bool = False) -> str:
+    """Compile every HIP source for gfx950 (one object per source, in parallel) and link them into one
+    shared library next to this file.  incremental=True skips objects newer than their source and the
+    headers."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ, exist_ok=True)
+    newest_header = max(os.path.getmtime(os.path.join(CSRC, h)) for h in HEADERS)
+    jobs = []
+    for s in SOURCES:
+        src, obj = os.path.join(CSRC, s), os.path.join(OBJ, s + ".o")
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            continue
+        jobs.append([hipcc] + FLAGS + ["-c", src, "-o", obj])
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        list(ex.map(lambda c: _run(c, verbose), jobs))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + [os.path.join(OBJ, s + ".o") for s in SOURCES]
+         + ["-o", LIB], verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    build_library()
+    build_library(incremental="--incremental" in sys.argv[1:])
     sys.exit(0)

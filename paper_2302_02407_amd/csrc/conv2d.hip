@@ -4,7 +4,7 @@
 // (Algorithm 2), all enqueued on the context's stream with no host synchronisation.
 #include <algorithm>
 
-#include "modarith.cuh"
+#include "modarith.h"
 
 #define CV_THREADS 256
 #define CV_MAX_TAPS 49
@@ -80,7 +80,40 @@ __global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTapsAny taps, u
     acc[o1] = barrett128(a1, m.q, m.mu, m.bits);
 }
 
+// Slot amounts of the f^2 taps (dy outer, dx inner, both from -(f-1)/2), reduced to [0, slots).
+static std::vector<uint32_t> tap_slot_steps(uint32_t W, uint32_t R, uint32_t f, uint32_t slots) {
+    std::vector<uint32_t> steps(f * f);
+    const int32_t half = (int32_t)(f - 1) / 2;
+    for (uint32_t t = 0; t < f * f; t++) {
+        const int32_t dy = (int32_t)(t / f) - half, dx = (int32_t)(t % f) - half;
+        int64_t step = ((int64_t)dy * W + dx) * R;
+        steps[t] = (uint32_t)(((step % (int64_t)slots) + slots) % slots);
+    }
+    return steps;
+}
+
+// he_conv2d workspace: [key-switch engine region][rescale scratch][rotated inputs][n_out accumulators at `level`]
+// [n_out temporaries at level-1]
+static size_t conv2d_ws_elems(const he_ctx* ctx, uint32_t level, uint32_t n_rot, uint32_t n_out) {
+    const size_t N = ctx->N, ct_e = (size_t)2 * (level + 1) * N, ct_lo_e = (size_t)2 * level * N;
+    const size_t ks_e = std::max(n_rot ? ks_engine_ws_elems(ctx, level, 1, n_rot) : 0, ks_engine_ws_elems(ctx, level - 1, n_out, n_out));
+    return ks_e + rescale_ws_elems(ctx, level, n_out) + (size_t)(n_rot + n_out) * ct_e + (size_t)n_out * ct_lo_e;
+}
+
+extern "C" int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* plan, uint64_t* h_bytes) {
+    return he_guard(ctx, "he_ws_query_conv2d: host allocation failed", [&]() -> int32_t {
+    if (!ctx || !plan || !h_bytes) return HE_ERR_BADARG;
+    if (plan->level == 0 || plan->level >= ctx->nq) return HE_ERR_LEVEL;
+    if ((plan->f & 1u) == 0 || plan->f * plan->f > CV_MAX_TAPS || plan->n_out == 0) return HE_ERR_BADARG;
+    uint32_t n_rot = 0;
+    for (uint32_t st : tap_slot_steps(plan->W, plan->R, plan->f, ctx->N / 2)) n_rot += st != 0;
+    *h_bytes = conv2d_ws_elems(ctx, plan->level, n_rot, plan->n_out) * sizeof(u64);
+    return HE_OK;
+    });
+}
+
 extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64_t* d_ct_in, uint64_t* const* h_d_ct_out) {
+    return he_guard(ctx, "he_conv2d: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!plan || !d_ct_in || !h_d_ct_out || !plan->h_d_weights) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: null argument");
     const uint32_t N = ctx->N, slots = N / 2, level = plan->level, f = plan->f, taps = f * f;
@@ -118,20 +151,19 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         if (!plan->h_d_weights[i]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: weight plaintext %u is null", i);
     for (uint32_t o = 0; o < plan->n_out; o++)
         if (!h_d_ct_out[o]) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: output %u is null", o);
-    // workspace: [key-switch engine region][rescale scratch][taps-1 rotated inputs][n_out accumulators]
-    //            [n_out temporaries]
     const uint32_t lo = level - 1;                       // level after the rescale
     const uint32_t n_out = plan->n_out, n_ras = (uint32_t)ras_g.size();
+    uint32_t n_rot = 0;
+    for (uint32_t t = 0; t < taps; t++) n_rot += tap_g[t] != 1;
     const size_t ct_e = (size_t)2 * L1 * N, ct_lo_e = (size_t)2 * level * N;
-    const size_t ks_e = std::max(ks_engine_ws_elems(ctx, level, 1, taps - 1), ks_engine_ws_elems(ctx, lo, n_out, n_out));
-    const size_t rs_e = rescale_ws_elems(ctx, level, n_out);
-    const size_t total = ks_e + rs_e + (size_t)(taps - 1 + n_out) * ct_e + (size_t)n_out * ct_lo_e;
+    const size_t total = conv2d_ws_elems(ctx, level, n_rot, n_out);
     int32_t rc = he_ensure_ws(ctx, total * sizeof(u64));
     if (rc != HE_OK) return rc;
-    u64* rs_ws = ctx->d_ws + ks_e;
-    u64* slid = rs_ws + rs_e;
-    u64* acc = slid + (size_t)(taps - 1) * ct_e;         // [n_out] ciphertexts at `level`
-    u64* tmp = acc + (size_t)n_out * ct_e;               // [n_out] ciphertexts at level lo
+    // laid out from the end of the region: [engine ...][rescale scratch][rotated inputs][accumulators][temporaries]
+    u64* tmp = ctx->d_ws + total - (size_t)n_out * ct_lo_e;  // [n_out] ciphertexts at level lo
+    u64* acc = tmp - (size_t)n_out * ct_e;                   // [n_out] ciphertexts at `level`
+    u64* slid = acc - (size_t)n_rot * ct_e;                  // [n_rot] rotated inputs
+    u64* rs_ws = slid - rescale_ws_elems(ctx, level, n_out);
     const u64* ct_in = (const u64*)d_ct_in;
 
     // Slide_f: one ModUp of c1 shared by all taps
@@ -204,6 +236,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         std::swap(cur, nxt);
     }
     return HE_OK;
+    });
 }
 
 // ---------------------------------------------------------------- RAConv (Algorithm 2)
@@ -274,6 +307,7 @@ __global__ __launch_bounds__(CV_THREADS) void sum_cts_kernel(SumList l, u64* out
 }
 
 extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* d_ct_out) {
+    return he_guard(ctx, "he_raconv: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!plan || !h_d_ct_in || !d_ct_out || !plan->h_d_weights) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: null argument");
     const uint32_t N = ctx->N, slots = N / 2, level = plan->level, f = plan->f, taps = f * f, n_in = plan->n_in;
@@ -364,4 +398,5 @@ extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint
     const u64* rin = total;
     u64* rout = (u64*)d_ct_out;
     return rescale_batch(ctx, &rin, &rout, 1, level, rs_ws);
+    });
 }

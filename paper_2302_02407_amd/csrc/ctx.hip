@@ -18,6 +18,13 @@ int32_t he_fail(he_ctx* ctx, int32_t code, const char* fmt, ...) {
     return code;
 }
 
+void he_fail_nothrow(he_ctx* ctx, const char* msg) noexcept {
+    try {
+        if (ctx) ctx->err = msg; else g_create_err = msg;
+    } catch (...) {
+    }
+}
+
 u64 h_mulmod(u64 a, u64 b, u64 m) { return (u64)((u128)a * b % m); }
 u64 h_powmod(u64 a, u64 e, u64 m) {
     u64 r = 1 % m;
@@ -95,6 +102,7 @@ const char* he_last_error(const he_ctx* ctx) { return ctx ? ctx->err.c_str() : g
 
 int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t nq, const uint64_t* h_p,
                       uint32_t np, uint32_t dnum, void* hip_stream) {
+    return he_guard(nullptr, "he_ctx_create: host allocation failed", [&]() -> int32_t {
     if (!out) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: out is null");
     *out = nullptr;
     if (logN < 8 || logN > 17) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: logN %u outside 8..17", logN);
@@ -112,8 +120,14 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
             if (mk == m) return he_fail(nullptr, HE_ERR_BADARG, "he_ctx_create: modulus %u repeats modulus %u", i, k);
         }
     }
+    // host tables first, so that a failed host allocation leaves nothing behind
+    std::vector<u64> tw((size_t)M * N), tw_sh((size_t)M * N), itw((size_t)M * N), itw_sh((size_t)M * N);
     he_ctx* c = new (std::nothrow) he_ctx();
     if (!c) return he_fail(nullptr, HE_ERR_ALLOC, "he_ctx_create: host allocation failed");
+    struct Owner {                                      // destroys the half-built context on every early exit
+        he_ctx* c;
+        ~Owner() { if (c) he_ctx_destroy(c); }
+    } own{c};
     c->logN = logN; c->N = N; c->nq = nq; c->np = np; c->dnum = dnum; c->M = M;
     c->alpha = (nq + dnum - 1) / dnum;
     c->stream = (hipStream_t)hip_stream;
@@ -123,11 +137,9 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
     memset(&c->cnt, 0, sizeof(c->cnt));
     c->prof_on = false;
     if (hipGetDevice(&c->device) != hipSuccess) {
-        delete c;
         return he_fail(nullptr, HE_ERR_HIP, "he_ctx_create: no HIP device");
     }
     // tables on the host
-    std::vector<u64> tw((size_t)M * N), tw_sh((size_t)M * N), itw((size_t)M * N), itw_sh((size_t)M * N);
     for (uint32_t i = 0; i < M; i++) {
         u64 m = i < nq ? h_q[i] : h_p[i - nq];
         c->mod[i] = m;
@@ -172,32 +184,35 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         he_fail(nullptr, e == hipErrorOutOfMemory ? HE_ERR_ALLOC : HE_ERR_HIP, "he_ctx_create: %s", hipGetErrorString(e));
-        he_ctx_destroy(c);
         return e == hipErrorOutOfMemory ? HE_ERR_ALLOC : HE_ERR_HIP;
     }
     {
         int32_t rc = ks_init_tables(c);
         if (rc != HE_OK) {
             g_create_err = c->err;
-            he_ctx_destroy(c);
-            return rc;
+                return rc;
         }
     }
-    // workspace for one key switch at the top level (raised digits + accumulators + temporaries)
+    // workspace for every one-ciphertext call at the top level: one key switch (raised digits +
+    // temporaries) with the three tensor-product polynomials of a ct x ct multiplication behind it, or
+    // one rescale; only the batched calls and the convolutions can need more (he_ws_reserve)
     if (np > 0) {
-        size_t elems = ks_engine_ws_elems(c, nq - 1, 1, 1);
+        size_t elems = ks_engine_ws_elems(c, nq - 1, 1, 1) + (size_t)3 * nq * N;
+        if (nq > 1) elems = elems > rescale_ws_elems(c, nq - 1, 1) ? elems : rescale_ws_elems(c, nq - 1, 1);
         int32_t rc = he_ensure_ws(c, elems * sizeof(u64));
         if (rc != HE_OK) {
             g_create_err = c->err;
-            he_ctx_destroy(c);
-            return rc;
+                return rc;
         }
     }
+    own.c = nullptr;
     *out = c;
     return HE_OK;
+    });
 }
 
 int32_t he_ctx_destroy(he_ctx* c) {
+    return he_guard(c, "he_ctx_destroy: host allocation failed", [&]() -> int32_t {
     if (!c) return HE_OK;
     (void)hipStreamSynchronize(c->stream);
     if (c->d_mc) (void)hipFree(c->d_mc);
@@ -210,35 +225,45 @@ int32_t he_ctx_destroy(he_ctx* c) {
     ks_free_tables(c);
     delete c;
     return HE_OK;
+    });
 }
 
 int32_t he_ctx_psi(const he_ctx* ctx, uint32_t mod_idx, uint64_t* h_psi_out) {
+    return he_guard(ctx, "he_ctx_psi: host allocation failed", [&]() -> int32_t {
     if (!ctx || !h_psi_out || mod_idx >= ctx->M) return HE_ERR_BADARG;
     *h_psi_out = ctx->psi[mod_idx];
     return HE_OK;
+    });
 }
 
 int32_t he_counters(const he_ctx* ctx, he_counters_t* h_out) {
+    return he_guard(ctx, "he_counters: host allocation failed", [&]() -> int32_t {
     if (!ctx || !h_out) return HE_ERR_BADARG;
     *h_out = ctx->cnt;
     return HE_OK;
+    });
 }
 
 int32_t he_counters_reset(he_ctx* ctx) {
+    return he_guard(ctx, "he_counters_reset: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     memset(&ctx->cnt, 0, sizeof(ctx->cnt));
     return HE_OK;
+    });
 }
 
 int32_t he_profile_begin(he_ctx* ctx) {
+    return he_guard(ctx, "he_profile_begin: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     for (auto& s : ctx->prof_events) { (void)hipEventDestroy(s.e0); (void)hipEventDestroy(s.e1); }
     ctx->prof_events.clear();
     ctx->prof_on = true;
     return HE_OK;
+    });
 }
 
 int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out) {
+    return he_guard(ctx, "he_profile_end: host allocation failed", [&]() -> int32_t {
     if (!ctx || !h_out) return HE_ERR_BADARG;
     ctx->prof_on = false;
     HE_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -258,15 +283,34 @@ int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out) {
     }
     ctx->prof_events.clear();
     return HE_OK;
+    });
 }
 
 int32_t he_sync(he_ctx* ctx) {
+    return he_guard(ctx, "he_sync: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     HE_HIP(ctx, hipStreamSynchronize(ctx->stream));
     return HE_OK;
+    });
+}
+
+int32_t he_ws_bytes(const he_ctx* ctx, uint64_t* h_bytes) {
+    return he_guard(ctx, "he_ws_bytes: host allocation failed", [&]() -> int32_t {
+    if (!ctx || !h_bytes) return HE_ERR_BADARG;
+    *h_bytes = ctx->ws_bytes;
+    return HE_OK;
+    });
+}
+
+int32_t he_ws_reserve(he_ctx* ctx, uint64_t bytes) {
+    return he_guard(ctx, "he_ws_reserve: host allocation failed", [&]() -> int32_t {
+    if (!ctx) return HE_ERR_BADARG;
+    return he_ensure_ws(ctx, (size_t)bytes);
+    });
 }
 
 int32_t he_evk_register(he_ctx* ctx, uint32_t galois_elt, const uint64_t* d_evk) {
+    return he_guard(ctx, "he_evk_register: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_evk) return he_fail(ctx, HE_ERR_BADARG, "he_evk_register: null key");
     if (galois_elt != 0 && ((galois_elt & 1u) == 0 || galois_elt >= 2 * ctx->N))
@@ -274,6 +318,7 @@ int32_t he_evk_register(he_ctx* ctx, uint32_t galois_elt, const uint64_t* d_evk)
     if (ctx->np == 0) return he_fail(ctx, HE_ERR_BADARG, "he_evk_register: context has no special primes");
     ctx->evk[galois_elt] = (const u64*)d_evk;
     return HE_OK;
+    });
 }
 
 } // extern "C"

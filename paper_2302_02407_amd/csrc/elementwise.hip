@@ -1,5 +1,5 @@
 // Coefficient-wise kernels: Galois permutation, MulPt-accumulate, AddCt, and their entry points.
-#include "modarith.cuh"
+#include "modarith.h"
 
 #define EW_THREADS 256
 
@@ -139,6 +139,7 @@ extern "C" {
 
 int32_t he_automorph(he_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, const uint32_t* h_mod_idx,
                      uint32_t n_limbs, uint32_t galois_elt, int32_t ntt_form) {
+    return he_guard(ctx, "he_automorph: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_in || !d_out || !h_mod_idx) return he_fail(ctx, HE_ERR_BADARG, "he_automorph: null argument");
     if ((galois_elt & 1u) == 0 || galois_elt >= 2 * ctx->N) return he_fail(ctx, HE_ERR_BADARG, "he_automorph: Galois element %u is not odd and below 2N", galois_elt);
@@ -156,21 +157,32 @@ int32_t he_automorph(he_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, const u
         if (rc != HE_OK) return rc;
     }
     return HE_OK;
+    });
 }
 
 int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const uint64_t* d_pt, uint32_t level, int32_t init) {
+    return he_guard(ctx, "he_ptct_mac: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_acc || !d_ct || !d_pt) return he_fail(ctx, HE_ERR_BADARG, "he_ptct_mac: null argument");
     if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_ptct_mac: level %u above L=%u", level, ctx->nq - 1);
+    {
+        // the kernel reads ct and pt through restrict pointers while it writes acc
+        const size_t pb = (size_t)(level + 1) * ctx->N * sizeof(u64);
+        const char *a = (const char*)d_acc, *c = (const char*)d_ct, *p = (const char*)d_pt;
+        if ((a < c + 2 * pb && c < a + 2 * pb) || (a < p + pb && p < a + 2 * pb))
+            return he_fail(ctx, HE_ERR_BADARG, "he_ptct_mac: the accumulator overlaps the ciphertext or the plaintext");
+    }
     dim3 grid(ctx->N / EW_THREADS, level + 1), block(EW_THREADS);
     hipLaunchKernelGGL(ptct_mac_kernel, grid, block, 0, ctx->stream, (u64*)d_acc, (const u64*)d_ct, (const u64*)d_pt,
                        ctx->d_mc, ctx->logN, level + 1, init);
     HE_HIP(ctx, hipGetLastError());
     ctx->cnt.mac += 1;
     return HE_OK;
+    });
 }
 
 int32_t he_affine(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const uint64_t* h_mul, const uint64_t* h_add, uint64_t* d_out) {
+    return he_guard(ctx, "he_affine: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_ct || !d_out || !h_mul || !h_add) return he_fail(ctx, HE_ERR_BADARG, "he_affine: null argument");
     if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_affine: level %u above L=%u", level, ctx->nq - 1);
@@ -185,9 +197,11 @@ int32_t he_affine(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const uint6
     hipLaunchKernelGGL(affine_kernel, grid, block, 0, ctx->stream, (const u64*)d_ct, (u64*)d_out, aa, ctx->d_mc, ctx->logN, level + 1);
     HE_HIP(ctx, hipGetLastError());
     return HE_OK;
+    });
 }
 
 int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out) {
+    return he_guard(ctx, "he_add: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_a || !d_b || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_add: null argument");
     if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_add: level %u above L=%u", level, ctx->nq - 1);
@@ -196,9 +210,11 @@ int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t l
                        ctx->logN, level + 1);
     HE_HIP(ctx, hipGetLastError());
     return HE_OK;
+    });
 }
 
 int32_t he_addpt(he_ctx* ctx, const uint64_t* d_ct, const uint64_t* d_pt, uint32_t level, uint64_t* d_out) {
+    return he_guard(ctx, "he_addpt: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_ct || !d_pt || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_addpt: null argument");
     if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_addpt: level %u above L=%u", level, ctx->nq - 1);
@@ -207,6 +223,7 @@ int32_t he_addpt(he_ctx* ctx, const uint64_t* d_ct, const uint64_t* d_pt, uint32
                        ctx->logN, level + 1);
     HE_HIP(ctx, hipGetLastError());
     return HE_OK;
+    });
 }
 
 } // extern "C"

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <map>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -88,6 +89,22 @@ u64 h_powmod(u64 a, u64 e, u64 m);
 u64 h_invmod(u64 a, u64 m);
 u64 h_shoup(u64 w, u64 m);
 uint32_t h_galois_of_step(const he_ctx* ctx, int32_t step);
+
+// Every extern "C" body runs inside he_guard: no C++ exception (a failed host allocation in a
+// std::vector / std::map / std::string) crosses the C ABI; it comes back as HE_ERR_ALLOC.
+void he_fail_nothrow(he_ctx* ctx, const char* msg) noexcept;
+template <class F>
+static inline int32_t he_guard(const he_ctx* ctx, const char* who, F&& body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        he_fail_nothrow(const_cast<he_ctx*>(ctx), who);
+        return HE_ERR_ALLOC;
+    } catch (...) {
+        he_fail_nothrow(const_cast<he_ctx*>(ctx), who);
+        return HE_ERR_ALLOC;
+    }
+}
 
 #define HE_HIP(ctx, call)                                                                            \
     do {                                                                                             \

@@ -19,7 +19,7 @@
 // ciphertext has only 24; jobs that use the same key share one pass over the key.
 #include <algorithm>
 
-#include "modarith.cuh"
+#include "modarith.h"
 
 #define KS_THREADS 256
 #define CONV_MAX_JOBS 8
@@ -685,6 +685,7 @@ extern "C" {
 
 int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t galois_elt_of_key, uint64_t* d_out0,
                      uint64_t* d_out1) {
+    return he_guard(ctx, "he_keyswitch: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_in || !d_out0 || !d_out1) return he_fail(ctx, HE_ERR_BADARG, "he_keyswitch: null argument");
     int32_t rc = check_ks_ready(ctx, level, "he_keyswitch");
@@ -700,10 +701,12 @@ int32_t he_keyswitch(he_ctx* ctx, const uint64_t* d_in, uint32_t level, uint32_t
     KsSrc src = {nullptr, (const u64*)d_in, nullptr, nullptr};
     KsJob job = {0, 1, it->second, (u64*)d_out0, (u64*)d_out1, 0};
     return ks_engine(ctx, level, &src, 1, &job, 1);
+    });
 }
 
 int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level, const int32_t* h_steps,
                         uint32_t n_steps, uint64_t* const* h_d_out, int32_t hoisted) {
+    return he_guard(ctx, "he_rotate_batch: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (n_ct == 0 || n_steps == 0) return HE_OK;
     if (!h_d_ct || !h_steps || !h_d_out) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_batch: null argument");
@@ -769,25 +772,43 @@ int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_c
         }
     }
     return ks_engine(ctx, level, srcs.data(), (uint32_t)srcs.size(), jobs.data(), (uint32_t)jobs.size());
+    });
+}
+
+int32_t he_ws_query_rotate_batch(const he_ctx* ctx, uint32_t level, uint32_t n_ct, uint32_t n_steps, int32_t hoisted,
+                                 uint64_t* h_bytes) {
+    return he_guard(ctx, "he_ws_query_rotate_batch: host allocation failed", [&]() -> int32_t {
+    if (!ctx || !h_bytes) return HE_ERR_BADARG;
+    if (level >= ctx->nq) return HE_ERR_LEVEL;
+    const uint64_t jobs = (uint64_t)n_ct * n_steps;
+    if (jobs > 0xFFFFFFFFull) return HE_ERR_BADARG;
+    *h_bytes = jobs == 0 ? 0 : ks_engine_ws_elems(ctx, level, hoisted ? n_ct : (uint32_t)jobs, (uint32_t)jobs) * sizeof(u64);
+    return HE_OK;
+    });
 }
 
 int32_t he_rotate_hoisted(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const int32_t* h_steps, uint32_t n_steps,
                           uint64_t* const* h_d_out) {
+    return he_guard(ctx, "he_rotate_hoisted: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_ct) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_hoisted: null argument");
     const uint64_t* cts[1] = {d_ct};
     return he_rotate_batch(ctx, cts, 1, level, h_steps, n_steps, h_d_out, 1);
+    });
 }
 
 int32_t he_rotate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, int32_t step, uint64_t* d_out) {
+    return he_guard(ctx, "he_rotate: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_ct || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_rotate: null argument");
     const uint64_t* cts[1] = {d_ct};
     uint64_t* outs[1] = {d_out};
     return he_rotate_batch(ctx, cts, 1, level, &step, 1, outs, 1);
+    });
 }
 
 int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out) {
+    return he_guard(ctx, "he_conjugate: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_ct || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_conjugate: null argument");
     int32_t rc = check_ks_ready(ctx, level, "he_conjugate");
@@ -801,9 +822,11 @@ int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t
     KsSrc src = {ct, ct + (size_t)L1 * N, nullptr, nullptr};
     KsJob job = {0, g, it->second, (u64*)d_out, (u64*)d_out + (size_t)L1 * N, 0};
     return ks_engine(ctx, level, &src, 1, &job, 1);
+    });
 }
 
 int32_t he_mulct(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out) {
+    return he_guard(ctx, "he_mulct: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_a || !d_b || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_mulct: null argument");
     int32_t rc = check_ks_ready(ctx, level, "he_mulct");
@@ -820,9 +843,11 @@ int32_t he_mulct(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t
     KsSrc src = {nullptr, d + 2 * pe, d, d + pe};
     KsJob job = {0, 1, it->second, (u64*)d_out, (u64*)d_out + pe, 1};
     return ks_engine(ctx, level, &src, 1, &job, 1);
+    });
 }
 
 int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out) {
+    return he_guard(ctx, "he_rescale: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (!d_ct || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_rescale: null argument");
     if (level == 0 || level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_rescale: level %u outside 1..%u", level, ctx->nq - 1);
@@ -834,6 +859,7 @@ int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* 
     const u64* cts[1] = {(const u64*)d_ct};
     u64* outs[1] = {(u64*)d_out};
     return rescale_batch(ctx, cts, outs, 1, level, ctx->d_ws);
+    });
 }
 
 } // extern "C"

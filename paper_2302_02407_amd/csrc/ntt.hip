@@ -13,7 +13,7 @@
 //                       COLS = 4096/ROWS adjacent columns of the 4096-wide row-major view;
 //   pass B ("contiguous"): the last 12 stages; a tile is 4096 consecutive elements.
 // Both passes run the same butterfly loop on the tile-local index space.
-#include "modarith.cuh"
+#include "modarith.h"
 
 #define NTT_THREADS 1024
 #define NTT_LOG_TILE_MAX 12
@@ -220,6 +220,7 @@ int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, co
 extern "C" {
 
 int32_t he_ntt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_t n_limbs) {
+    return he_guard(ctx, "he_ntt: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (n_limbs == 0) return HE_OK;
     if (!d_data || !h_mod_idx) return he_fail(ctx, HE_ERR_BADARG, "he_ntt: null argument");
@@ -231,9 +232,11 @@ int32_t he_ntt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_
         if (rc != HE_OK) return rc;
     }
     return HE_OK;
+    });
 }
 
 int32_t he_intt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32_t n_limbs) {
+    return he_guard(ctx, "he_intt: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
     if (n_limbs == 0) return HE_OK;
     if (!d_data || !h_mod_idx) return he_fail(ctx, HE_ERR_BADARG, "he_intt: null argument");
@@ -245,6 +248,7 @@ int32_t he_intt(he_ctx* ctx, uint64_t* d_data, const uint32_t* h_mod_idx, uint32
         if (rc != HE_OK) return rc;
     }
     return HE_OK;
+    });
 }
 
 } // extern "C"

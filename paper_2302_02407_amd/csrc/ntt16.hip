@@ -15,7 +15,7 @@
 // one small-quotient reduction canonicalises at the very end.  Wider moduli (below 2^60) keep
 // [0,8q) with one conditional subtraction of 4q per butterfly.  The inverse keeps [0,4q)
 // throughout (sums are reduced, differences re-enter through the twiddle product).
-#include "modarith.cuh"
+#include "modarith.h"
 
 #define T16_THREADS 256
 
