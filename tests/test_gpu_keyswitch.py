@@ -1,5 +1,7 @@
 """GPU parity: key switching, rotations (single and hoisted), conjugation, MulPt-accumulate,
 add and rescale vs the CPU oracle, bit-exact; plus Dec(Rot(Enc z)) = roll(z) on the GPU result."""
+import sys
+
 import numpy as np
 import pytest
 
@@ -101,11 +103,12 @@ def test_rotate_batch_matches_single_calls_and_oracle(cfg, level, n_ct, steps):
         assert (ref[(c, i)] == want).all()
 
 
-@pytest.mark.timeout(600)
+@pytest.mark.timeout(900)
 def test_config2_full_batch_as_benchmarked():
     """Workload 2 at the size and launch configuration bench.py times: 64 uniform ciphertexts at level 23,
     all 15 power-of-two steps through he_rotate_batch, singly and hoisted.  Every output of the two
-    modes agrees bit for bit, two runs agree (determinism), and sampled outputs equal the oracle."""
+    modes agrees bit for bit, two runs agree (determinism), and 4 ciphertexts x (15 steps + conjugation)
+    equal the oracle."""
     import torch
     from gpu_util import dev, host, zeros
     prm = config_params(2)
@@ -134,9 +137,22 @@ def test_config2_full_batch_as_benchmarked():
     ctx.he_rotate_batch(cts, level, steps, out_h, hoisted=True)
     torch.cuda.synchronize()
     assert sums == [int(o.view(torch.int64).sum().item()) for o in out_h[::37]]
-    for c, i in ((0, 0), (17, 7), (63, 14)):
-        want = orc.rotate(host(cts[c]), level, orc.galois_elt(steps[i]), host(keys[steps[i]]))
-        assert (host(out_h[c * 15 + i]) == want).all(), (c, i)
+    # the stated oracle subset: four seeded ciphertexts x all 15 steps + conjugation, bit for bit (the oracle
+    # raises each ciphertext once and rotates from the raised digits, which its own pins show equals rotating singly)
+    keys_h = {s: host(keys[s]) for s in steps}
+    kc = uniform((prm.dnum, 2), prm.moduli)
+    ctx.he_evk_register(2 * N - 1, kc)
+    kc_h = host(kc)
+    for c in (0, 17, 40, 63):
+        ct_h = host(cts[c])
+        raised = orc.modup(ct_h[1], level)
+        for i, s in enumerate(steps):
+            want = orc.rotate_from_raised(ct_h, raised, level, orc.galois_elt(s), keys_h[s])
+            assert (host(out_h[c * 15 + i]) == want).all(), (c, s)
+        oc = zeros(2, level + 1, N)
+        ctx.he_conjugate(cts[c], level, oc)
+        assert (host(oc) == orc.rotate_from_raised(ct_h, raised, level, orc.galois_conj, kc_h)).all(), (c, "conj")
+        print("config 2: ciphertext %d, 15 steps + conjugation equal the oracle" % c, file=sys.__stdout__, flush=True)
 
 
 def test_wide_digits_generic_conversion_path():
@@ -389,3 +405,54 @@ def test_random_parameter_sets_match_oracle(case):
         res = zeros(2, level, N)
         ctx.he_rescale(prod, level, res)
         assert (host(res) == orc.rescale(want, level)).all()
+
+
+@pytest.mark.parametrize("logN,q_bits,p_bits", [(13, 40, 50), (15, 54, 60), (17, 36, 59), (14, 57, 58)])
+def test_two_pass_generic_rings_key_switching(logN, q_bits, p_bits):
+    """Ring sizes above 2^12 other than 2^16 (the paper's N = 2^15 and 2^17 among them) run the generic
+    transform in two passes with gathered sources, per-limb output scaling and the stand-alone ModDown
+    epilogue: key switch, hoisted and single rotations, conjugation, rescale and ct x ct multiply against the
+    oracle, at the top level (three digits, the last one partial) and at a level with two digits."""
+    from gpu_util import dev, host, zeros
+    prm = toy_params(logN=logN, q_bits=q_bits, nq=5, p_bits=p_bits, np_=2, dnum=3, hamming=64, seed=300 + logN)
+    rng, orc, ctx, cl = _setup(prm, 300 + logN)
+    N = prm.N
+    steps = [1, N // 4 + 3]
+    keys = {s: _key(prm, rng, cl, orc.galois_elt(s)) for s in steps}
+    for s, k in keys.items():
+        ctx.he_evk_register(ctx.galois_elt(s), dev(k))
+    kc = _key(prm, rng, cl, orc.galois_conj)
+    ctx.he_evk_register(2 * N - 1, dev(kc))
+    rlk = cl.relin_key(S.uniform_limbs(rng, prm.moduli, N, prm.dnum), S.gaussian_error(rng, N, prm.sigma, prm.dnum))
+    ctx.he_evk_register(0, dev(rlk))
+    for level in (4, 2):
+        ct, ct2 = _rand_ct(prm, rng, level), _rand_ct(prm, rng, level)
+        o0, o1 = zeros(level + 1, N), zeros(level + 1, N)
+        ctx.he_keyswitch(dev(ct[1]), level, ctx.galois_elt(1), o0, o1)
+        w0, w1 = orc.keyswitch(ct[1], level, keys[1])
+        assert (host(o0) == w0).all() and (host(o1) == w1).all(), (logN, level)
+        outs = [zeros(2, level + 1, N) for _ in steps]
+        ctx.he_rotate_hoisted(dev(ct), level, steps, outs)
+        for s, o in zip(steps, outs):
+            want = orc.rotate(ct, level, orc.galois_elt(s), keys[s])
+            assert (host(o) == want).all(), (logN, level, s)
+            single = zeros(2, level + 1, N)
+            ctx.he_rotate(dev(ct), level, s, single)
+            assert (host(single) == want).all(), (logN, level, s)
+        oc = zeros(2, level + 1, N)
+        ctx.he_conjugate(dev(ct), level, oc)
+        assert (host(oc) == orc.rotate(ct, level, orc.galois_conj, kc)).all(), (logN, level)
+        prod = zeros(2, level + 1, N)
+        ctx.he_mulct(dev(ct), dev(ct2), level, prod)
+        want = orc.mulct(ct, ct2, level, rlk)
+        assert (host(prod) == want).all(), (logN, level)
+        res = zeros(2, level, N)
+        ctx.he_rescale(prod, level, res)
+        assert (host(res) == orc.rescale(want, level)).all(), (logN, level)
+    # a real encryption decrypts to the rotated message on this path too
+    z = rng.uniform(-1, 1, N // 2) + 1j * rng.uniform(-1, 1, N // 2)
+    scale = 2.0 ** (q_bits - 6)      # the un-rounded ModDown leaves up to ~2N/pi * k / scale in the slot nearest the real axis
+    ct = cl.encrypt(z, scale, 4, S.uniform_limbs(rng, prm.q[:5], N)[0], S.gaussian_error(rng, N, prm.sigma)[0])
+    out = zeros(2, 5, N)
+    ctx.he_rotate(dev(ct), 4, 1, out)
+    assert np.max(np.abs(cl.decrypt(host(out), 4, scale) - np.roll(z, -1))) < 1e-3
