@@ -213,14 +213,23 @@ def encode_ra_weights(orc: Oracle, geo: RAGeometry, wt, level, pt_scale):
     return pts
 
 
-def raconv(orc: Oracle, geo: RAGeometry, cts, level, pts, evks, keep=False):
-    """cts: n_in ciphertexts [2][level+1][N] -> one ciphertext [2][level][N]."""
+def raconv(orc: Oracle, geo: RAGeometry, cts, level, pts, evks, keep=False, deferred=False):
+    """cts: n_in ciphertexts [2][level+1][N] -> one ciphertext [2][level][N].
+
+    deferred=True evaluates Slide_1 & Sum_f with one ModDown for the whole sum (Oracle.rotate_sum_deferred)
+    instead of one per rotated tap: same message, different bits, less rounding."""
     inter = {"mac": [], "rot": []}
     for t in range(len(geo.taps)):
         acc = None
         for i in range(geo.n_in):
             acc = orc.ptct_mac(acc, cts[i], pts[i, t], level, init=(i == 0))
         inter["mac"].append(acc)
+    if deferred:
+        gs = [orc.galois_elt(step) for step in geo.tap_steps]
+        total = orc.rotate_sum_deferred(inter["mac"], level, gs, [evks.get(step) for step in geo.tap_steps])
+        inter["sum"] = total
+        out = orc.rescale(total, level)
+        return (out, inter) if keep else out
     total = None
     for t, step in enumerate(geo.tap_steps):
         term = inter["mac"][t] if step == 0 else orc.rotate(inter["mac"][t], level, orc.galois_elt(step), evks[step])

@@ -374,6 +374,18 @@ void orc_rotate_from_raised(const orc_ctx* c, const u64* ct, const u64* raised, 
     free(rot); free(acc); free(s0);
 }
 
+/* out[l] = a[l] + b[l] mod the modulus listed for limb l (used to add key-switch accumulators over the
+ * raised basis q_0..q_level, p_*). */
+void orc_add_limbs(const orc_ctx* c, const u64* a, const u64* b, const uint32_t* mod_idx, uint32_t n_limbs, u64* out) {
+    for (uint32_t l = 0; l < n_limbs; l++) {
+        u64 m = c->mod[mod_idx[l]];
+        for (uint32_t n = 0; n < c->N; n++) {
+            size_t i = (size_t)l * c->N + n;
+            out[i] = addmod(a[i], b[i], m);
+        }
+    }
+}
+
 /* Rotation of a ciphertext ct = [2][level+1][N] by Galois element g with its key. */
 void orc_rotate(const orc_ctx* c, const u64* ct, uint32_t level, uint32_t g, const u64* evk, u64* out) {
     uint32_t N = c->N, R = level + 1 + c->np, beta = n_digits(c, level);

@@ -47,6 +47,7 @@ def lib():
         _lib.orc_psi.argtypes = [C.c_void_p, C.c_uint32]
         _lib.orc_num_digits.restype = C.c_uint32
         _lib.orc_num_digits.argtypes = [C.c_void_p, C.c_uint32]
+        _lib.orc_num_threads.restype = C.c_int
     return _lib
 
 
@@ -205,6 +206,45 @@ class Oracle:
         out = np.empty_like(ct)
         lib().orc_rotate_from_raised(self._h, _p(ct), _p(raised), C.c_uint32(level), C.c_uint32(g), _p(evk), _p(out))
         return out
+
+    def add_limbs(self, a, b, mod_idx):
+        """a + b per limb, limb l modulo moduli[mod_idx[l]]."""
+        a, b = _u64(a), _u64(b)
+        mi = _idx(mod_idx)
+        fa, fb = a.reshape(-1, self.N), b.reshape(-1, self.N)
+        assert fa.shape == fb.shape and fa.shape[0] == mi.size
+        out = np.empty_like(fa)
+        lib().orc_add_limbs(self._h, _p(fa), _p(fb), _p(mi, _u32p), C.c_uint32(mi.size), _p(out))
+        return out.reshape(a.shape)
+
+    def rotate_sum_deferred(self, cts, level, gs, evks):
+        """sum_t Rot(cts[t]; g_t) with the ModDown deferred across the sum (Slide_1 & Sum_f of the
+        paper's Algorithm 2 evaluated with a single ModDown): every rotated term is raised and multiplied
+        into its key on its own, the products are summed over the raised basis q_0..q_level, p_*, and only
+        the sum is brought down:
+            A_c   = sum_{t: g_t != 1} sum_j sigma_{g_t}(ModUp(c1_t)_j) * evk_t,j,c      (c = 0, 1)
+            out   = ( sum_{t: g_t != 1} sigma_{g_t}(c0_t) + ModDown(A_0) + sum_{t: g_t = 1} c0_t ,
+                      ModDown(A_1) + sum_{t: g_t = 1} c1_t ).
+        The result decrypts to the same sum as rotating term by term, but its bits differ (ModDown does
+        not distribute over sums), and it carries one ModDown's rounding instead of one per term.
+        cts: ciphertexts [2][level+1][N]; gs: Galois elements; evks[t]: key of g_t (ignored where g_t = 1)."""
+        L1, rm = level + 1, self.raised_moduli(level)
+        qm = list(range(L1))
+        acc = rot0 = plain = None
+        for ct, g, evk in zip(cts, gs, evks):
+            ct = _u64(ct)
+            if g == 1:
+                plain = ct if plain is None else self.add(plain, ct, level)
+                continue
+            raised = self.modup(ct[1], level)
+            ip = self.inner_product(self.automorph_ntt(raised, g), level, evk)
+            acc = ip if acc is None else self.add_limbs(acc, ip, rm + rm)
+            r0 = self.automorph_ntt(ct[0], g)
+            rot0 = r0 if rot0 is None else self.add_limbs(rot0, r0, qm)
+        if acc is None:
+            return plain
+        out = np.stack([self.add_limbs(self.moddown(acc[0], level), rot0, qm), self.moddown(acc[1], level)])
+        return out if plain is None else self.add(out, plain, level)
 
     # ---- MulPt accumulate, rescale, add
     def ptct_mac(self, acc, ct, pt, level, init):
