@@ -213,6 +213,19 @@ int32_t he_affine(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const uint6
  * drop that limb: d_ct [2][level+1][N] -> d_out [2][level][N], 1 <= level <= L. */
 int32_t he_rescale(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out);
 
+/* he_rescale for callers that cannot allocate device memory - code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc/hipFree.  Same arguments, same result bit for bit; its
+ * scratch ((2 + 2*level) * N residues) lives in a static device array of HE_NOALLOC_SCRATCH_BYTES that
+ * each GPU the library runs on holds until the process ends, instead of in the context's workspace.
+ * The call allocates and frees nothing on the device and never synchronises.  Levels whose scratch
+ * exceeds the array (level > 15 at N = 2^16) are refused with HE_ERR_BADARG, as is a call while
+ * he_profile_begin is active (launch timing creates events).  The context's device must be the current
+ * device.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two contexts, two threads) race; serialise them.  Nothing in the array has to survive or be
+ * cleared between calls. */
+#define HE_NOALLOC_SCRATCH_BYTES (16u << 20)
+int32_t he_rescale_noalloc(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out);
+
 /* Channel-aligned convolution CAConv (Section 3.1; Algorithm 1 for Slide_f and
  * MulFilter&Sum_f): Slide_f = hoisted rotations by (dy*W+dx)*R for the f^2 taps; for each
  * output o: sum over taps of rotated input * weight plaintext, Rescale, then rotate-and-sum

@@ -19,7 +19,7 @@ EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_addpt", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
-    "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d",
+    "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
 ]
 
 
@@ -91,6 +91,7 @@ def load():
         "he_ws_reserve": [vp, C.c_uint64],
         "he_ws_query_rotate_batch": [vp, u32, u32, u32, i32, u64p],
         "he_ws_query_conv2d": [vp, C.POINTER(ConvPlan), u64p],
+        "he_rescale_noalloc": [vp, vp, u32, vp],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -319,6 +320,12 @@ class HEContext:
         _need(ct, 2 * (level + 1) * self.N, "ct")
         _need(out, 2 * level * self.N, "out")
         self._ck(self._lib.he_rescale(self._h, _dev(ct), level, _dev(out)))
+        return out
+
+    def he_rescale_noalloc(self, ct, level, out):
+        _need(ct, 2 * (level + 1) * self.N, "ct")
+        _need(out, 2 * level * self.N, "out")
+        self._ck(self._lib.he_rescale_noalloc(self._h, _dev(ct), level, _dev(out)))
         return out
 
     # ---- convolution

@@ -193,6 +193,13 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
                 return rc;
         }
     }
+    {
+        int32_t rc = he_noalloc_init_device(c, c->device);
+        if (rc != HE_OK) {
+            g_create_err = c->err;
+            return rc;
+        }
+    }
     // workspace for every one-ciphertext call at the top level: one key switch (raised digits +
     // temporaries) with the three tensor-product polynomials of a ct x ct multiplication behind it, or
     // one rescale; only the batched calls and the convolutions can need more (he_ws_reserve)

@@ -112,6 +112,8 @@ static inline int32_t he_guard(const he_ctx* ctx, const char* who, F&& body) noe
         if (e__ != hipSuccess) return he_fail(ctx, HE_ERR_HIP, "%s: %s", #call, hipGetErrorString(e__)); \
     } while (0)
 
+int32_t he_noalloc_init_device(he_ctx* ctx, int device);   // noalloc.hip: address of the static scratch on this GPU
+
 // ---- internal device-work launchers (all enqueue on ctx->stream, none synchronises)
 #define HE_MAX_SEGS 16      // distinct source allocations one transform launch can read from
 #define HE_MAX_KS_JOBS 16   // key-switch jobs whose ModDown runs in one set of launches
