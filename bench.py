@@ -25,22 +25,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
-# vector-ALU issue peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = one wave64 instruction per SIMD every
-# 4 cycles; the rate at which 32-bit integer multiplies, 64-bit adds and fp64 FMAs issue on this chip
-ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_rotation_n65536_hbm_traffic.md")
 VALU_FILE = os.path.join(ROOT, "profiles", "bench_rotation_n65536_valu_instructions.md")
 
 
-def _profile_constant(path, key):
-    """A `key = integer` line of a committed rocprofv3 --pmc summary, or None if absent."""
+def _profile_constant(path, key, build_id):
+    """A `key = integer` line of a committed rocprofv3 --pmc summary, or None if the file is absent or was
+    taken on another build of the library (its `build_id = ...` line differs from the library being timed)."""
     try:
+        val, stamp = None, None
         for line in open(path):
             if line.startswith(key):
-                return int(line.split("=")[1])
+                val = int(line.split("=")[1])
+            if line.startswith("build_id"):
+                stamp = line.split("=")[1].strip()
+        return val if stamp == build_id else None
     except OSError:
-        pass
-    return None
+        return None
 
 
 def uniform_dev(torch, gen, moduli, N, lead=()):
@@ -162,42 +163,70 @@ def main():
         return e0.elapsed_time(e1) / reps
 
 
-    # roofline of the dominant kernel: one more, identical step with an event pair around every
+    # roofline of the dominant kernels: one more, identical step with an event pair around every
     # transform launch (kept out of the timed steps so the events do not perturb `value`)
     ctx.he_profile_begin()
     step()
     prof = ctx.he_profile_end()
+    build_id = ctx.he_build_id()
+    limb_bytes = N * 8
     passes_per_transform = 2 if prm.logN > 12 else 1
-    # algorithmic bytes: a limb transform must read and write the limb once (2*N*8 B), each of its
-    # launches credited an equal share; the passes that also compute the key-switch inner product
-    # must in addition read the raised digits once (N*8 B per digit limb; keys not counted)
-    alg_bytes = (prof["transform_limb_passes"] * (2.0 * N * 8) / passes_per_transform
-                 + prof["inner_product_digit_limbs"] * (N * 8.0))
-    achieved = alg_bytes / (prof["transform_ms"] * 1e-3) / 1e9
-    # per-limb-pass constants measured with rocprofv3 --pmc on this same command (profiles/)
-    bplp = _profile_constant(TRAFFIC_FILE, "transform_bytes_per_limb_pass")
-    ops = _profile_constant(VALU_FILE, "transform_valu_lane_ops_per_limb_pass")
+    # algorithmic bytes: a limb transform reads and writes its limb once (2*N*8 B = 1 MiB at N = 2^16);
+    # it runs as two passes, each credited half: 0.5 MiB per limb pass and nothing else
+    alg_bytes = prof["transform_limb_passes"] * (2.0 * limb_bytes) / passes_per_transform
     t_s = prof["transform_ms"] * 1e-3
     launches = max(1, prof["transform_launches"])
+    achieved = alg_bytes / t_s / 1e9
+    # per-limb-pass constants measured with rocprofv3 --pmc on this same command (profiles/); each summary is
+    # stamped with the build it was taken on and is not quoted for any other build
+    bplp = _profile_constant(TRAFFIC_FILE, "transform_bytes_per_limb_pass", build_id)
+    ops = _profile_constant(VALU_FILE, "transform_valu_lane_ops_per_limb_pass", build_id)
+    kinds = ["fwd_column", "fwd_row", "fwd_row_inner_product_moddown", "inv_row", "inv_row_inner_product", "inv_column"]
+    by_pass = {}
+    for i, name in enumerate(kinds):
+        if prof["pass_launches"][i]:
+            ms_i = prof["pass_ms"][i]
+            by_pass[name] = {"launches": prof["pass_launches"][i], "limb_passes": prof["pass_limbs"][i],
+                             "avg_launch_us": round(ms_i * 1e3 / prof["pass_launches"][i], 2),
+                             "us_per_limb_pass": round(ms_i * 1e3 / prof["pass_limbs"][i], 4),
+                             "frac": round(prof["pass_limbs"][i] * limb_bytes / (ms_i * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     roofline = {
-        "kernel": "ntt16_* (the four passes of the N=2^16 transform, incl. the fused inner product and ModDown epilogue)",
+        "kernel": "ntt16_* (the four passes of the N=2^16 transform, incl. the passes that carry the key-switch inner product and the ModDown epilogue)",
         "bound": "hbm",
-        "achieved": round(achieved, 1),          # algorithmic bytes (1 MiB per limb transform + digit reads) / time
+        "achieved": round(achieved, 1),          # 0.5 MiB per limb pass / time, nothing else counted
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": None if bplp is None else round(bplp * prof["transform_limb_passes"] / launches),
         "algorithmic_bytes_per_launch": round(alg_bytes / launches),
+        "limb_passes_per_launch": round(prof["transform_limb_passes"] / launches, 2),
         "measured_GBps": None if bplp is None else round(bplp * prof["transform_limb_passes"] / t_s / 1e9, 1),
         "launches": prof["transform_launches"],
         "avg_launch_us": round(prof["transform_ms"] * 1e3 / launches, 2),
         "share_of_step": round(prof["transform_ms"] / ms_per_step, 3),
+        "by_pass": by_pass,
+        # the same with the raised-digit limbs the inner-product passes have to read added (N*8 B each; keys not counted)
+        "frac_with_digit_reads": round((alg_bytes + prof["inner_product_digit_limbs"] * limb_bytes) / t_s / 1e9 / HBM_PEAK_GBS, 4),
+        "build_id": build_id,
     }
+    # second roof: vector-ALU issue.  Peak = radix-2 butterflies/s measured on this GPU in this run with the
+    # passes' own register blocks running out of registers (he_probe_alu); achieved = butterflies of the
+    # timed launches (N/2 * 8 stages per limb pass) / their time.  Narrow (q) and wide (special) primes
+    # are weighted by their share of the limb passes; the inverse rate by the inverse passes' share.
+    probe = ctx.he_probe_alu()
+    bf_per_pass = (N // 2) * (prm.logN // passes_per_transform)
+    inv_share = (prof["pass_limbs"][3] + prof["pass_limbs"][4] + prof["pass_limbs"][5]) / max(1, prof["transform_limb_passes"])
+    fwd_rate = probe["fwd_butterflies_per_s"]
+    inv_rate = probe["inv_butterflies_per_s"] or fwd_rate
+    peak_bf = 1.0 / ((1.0 - inv_share) / fwd_rate + inv_share / inv_rate)
+    ach_bf = prof["transform_limb_passes"] * bf_per_pass / t_s
+    roofline["alu"] = {"achieved": round(ach_bf / 1e12, 3), "peak": round(peak_bf / 1e12, 3), "unit": "T butterfly/s",
+                       "frac": round(ach_bf / peak_bf, 4),
+                       "probe": {k_: round(v / 1e12, 3) for k_, v in probe.items()},
+                       "note": "butterflies only; conversions, inner products and epilogues issued by the same kernels are extra ALU work not counted in achieved"}
     if ops is not None:
-        # second roof: vector-ALU issue (64-bit modular arithmetic built from 32-bit multiplies)
-        a = ops * prof["transform_limb_passes"] / t_s / 1e12
-        roofline["alu"] = {"achieved": round(a, 2), "peak": round(ALU_PEAK_TOPS, 2), "unit": "T lane-op/s",
-                           "frac": round(a / ALU_PEAK_TOPS, 4)}
+        roofline["alu"]["valu_lane_ops_per_limb_pass"] = ops
+        roofline["alu"]["lane_ops_per_s_T"] = round(ops * prof["transform_limb_passes"] / t_s / 1e12, 2)
 
     extras = {}
     if not args.no_extras:
@@ -207,13 +236,23 @@ def main():
         ms_hoisted = timed(lambda: ctx.he_rotate_batch(cts, level, steps15, outs, hoisted=True), reps=2)
         ms_one_single = timed(lambda: [ctx.he_rotate(cts[0], level, s, outs[i]) for i, s in enumerate(steps15)])
         ms_one_hoisted = timed(lambda: ctx.he_rotate_hoisted(cts[0], level, steps15, outs[:15]))
-        # the whole key switch against the HBM roof: compulsory bytes of one key switch with its own key =
-        # input 24 + key 192 + outputs 48 limbs of N*8 B (what a fully fused pipeline would have to move)
-        ks_bytes = (L1 + 2 * prm.dnum * (L1 + k) + 2 * L1) * N * 8
+        # the whole key switch against the HBM roof.  Compulsory bytes of one key switch = input polynomial
+        # (L1 limbs) + outputs (2*L1 limbs) + its share of the key (2*dnum*(L1+k) limbs).  Loop order of this
+        # engine: rotations are ordered step-major within a wave of 8 raised sources and run in launch sets
+        # of up to 10 jobs; jobs of a set that use the same key share one pass over it, so the key is counted
+        # once per (launch set, key) - the engine reports those key limbs (key_limbs_read).  The own-key
+        # figure (every key switch reads its whole key) is given beside it.
+        own_bytes = (L1 + 2 * prm.dnum * (L1 + k) + 2 * L1) * limb_bytes
+        sched_bytes = (3 * L1) * limb_bytes + prof["key_limbs_read"] * limb_bytes / ks_per_step
+        rate_s, rate_h = 15 * B / (ms_single * 1e-3), 15 * B / (ms_hoisted * 1e-3)
         roofline["keyswitch"] = {
-            "compulsory_bytes": ks_bytes,
-            "frac_single": round(15 * B / (ms_single * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
-            "frac_hoisted": round(15 * B / (ms_hoisted * 1e-3) * ks_bytes / 1e9 / HBM_PEAK_GBS, 4),
+            "loop_order": "step-major; 8 sources raised per wave; launch sets of <= 10 jobs; one key pass per (launch set, key)",
+            "bytes_as_scheduled": round(sched_bytes),
+            "frac_single": round(rate_s * sched_bytes / 1e9 / HBM_PEAK_GBS, 4),
+            "frac_hoisted": round(rate_h * sched_bytes / 1e9 / HBM_PEAK_GBS, 4),
+            "bytes_own_key": own_bytes,
+            "frac_single_own_key": round(rate_s * own_bytes / 1e9 / HBM_PEAK_GBS, 4),
+            "frac_hoisted_own_key": round(rate_h * own_bytes / 1e9 / HBM_PEAK_GBS, 4),
         }
         extras.update({
             "single_keyswitch_per_s": round(15 * B / (ms_single * 1e-3), 1),
@@ -287,8 +326,12 @@ def main():
         # the layer that consumes those 8 outputs: reordered RAConv (Algorithm 2), 8 inputs x 9 taps at level 22
         ra_w = [w[:level] for w in weights]
         ra_out = torch.empty((2, level - 1, N), dtype=torch.uint64, device="cuda")
-        ms_ra = timed(lambda: ctx.he_raconv(32, 2, 3, level - 1, ra_w, conv_out, ra_out), reps=3)
+        ms_ra = timed(lambda: ctx.he_raconv(32, 2, 3, level - 1, ra_w, conv_out, ra_out), reps=5)
         extras["raconv_ms"] = round(ms_ra, 3)
+        # the same layer with Slide_1&Sum_f sharing one ModDown across its eight rotations
+        ctx.he_ws_reserve(ctx.he_ws_query_raconv(8, 32, 2, 3, level - 1, deferred=True))
+        ms_ra = timed(lambda: ctx.he_raconv(32, 2, 3, level - 1, ra_w, conv_out, ra_out, deferred=True), reps=5)
+        extras["raconv_one_moddown_ms"] = round(ms_ra, 3)
         # sum across the gap and re-replication after that RAConv (two channels per ciphertext): 2 rotations,
         # one mask multiplication, one rescale, level 21 -> 20
         from paper_2302_02407_amd import block as blk

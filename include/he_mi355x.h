@@ -53,13 +53,14 @@ typedef enum {
  * rotations per stage; these let a caller check CAConv issues f^2-1 Slide + n_o*log2(C_a) RaS
  * key switches and no other). */
 typedef struct {
-    uint64_t keyswitch;   /* inner product + ModDown pairs executed */
+    uint64_t keyswitch;   /* key-switch inner products executed (one per rotation / relinearisation) */
     uint64_t modup;       /* digit decompositions (ModUp of one polynomial) */
     uint64_t ntt_limbs;   /* forward limb transforms */
     uint64_t intt_limbs;  /* inverse limb transforms */
     uint64_t mac;         /* plaintext-ciphertext products accumulated */
     uint64_t rescale;     /* ciphertext rescales */
     uint64_t automorph;   /* limb permutations (explicit calls and c0 of rotations) */
+    uint64_t moddown;     /* ModDowns of an accumulator pair (equals keyswitch unless a sum of rotations shared one) */
 } he_counters_t;
 
 /* Geometry and operands of one channel-aligned convolution (paper Section 3.1, CAConv on the
@@ -84,6 +85,8 @@ typedef struct {
     uint32_t W, R;               /* image row length and inner slot stride */
     uint32_t f;                  /* odd filter width */
     uint32_t level;              /* level of the inputs; the output is at level-1 */
+    uint32_t deferred_moddown;   /* 0: every off-centre tap is rotated completely, then added; 1: Slide_1&Sum_f as
+                                    he_rotate_sum with deferred != 0 (one ModDown for the sum of the f^2-1 rotations) */
     const uint64_t* const* h_d_weights; /* host array of n_in*f*f device pointers */
 } he_raconv_plan;
 
@@ -108,15 +111,37 @@ int32_t he_counters_reset(he_ctx* ctx);
  * he_profile_end synchronises the stream, sums the spans and stops.  transform_limb_passes
  * counts limbs per launch (a full NTT of one limb at N > 2^12 is two launches = two passes).
  * inner_product_digit_limbs counts the raised-digit limbs that passes carrying the key-switch
- * inner product have to read besides their own limb (N = 2^16 path; 0 elsewhere). */
+ * inner product have to read besides their own limb (N = 2^16 path; 0 elsewhere).
+ * pass_* split the same launches by kind: 0 forward column pass, 1 forward row pass, 2 forward row
+ * pass carrying the inner product of the q-limbs and the ModDown epilogue, 3 inverse row pass,
+ * 4 inverse row pass computing the inner product of the special-prime limbs, 5 inverse column pass.
+ * key_limbs_read counts the evaluation-key limbs the inner products had to read in the order the
+ * engine ran them (one pass over a key per group of same-key jobs of a launch set). */
 typedef struct {
     uint64_t transform_launches;
     uint64_t transform_limb_passes;
     uint64_t inner_product_digit_limbs;
     double transform_ms;
+    uint64_t pass_launches[6];
+    uint64_t pass_limbs[6];
+    double pass_ms[6];
+    uint64_t key_limbs_read;
 } he_profile_t;
 int32_t he_profile_begin(he_ctx* ctx);
 int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out);
+/* Vector-ALU roof of the transforms on this GPU, measured: radix-2 butterflies per second when the
+ * register blocks of the N = 2^16 passes (Shoup twiddle product from 32-bit multiplies, lazy ranges)
+ * run back to back out of registers: forward and inverse on the first ciphertext prime, forward on
+ * the first modulus wider than 57 bits (0 if there is none).  Synchronises the stream. */
+typedef struct {
+    double fwd_butterflies_per_s;
+    double inv_butterflies_per_s;
+    double fwd_wide_butterflies_per_s;
+} he_alu_probe_t;
+int32_t he_probe_alu(he_ctx* ctx, he_alu_probe_t* h_out);
+/* Identifies the build: hash of the library's sources taken when it was compiled (so that counter
+ * summaries taken on one build are not quoted for another). */
+const char* he_build_id(void);
 /* Block until everything enqueued on the context's stream has finished. */
 int32_t he_sync(he_ctx* ctx);
 
@@ -179,6 +204,15 @@ int32_t he_rotate_batch(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_c
                         const int32_t* h_steps, uint32_t n_steps, uint64_t* const* h_d_out, int32_t hoisted);
 int32_t he_ws_query_rotate_batch(const he_ctx* ctx, uint32_t level, uint32_t n_ct, uint32_t n_steps, int32_t hoisted,
                                  uint64_t* h_bytes);
+/* Slide_1 & Sum_f of Algorithm 2: d_out = sum over t < n_ct of CRot(h_d_ct[t]; h_steps[t]), all ciphertexts
+ * [2][level+1][N] at `level` (a step of 0 adds the ciphertext as it is), 1 <= n_ct <= 49; d_out must not overlap an
+ * input.  deferred == 0: every rotation is completed on its own (same bits as he_rotate followed by he_add).
+ * deferred != 0: the rotations share ONE ModDown - each term's raised digits are multiplied into its key, the
+ * products are summed over q_0..q_level,p_*, and the sum is brought down once; out0 also gets the sum of the rotated c0
+ * parts.  The result encrypts the same sum with one ModDown's rounding instead of one per rotation, and differs in
+ * bits from the deferred == 0 result.  Grows the workspace with n_ct (all raised digits are live at once). */
+int32_t he_rotate_sum(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level, const int32_t* h_steps,
+                      uint64_t* d_out, int32_t deferred);
 /* CRot(ct; step): identical bits to he_rotate_hoisted with n_steps = 1. */
 int32_t he_rotate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, int32_t step, uint64_t* d_out);
 /* Slot-wise complex conjugation (Galois element 2N-1, key registered under 2N-1). */
@@ -242,6 +276,7 @@ int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* plan, uint64_t
  * [2][level][N], must not overlap an input.  Needs keys for every non-zero tap amount.
  * Grows the context workspace on first use (allocates). */
 int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* d_ct_out);
+int32_t he_ws_query_raconv(const he_ctx* ctx, const he_raconv_plan* plan, uint64_t* h_bytes);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,7 @@ EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_addpt", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
-    "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
+    "he_probe_alu", "he_build_id", "he_rotate_sum", "he_ws_query_raconv", "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
 ]
 
 
@@ -30,12 +30,19 @@ class HEError(RuntimeError):
 
 
 class Counters(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in ("keyswitch", "modup", "ntt_limbs", "intt_limbs", "mac", "rescale", "automorph")]
+    _fields_ = [(n, C.c_uint64) for n in ("keyswitch", "modup", "ntt_limbs", "intt_limbs", "mac", "rescale", "automorph", "moddown")]
 
 
 class Profile(C.Structure):
     _fields_ = [("transform_launches", C.c_uint64), ("transform_limb_passes", C.c_uint64),
-                ("inner_product_digit_limbs", C.c_uint64), ("transform_ms", C.c_double)]
+                ("inner_product_digit_limbs", C.c_uint64), ("transform_ms", C.c_double),
+                ("pass_launches", C.c_uint64 * 6), ("pass_limbs", C.c_uint64 * 6), ("pass_ms", C.c_double * 6),
+                ("key_limbs_read", C.c_uint64)]
+
+
+class AluProbe(C.Structure):
+    _fields_ = [("fwd_butterflies_per_s", C.c_double), ("inv_butterflies_per_s", C.c_double),
+                ("fwd_wide_butterflies_per_s", C.c_double)]
 
 
 class ConvPlan(C.Structure):
@@ -45,7 +52,7 @@ class ConvPlan(C.Structure):
 
 class RaConvPlan(C.Structure):
     _fields_ = [("n_in", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32), ("level", C.c_uint32),
-                ("h_d_weights", C.POINTER(C.c_void_p))]
+                ("deferred_moddown", C.c_uint32), ("h_d_weights", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -70,6 +77,7 @@ def load():
         "he_sync": [vp],
         "he_profile_begin": [vp],
         "he_profile_end": [vp, C.POINTER(Profile)],
+        "he_probe_alu": [vp, C.POINTER(AluProbe)],
         "he_ntt": [vp, vp, u32p, u32],
         "he_intt": [vp, vp, u32p, u32],
         "he_automorph": [vp, vp, vp, u32p, u32, u32, i32],
@@ -78,6 +86,8 @@ def load():
         "he_rotate_hoisted": [vp, vp, u32, i32p, u32, C.POINTER(vp)],
         "he_rotate_batch": [vp, C.POINTER(vp), u32, u32, i32p, u32, C.POINTER(vp), i32],
         "he_rotate": [vp, vp, u32, i32, vp],
+        "he_rotate_sum": [vp, C.POINTER(vp), u32, u32, i32p, vp, i32],
+        "he_ws_query_raconv": [vp, C.POINTER(RaConvPlan), u64p],
         "he_conjugate": [vp, vp, u32, vp],
         "he_ptct_mac": [vp, vp, vp, vp, u32, i32],
         "he_add": [vp, vp, vp, u32, vp],
@@ -99,6 +109,8 @@ def load():
         fn.restype = i32
     lib.he_last_error.argtypes = [vp]
     lib.he_last_error.restype = C.c_char_p
+    lib.he_build_id.argtypes = []
+    lib.he_build_id.restype = C.c_char_p
     _lib = lib
     return lib
 
@@ -187,7 +199,15 @@ class HEContext:
     def he_profile_end(self):
         p = Profile()
         self._ck(self._lib.he_profile_end(self._h, C.byref(p)))
-        return {n: getattr(p, n) for n, _ in Profile._fields_}
+        return {n: (list(getattr(p, n)) if n.startswith("pass_") else getattr(p, n)) for n, _ in Profile._fields_}
+
+    def he_probe_alu(self):
+        p = AluProbe()
+        self._ck(self._lib.he_probe_alu(self._h, C.byref(p)))
+        return {n: getattr(p, n) for n, _ in AluProbe._fields_}
+
+    def he_build_id(self):
+        return self._lib.he_build_id().decode()
 
     def galois_elt(self, step):
         return pow(5, step % (self.N // 2), 2 * self.N)
@@ -268,6 +288,18 @@ class HEContext:
         self._ck(self._lib.he_rotate_batch(self._h, ca, len(cts), level, sa, len(steps), oa, 1 if hoisted else 0))
         return outs
 
+    def he_rotate_sum(self, cts, level, steps, out, deferred=False):
+        """out = sum_t CRot(cts[t]; steps[t]); deferred=True shares one ModDown across the sum."""
+        steps = [int(s) for s in steps]
+        if len(cts) != len(steps):
+            raise ValueError("one step per ciphertext")
+        for t in list(cts) + [out]:
+            _need(t, 2 * (level + 1) * self.N, "ciphertext")
+        sa = (C.c_int32 * max(1, len(steps)))(*steps)
+        ca = (C.c_void_p * max(1, len(cts)))(*[_dev(c).value for c in cts])
+        self._ck(self._lib.he_rotate_sum(self._h, ca, len(cts), level, sa, _dev(out), 1 if deferred else 0))
+        return out
+
     def he_rotate(self, ct, level, step, out):
         _need(ct, 2 * (level + 1) * self.N, "ct")
         _need(out, 2 * (level + 1) * self.N, "out")
@@ -345,7 +377,13 @@ class HEContext:
         self._ck(self._lib.he_conv2d(self._h, C.byref(plan), _dev(ct_in), oa))
         return outs
 
-    def he_raconv(self, W, R, f, level, weights, cts_in, out):
+    def he_ws_query_raconv(self, n_in, W, R, f, level, deferred=False):
+        v = C.c_uint64()
+        plan = RaConvPlan(n_in, W, R, f, level, 1 if deferred else 0, None)
+        self._ck(self._lib.he_ws_query_raconv(self._h, C.byref(plan), C.byref(v)))
+        return v.value
+
+    def he_raconv(self, W, R, f, level, weights, cts_in, out, deferred=False):
         """weights: list of n_in*f*f device tensors [level+1][N] (input-major); cts_in: n_in tensors
         [2][level+1][N]; out: [2][level][N]."""
         n_in = len(cts_in)
@@ -358,6 +396,6 @@ class HEContext:
         _need(out, 2 * level * self.N, "out")
         wa = (C.c_void_p * len(weights))(*[_dev(w).value for w in weights])
         ia = (C.c_void_p * n_in)(*[_dev(c).value for c in cts_in])
-        plan = RaConvPlan(n_in, W, R, f, level, C.cast(wa, C.POINTER(C.c_void_p)))
+        plan = RaConvPlan(n_in, W, R, f, level, 1 if deferred else 0, C.cast(wa, C.POINTER(C.c_void_p)))
         self._ck(self._lib.he_raconv(self._h, C.byref(plan), ia, _dev(out)))
         return out

@@ -25,6 +25,16 @@ def _run(cmd, verbose):
         print(out)
 
 
+def source_hash() -> str:
+    """sha256 over the library's sources and headers (the build identifier compiled into the library)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(SOURCES) + sorted(HEADERS):
+        with open(os.path.join(CSRC, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def build_library(verbose: bool = True, incremental: bool = False) -> str:
     """Compile every HIP source for gfx950 (one object per source, in parallel) and link them into one
     shared library next to this file.  incremental=True skips objects newer than their source and the
@@ -33,11 +43,13 @@ def build_library(verbose: bool = True, incremental: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     newest_header = max(os.path.getmtime(os.path.join(CSRC, h)) for h in HEADERS)
     jobs = []
+    build_id = source_hash()
     for s in SOURCES:
         src, obj = os.path.join(CSRC, s), os.path.join(OBJ, s + ".o")
-        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+        if incremental and s != "ctx.hip" and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
             continue
-        jobs.append([hipcc] + FLAGS + ["-c", src, "-o", obj])
+        extra = ['-DHE_BUILD_ID="%s"' % build_id] if s == "ctx.hip" else []
+        jobs.append([hipcc] + FLAGS + extra + ["-c", src, "-o", obj])
     with ThreadPoolExecutor(max_workers=8) as ex:
         list(ex.map(lambda c: _run(c, verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + [os.path.join(OBJ, s + ".o") for s in SOURCES]

@@ -306,6 +306,99 @@ __global__ __launch_bounds__(CV_THREADS) void sum_cts_kernel(SumList l, u64* out
     out[o] = acc;
 }
 
+// Slide_1 & Sum_f (Algorithm 2): total = sum_t Rot(term_t) over ciphertexts at `level`, term t rotated by the Galois
+// element g[t] with key[t] (g = 1: added as it is).  deferred = false: one complete rotation per term, then
+// additions; deferred = true: one ModDown for the whole sum.  `total` may alias term 0 only when !deferred.
+// ws: slide1_sum_ws_elems elements.
+static size_t slide1_sum_ws_elems(const he_ctx* ctx, uint32_t level, uint32_t n_rot, bool deferred) {
+    if (n_rot == 0) return 0;
+    if (deferred) return ks_rotate_sum_ws_elems(ctx, level, n_rot);
+    return ks_engine_ws_elems(ctx, level, n_rot, n_rot) + (size_t)n_rot * 2 * (level + 1) * ctx->N;
+}
+
+static int32_t slide1_sum(he_ctx* ctx, uint32_t level, const u64* const* cts, const uint32_t* g, const u64* const* key, uint32_t n,
+                          bool deferred, u64* total, u64* ws) {
+    const uint32_t N = ctx->N, L1 = level + 1;
+    const size_t ct_e = (size_t)2 * L1 * N;
+    uint32_t n_rot = 0;
+    for (uint32_t t = 0; t < n; t++) n_rot += g[t] != 1;
+    if (deferred && n_rot) {
+        std::vector<KsSumTerm> terms(n);
+        for (uint32_t t = 0; t < n; t++) terms[t] = {cts[t], cts[t] + (size_t)L1 * N, g[t], key[t]};
+        return ks_rotate_sum_deferred(ctx, level, terms.data(), n, total, total + (size_t)L1 * N, ws);
+    }
+    SumList sl;
+    sl.n = 0;
+    if (n_rot) {
+        u64* rot = ws + ks_engine_ws_elems(ctx, level, n_rot, n_rot);   // [n_rot] rotated terms behind the engine's region
+        std::vector<KsSrc> srcs;
+        std::vector<KsJob> jobs;
+        for (uint32_t t = 0; t < n; t++) {
+            if (g[t] == 1) { sl.in[sl.n++] = cts[t]; continue; }
+            u64* out = rot + (size_t)srcs.size() * ct_e;
+            jobs.push_back({(uint32_t)srcs.size(), g[t], key[t], out, out + (size_t)L1 * N, 0});
+            srcs.push_back({cts[t], cts[t] + (size_t)L1 * N, nullptr, nullptr});
+            sl.in[sl.n++] = out;
+        }
+        int32_t rc = ks_engine(ctx, level, srcs.data(), (uint32_t)srcs.size(), jobs.data(), (uint32_t)jobs.size());
+        if (rc != HE_OK) return rc;
+    } else {
+        for (uint32_t t = 0; t < n; t++) sl.in[sl.n++] = cts[t];
+    }
+    hipLaunchKernelGGL(sum_cts_kernel, dim3(N / CV_THREADS, 2 * L1), dim3(CV_THREADS), 0, ctx->stream, sl, total, ctx->d_mc, ctx->logN, L1);
+    HE_HIP(ctx, hipGetLastError());
+    return HE_OK;
+}
+
+extern "C" int32_t he_rotate_sum(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level, const int32_t* h_steps,
+                                 uint64_t* d_out, int32_t deferred) {
+    return he_guard(ctx, "he_rotate_sum: host allocation failed", [&]() -> int32_t {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!h_d_ct || !h_steps || !d_out) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_sum: null argument");
+    if (n_ct == 0 || n_ct > CV_MAX_TAPS) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_sum: between 1 and %d terms", CV_MAX_TAPS);
+    if (ctx->np == 0) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_sum: context has no special primes");
+    if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_rotate_sum: level %u above L=%u", level, ctx->nq - 1);
+    const uint32_t N = ctx->N, L1 = level + 1;
+    const size_t ct_b = (size_t)2 * L1 * N * sizeof(u64);
+    std::vector<uint32_t> g(n_ct);
+    std::vector<const u64*> key(n_ct, nullptr), cts(n_ct);
+    uint32_t n_rot = 0;
+    for (uint32_t t = 0; t < n_ct; t++) {
+        if (!h_d_ct[t]) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_sum: ciphertext %u is null", t);
+        const char *a = (const char*)h_d_ct[t], *b = (const char*)d_out;
+        if (a < b + ct_b && b < a + ct_b) return he_fail(ctx, HE_ERR_BADARG, "he_rotate_sum: the output overlaps ciphertext %u", t);
+        cts[t] = (const u64*)h_d_ct[t];
+        g[t] = h_galois_of_step(ctx, h_steps[t]);
+        if (g[t] == 1) continue;
+        auto it = ctx->evk.find(g[t]);
+        if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_rotate_sum: no key for step %d (Galois element %u)", h_steps[t], g[t]);
+        key[t] = it->second;
+        n_rot++;
+    }
+    int32_t rc = he_ensure_ws(ctx, slide1_sum_ws_elems(ctx, level, n_rot, deferred != 0) * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    return slide1_sum(ctx, level, cts.data(), g.data(), key.data(), n_ct, deferred != 0, (u64*)d_out, ctx->d_ws);
+    });
+}
+
+// he_raconv workspace: [Slide_1 & Sum_f region][rescale scratch][taps accumulators][the sum (deferred only)]
+static size_t raconv_ws_elems(const he_ctx* ctx, uint32_t level, uint32_t taps, uint32_t n_rot, bool deferred) {
+    const size_t ct_e = (size_t)2 * (level + 1) * ctx->N;
+    return slide1_sum_ws_elems(ctx, level, n_rot, deferred) + rescale_ws_elems(ctx, level, 1) + (size_t)(taps + (deferred ? 1 : 0)) * ct_e;
+}
+
+extern "C" int32_t he_ws_query_raconv(const he_ctx* ctx, const he_raconv_plan* plan, uint64_t* h_bytes) {
+    return he_guard(ctx, "he_ws_query_raconv: host allocation failed", [&]() -> int32_t {
+    if (!ctx || !plan || !h_bytes) return HE_ERR_BADARG;
+    if (plan->level == 0 || plan->level >= ctx->nq) return HE_ERR_LEVEL;
+    if ((plan->f & 1u) == 0 || plan->f * plan->f > CV_MAX_TAPS || plan->n_in == 0) return HE_ERR_BADARG;
+    uint32_t n_rot = 0;
+    for (uint32_t st : tap_slot_steps(plan->W, plan->R, plan->f, ctx->N / 2)) n_rot += st != 0;
+    *h_bytes = raconv_ws_elems(ctx, plan->level, plan->f * plan->f, n_rot, plan->deferred_moddown != 0) * sizeof(u64);
+    return HE_OK;
+    });
+}
+
 extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* d_ct_out) {
     return he_guard(ctx, "he_raconv: host allocation failed", [&]() -> int32_t {
     if (!ctx) return HE_ERR_BADARG;
@@ -318,18 +411,16 @@ extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint
     if (plan->W == 0 || plan->R == 0 || (u64)plan->W * plan->R * f > slots)
         return he_fail(ctx, HE_ERR_BADARG, "he_raconv: row length %u x stride %u does not fit the slots", plan->W, plan->R);
     const uint32_t L1 = level + 1;
+    const bool deferred = plan->deferred_moddown != 0;
+    const std::vector<uint32_t> steps = tap_slot_steps(plan->W, plan->R, f, slots);
     std::vector<uint32_t> tap_g(taps);
     std::vector<const u64*> tap_key(taps, nullptr);
-    const int32_t half = (int32_t)(f - 1) / 2;
     uint32_t n_rot = 0;
     for (uint32_t t = 0; t < taps; t++) {
-        int32_t dy = (int32_t)(t / f) - half, dx = (int32_t)(t % f) - half;
-        int64_t step = ((int64_t)dy * plan->W + dx) * plan->R;
-        step = ((step % (int64_t)slots) + slots) % slots;
-        tap_g[t] = h_galois_of_step(ctx, (int32_t)step);
+        tap_g[t] = h_galois_of_step(ctx, (int32_t)steps[t]);
         if (tap_g[t] != 1) {
             auto it = ctx->evk.find(tap_g[t]);
-            if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_raconv: no key for tap rotation %lld", (long long)step);
+            if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_raconv: no key for tap rotation %u", steps[t]);
             tap_key[t] = it->second;
             n_rot++;
         }
@@ -338,16 +429,14 @@ extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint
         if (!h_d_ct_in[i]) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: input %u is null", i);
     for (uint32_t i = 0; i < n_in * taps; i++)
         if (!plan->h_d_weights[i]) return he_fail(ctx, HE_ERR_BADARG, "he_raconv: weight plaintext %u is null", i);
-    // workspace: [key-switch engine region][rescale scratch][taps accumulators][n_rot rotated accumulators]
     const size_t ct_e = (size_t)2 * L1 * N;
-    const size_t ks_e = n_rot ? ks_engine_ws_elems(ctx, level, n_rot, n_rot) : 0;
-    const size_t rs_e = rescale_ws_elems(ctx, level, 1);
-    int32_t rc = he_ensure_ws(ctx, (ks_e + rs_e + (size_t)(taps + n_rot) * ct_e) * sizeof(u64));
+    const size_t sl_e = slide1_sum_ws_elems(ctx, level, n_rot, deferred), rs_e = rescale_ws_elems(ctx, level, 1);
+    int32_t rc = he_ensure_ws(ctx, raconv_ws_elems(ctx, level, taps, n_rot, deferred) * sizeof(u64));
     if (rc != HE_OK) return rc;
-    u64* rs_ws = ctx->d_ws + ks_e;
+    u64* rs_ws = ctx->d_ws + sl_e;
     u64* acc = rs_ws + rs_e;                              // [taps] ciphertexts at `level`
-    u64* rot = acc + (size_t)taps * ct_e;                 // [n_rot]
-
+    u64* total = deferred ? acc + (size_t)taps * ct_e : acc;   // not deferred: the sum overwrites the first accumulator
+                                                               // (each element is read before it is written)
     // MulFilter&Sum_ci: per tap, the sum over all inputs of input x inversely rotated filter
     {
         dim3 grid(N / CV_THREADS, L1), block(CV_THREADS);
@@ -368,34 +457,15 @@ extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint
         }
         ctx->cnt.mac += (uint64_t)taps * n_in;
     }
-    // Slide_1&Sum_f: one rotation per off-centre tap (each accumulator is its own source), then additions
-    SumList sl;
-    sl.n = 0;
-    if (n_rot) {
-        std::vector<KsSrc> srcs;
-        std::vector<KsJob> jobs;
-        for (uint32_t t = 0; t < taps; t++) {
-            const u64* a = acc + (size_t)t * ct_e;
-            if (tap_g[t] == 1) { sl.in[sl.n++] = a; continue; }
-            u64* out = rot + (size_t)srcs.size() * ct_e;
-            jobs.push_back({(uint32_t)srcs.size(), tap_g[t], tap_key[t], out, out + (size_t)L1 * N, 0});
-            srcs.push_back({a, a + (size_t)L1 * N, nullptr, nullptr});
-            sl.in[sl.n++] = out;
-        }
-        rc = ks_engine(ctx, level, srcs.data(), (uint32_t)srcs.size(), jobs.data(), (uint32_t)jobs.size());
+    // Slide_1&Sum_f: one rotation per off-centre tap (each accumulator is its own source) and additions
+    const u64* rin = acc;
+    if (taps > 1) {
+        std::vector<const u64*> cts(taps);
+        for (uint32_t t = 0; t < taps; t++) cts[t] = acc + (size_t)t * ct_e;
+        rc = slide1_sum(ctx, level, cts.data(), tap_g.data(), tap_key.data(), taps, deferred, total, ctx->d_ws);
         if (rc != HE_OK) return rc;
-    } else {
-        for (uint32_t t = 0; t < taps; t++) sl.in[sl.n++] = acc + (size_t)t * ct_e;
+        rin = total;
     }
-    u64* total = acc;                                    // the sum overwrites the first accumulator (read before written per element)
-    if (sl.n > 1) {
-        hipLaunchKernelGGL(sum_cts_kernel, dim3(N / CV_THREADS, 2 * L1), dim3(CV_THREADS), 0, ctx->stream, sl, total, ctx->d_mc,
-                           ctx->logN, L1);
-        HE_HIP(ctx, hipGetLastError());
-    } else {
-        total = (u64*)sl.in[0];
-    }
-    const u64* rin = total;
     u64* rout = (u64*)d_ct_out;
     return rescale_batch(ctx, &rin, &rout, 1, level, rs_ws);
     });

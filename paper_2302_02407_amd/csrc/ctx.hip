@@ -264,6 +264,7 @@ int32_t he_profile_begin(he_ctx* ctx) {
     if (!ctx) return HE_ERR_BADARG;
     for (auto& s : ctx->prof_events) { (void)hipEventDestroy(s.e0); (void)hipEventDestroy(s.e1); }
     ctx->prof_events.clear();
+    ctx->prof_key_limbs = 0;
     ctx->prof_on = true;
     return HE_OK;
     });
@@ -274,10 +275,7 @@ int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out) {
     if (!ctx || !h_out) return HE_ERR_BADARG;
     ctx->prof_on = false;
     HE_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    h_out->transform_launches = 0;
-    h_out->transform_limb_passes = 0;
-    h_out->inner_product_digit_limbs = 0;
-    h_out->transform_ms = 0.0;
+    memset(h_out, 0, sizeof(*h_out));
     for (auto& s : ctx->prof_events) {
         float ms = 0.f;
         HE_HIP(ctx, hipEventElapsedTime(&ms, s.e0, s.e1));
@@ -285,13 +283,39 @@ int32_t he_profile_end(he_ctx* ctx, he_profile_t* h_out) {
         h_out->transform_limb_passes += s.limbs;
         h_out->inner_product_digit_limbs += s.digit_limbs;
         h_out->transform_ms += ms;
+        const uint32_t kd = s.kind < 6 ? s.kind : 0;
+        h_out->pass_launches[kd] += 1;
+        h_out->pass_limbs[kd] += s.limbs;
+        h_out->pass_ms[kd] += ms;
         (void)hipEventDestroy(s.e0);
         (void)hipEventDestroy(s.e1);
     }
+    h_out->key_limbs_read = ctx->prof_key_limbs;
     ctx->prof_events.clear();
     return HE_OK;
     });
 }
+
+int32_t he_probe_alu(he_ctx* ctx, he_alu_probe_t* h_out) {
+    return he_guard(ctx, "he_probe_alu: host allocation failed", [&]() -> int32_t {
+    if (!ctx || !h_out) return HE_ERR_BADARG;
+    const uint32_t groups = 256 * 16;                    // 16 work groups of 256 threads per compute unit
+    int32_t rc = he_ensure_ws(ctx, (size_t)groups * 256 * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    double r[3];
+    rc = probe_butterfly_rates(ctx, ctx->d_ws, groups, r);
+    if (rc != HE_OK) return rc;
+    h_out->fwd_butterflies_per_s = r[0];
+    h_out->inv_butterflies_per_s = r[1];
+    h_out->fwd_wide_butterflies_per_s = r[2];
+    return HE_OK;
+    });
+}
+
+#ifndef HE_BUILD_ID
+#define HE_BUILD_ID "unknown"
+#endif
+const char* he_build_id(void) { return HE_BUILD_ID; }
 
 int32_t he_sync(he_ctx* ctx) {
     return he_guard(ctx, "he_sync: host allocation failed", [&]() -> int32_t {

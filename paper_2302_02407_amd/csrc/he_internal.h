@@ -45,6 +45,8 @@ struct ProfSpan {
     hipEvent_t e0, e1;
     uint32_t limbs;   // limbs transformed by the launch between the two events
     uint32_t digit_limbs; // raised-digit limbs a pass that carries the key-switch inner product has to read
+    uint32_t kind;        // he_profile_t::pass_ms index: 0 fwd column, 1 fwd row, 2 fwd row + inner product/epilogue,
+                          // 3 inv row, 4 inv row + inner product, 5 inv column
 };
 
 struct he_ctx {
@@ -78,6 +80,7 @@ struct he_ctx {
     he_counters_t cnt;
     bool prof_on;                       // time every transform launch with an event pair
     std::vector<ProfSpan> prof_events;
+    uint64_t prof_key_limbs;            // key limbs the inner products had to read while timing was on (one pass per key per chunk)
     std::string err;
 };
 
@@ -139,6 +142,10 @@ struct ModDownEpilogue {
     // acc_c[r] = sum_j digit_j[r] (gathered by the Galois map) * evk_j,c[r] itself, digit j's own limbs
     // taken from the switched polynomial.  beta <= 8.
     uint32_t fused, beta, alpha, M;
+    // n_terms > 0 (fused only): the launch serves ONE output whose accumulator is the sum over n_terms
+    // (polynomial, Galois element, key) terms, a sum of rotations brought down by one ModDown; raised/own/evk/g
+    // are then indexed by term, c0[0] must be null (the rotated c0 parts arrive summed through self0[0]).
+    uint32_t n_terms;
     const u64* raised[HE_MAX_KS_JOBS];  // [beta][R][N]
     const u64* own[HE_MAX_KS_JOBS];     // [L1][N]
     const u64* evk[HE_MAX_KS_JOBS];     // [dnum][2][M][N]
@@ -152,6 +159,7 @@ struct IpPrologue {
     const u64* evk[HE_MAX_KS_JOBS];     // [dnum][2][M][N]
     uint32_t g[HE_MAX_KS_JOBS];
     uint32_t beta, R, M, L1, k, nq;
+    uint32_t n_terms;                   // as in ModDownEpilogue: > 0 = one output, arrays indexed by term
 };
 
 // One batched transform launch (both passes).  Limb i is read at seg[src_seg[i]] + src_limb[i]*N
@@ -176,6 +184,7 @@ struct TransformDesc {
 void scale_entry(const he_ctx* c, ScaleList& sc, uint32_t i, uint32_t mi, u64 s);
 int32_t launch_transform(he_ctx* ctx, const TransformDesc& d);
 int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d);   // N = 2^16 fast path
+int32_t probe_butterfly_rates(he_ctx* ctx, u64* d_out, uint32_t groups, double rate_out[3]);   // ntt16.hip
 int32_t launch_moddown_final(he_ctx* ctx, const u64* conv, uint32_t n_jobs, const ModDownEpilogue& ep);
 
 // in-place conveniences
@@ -205,5 +214,15 @@ struct KsJob {
 // Runs every job: one ModUp per source, then inner product + ModDown per job, batched.
 int32_t ks_engine(he_ctx* ctx, uint32_t level, const KsSrc* srcs, uint32_t n_src, const KsJob* jobs, uint32_t n_jobs);
 size_t ks_engine_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_src, uint32_t n_jobs);
+// Sum of rotations with one ModDown for the whole sum.  Terms with g == 1 are added as they are (evk unused).
+#define HE_MAX_SUM_TERMS 49
+struct KsSumTerm {
+    const u64* c0;   // [level+1][N]
+    const u64* c1;
+    uint32_t g;
+    const u64* evk;
+};
+size_t ks_rotate_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_rot);
+int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms, uint32_t n_terms, u64* out0, u64* out1, u64* ws);
 size_t rescale_ws_elems(const he_ctx* c, uint32_t level, uint32_t n);
 int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint32_t n, uint32_t level, u64* ws);

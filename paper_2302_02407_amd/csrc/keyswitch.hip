@@ -474,6 +474,75 @@ static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t l
     return HE_OK;
 }
 
+// Stand-alone inner product of the jobs described by `ib` (grouped by key): acc [job][2][R][N].
+static int32_t launch_inner_product(he_ctx* c, uint32_t level, const IpBatch& ib, uint32_t groups, u64* acc) {
+    const uint32_t R = level + 1 + c->np, beta = num_digits(c, level);
+    dim3 grid(c->N / KS_THREADS, R, groups), block(KS_THREADS);
+    if (beta <= 4)
+        hipLaunchKernelGGL(inner_product_kernel<4>, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M, level,
+                           c->nq, c->alpha);
+    else if (beta <= 8)
+        hipLaunchKernelGGL(inner_product_kernel<8>, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M, level,
+                           c->nq, c->alpha);
+    else
+        hipLaunchKernelGGL(inner_product_wide_kernel, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M,
+                           level, c->nq, c->alpha);
+    HE_HIP(c, hipGetLastError());
+    return HE_OK;
+}
+
+// The ModDown of J accumulators (each [2][R][N]; on the fused N = 2^16 path they are never stored and `ip` / `ep`
+// describe how the transforms compute them): special-prime limbs -> coefficient form (pre-multiplied by
+// N^-1 * (P/p_t)^-1), conversion to q_0..q_level, forward transform with the epilogue described by `ep`.
+static int32_t moddown_chain(he_ctx* c, uint32_t level, uint32_t J, u64* acc, u64* tmp_dn, u64* conv, const IpPrologue* ip,
+                             const ModDownEpilogue& ep) {
+    const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k;
+    ScaleList sc;
+    for (uint32_t t = 0; t < k; t++) {
+        u64 p = c->mod[c->nq + t];
+        scale_entry(c, sc, t, c->nq + t, h_mulmod(c->h_mc[c->nq + t].ninv, c->h_dn_invhat[t], p));
+    }
+    {
+        const uint32_t n = J * 2 * k;
+        std::vector<uint32_t> mods(n);
+        std::vector<uint16_t> lim(n);
+        for (uint32_t i = 0; i < n; i++) {
+            uint32_t t = i % k, pc = i / k;
+            mods[i] = c->nq + t;
+            lim[i] = (uint16_t)(pc * R + L1 + t);
+        }
+        TransformDesc t = {};
+        t.fwd = false; t.seg[0] = acc; t.n_seg = 1; t.dst = tmp_dn; t.n = n;
+        t.mod_idx = mods.data(); t.src_limb = lim.data(); t.scale = &sc; t.scale_period = k;
+        t.ip = ip;
+        int32_t rc = launch_transform(c, t);
+        if (rc != HE_OK) return rc;
+    }
+    {
+        ConvBatch b;
+        b.njobs = 1; b.reps = 2 * J;
+        b.src_stride = (size_t)k * N;
+        b.dst_stride = (size_t)L1 * N;
+        ConvJob& job = b.job[0];
+        job.src = tmp_dn; job.dst = conv; job.hat = c->d_dn_hat; job.hat_w = pad8(k); job.ns = k; job.nt = L1;
+        for (uint32_t r = 0; r < L1; r++) { job.tgt_limb[r] = (uint8_t)r; job.tgt_mod[r] = (uint8_t)r; }
+        int32_t rc = launch_baseconv(c, b, L1, k);
+        if (rc != HE_OK) return rc;
+    }
+    {
+        const uint32_t n = J * 2 * L1;
+        std::vector<uint32_t> mods(n);
+        for (uint32_t i = 0; i < n; i++) mods[i] = i % L1;
+        TransformDesc t = {};
+        t.fwd = true; t.seg[0] = conv; t.n_seg = 1; t.dst = conv; t.n = n; t.mod_idx = mods.data(); t.ep = &ep;
+        t.lazy_out = true;
+        int32_t rc = launch_transform(c, t);
+        if (rc != HE_OK) return rc;
+    }
+    c->cnt.moddown += J;
+    return HE_OK;
+}
+
 // Inner product + ModDown of up to HE_MAX_KS_JOBS jobs whose sources are already raised.
 // raised_of[i] / srcs give job i's raised digits and source; scratch: acc, tmp_dn, conv.
 static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs, const KsJob* jobs, const u64* const* raised_of,
@@ -492,6 +561,7 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
             groups++;
         }
     }
+    if (c->prof_on) c->prof_key_limbs += (uint64_t)groups * 2 * beta * R;
     // On the N = 2^16 path no accumulator is materialised: the special-prime limbs of the inner product are
     // computed by the first pass of their inverse transform, the q-limbs inside the ModDown epilogue (they would
     // only be written here and read back there).  Other rings run the stand-alone kernel.
@@ -501,74 +571,24 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
         ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq;
         for (uint32_t i = 0; i < J; i++) { ip.raised[i] = raised_of[i]; ip.evk[i] = jobs[i].evk; ip.g[i] = jobs[i].g; }
     } else {
-        dim3 grid(N / KS_THREADS, R, groups), block(KS_THREADS);
-        if (beta <= 4)
-            hipLaunchKernelGGL(inner_product_kernel<4>, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M, level,
-                               c->nq, c->alpha);
-        else if (beta <= 8)
-            hipLaunchKernelGGL(inner_product_kernel<8>, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M, level,
-                               c->nq, c->alpha);
-        else
-            hipLaunchKernelGGL(inner_product_wide_kernel, grid, block, 0, c->stream, ib, acc, c->d_mc, c->logN, R, beta, c->M,
-                               level, c->nq, c->alpha);
-        HE_HIP(c, hipGetLastError());
-    }
-    // p-limbs of all accumulators -> coefficient form, pre-multiplied by N^-1 * (P/p_t)^-1
-    ScaleList sc;
-    for (uint32_t t = 0; t < k; t++) {
-        u64 p = c->mod[c->nq + t];
-        scale_entry(c, sc, t, c->nq + t, h_mulmod(c->h_mc[c->nq + t].ninv, c->h_dn_invhat[t], p));
-    }
-    {
-        const uint32_t n = J * 2 * k;
-        std::vector<uint32_t> mods(n);
-        std::vector<uint16_t> lim(n);
-        for (uint32_t i = 0; i < n; i++) {
-            uint32_t t = i % k, pc = i / k;
-            mods[i] = c->nq + t;
-            lim[i] = (uint16_t)(pc * R + L1 + t);
-        }
-        TransformDesc t = {};
-        t.fwd = false; t.seg[0] = acc; t.n_seg = 1; t.dst = tmp_dn; t.n = n;
-        t.mod_idx = mods.data(); t.src_limb = lim.data(); t.scale = &sc; t.scale_period = k;
-        t.ip = fused ? &ip : nullptr;
-        int32_t rc = launch_transform(c, t);
+        int32_t rc = launch_inner_product(c, level, ib, groups, acc);
         if (rc != HE_OK) return rc;
     }
-    {
-        ConvBatch b;
-        b.njobs = 1; b.reps = 2 * J;
-        b.src_stride = (size_t)k * N;
-        b.dst_stride = (size_t)L1 * N;
-        ConvJob& job = b.job[0];
-        job.src = tmp_dn; job.dst = conv; job.hat = c->d_dn_hat; job.hat_w = pad8(k); job.ns = k; job.nt = L1;
-        for (uint32_t r = 0; r < L1; r++) { job.tgt_limb[r] = (uint8_t)r; job.tgt_mod[r] = (uint8_t)r; }
-        int32_t rc = launch_baseconv(c, b, L1, k);
-        if (rc != HE_OK) return rc;
+    ModDownEpilogue ep = {};
+    ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
+    ep.fused = fused ? 1u : 0u; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M;
+    for (uint32_t i = 0; i < J; i++) {
+        const KsSrc& src = srcs[jobs[i].src];
+        ep.raised[i] = raised_of[i]; ep.own[i] = src.c1; ep.evk[i] = jobs[i].evk;
+        ep.c0[i] = src.c0;
+        ep.self0[i] = jobs[i].add_self ? src.s0 : nullptr;
+        ep.self1[i] = jobs[i].add_self ? src.s1 : nullptr;
+        ep.out0[i] = jobs[i].out0; ep.out1[i] = jobs[i].out1;
+        ep.g[i] = jobs[i].g;
+        if (ep.c0[i]) c->cnt.automorph += L1;
     }
-    {
-        ModDownEpilogue ep = {};
-        ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
-        ep.fused = fused ? 1u : 0u; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M;
-        for (uint32_t i = 0; i < J; i++) {
-            const KsSrc& src = srcs[jobs[i].src];
-            ep.raised[i] = raised_of[i]; ep.own[i] = src.c1; ep.evk[i] = jobs[i].evk;
-            ep.c0[i] = src.c0;
-            ep.self0[i] = jobs[i].add_self ? src.s0 : nullptr;
-            ep.self1[i] = jobs[i].add_self ? src.s1 : nullptr;
-            ep.out0[i] = jobs[i].out0; ep.out1[i] = jobs[i].out1;
-            ep.g[i] = jobs[i].g;
-            if (ep.c0[i]) c->cnt.automorph += L1;
-        }
-        const uint32_t n = J * 2 * L1;
-        std::vector<uint32_t> mods(n);
-        for (uint32_t i = 0; i < n; i++) mods[i] = i % L1;
-        TransformDesc t = {};
-        t.fwd = true; t.seg[0] = conv; t.n_seg = 1; t.dst = conv; t.n = n; t.mod_idx = mods.data(); t.ep = &ep;
-        t.lazy_out = true;
-        int32_t rc = launch_transform(c, t);
-        if (rc != HE_OK) return rc;
-    }
+    int32_t rc = moddown_chain(c, level, J, acc, tmp_dn, conv, fused ? &ip : nullptr, ep);
+    if (rc != HE_OK) return rc;
     c->cnt.keyswitch += J;
     return HE_OK;
 }
@@ -616,6 +636,140 @@ int32_t ks_engine(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t n_src, 
             pos += J;
         }
     }
+    return HE_OK;
+}
+
+
+// ---------------------------------------------------------------- sum of rotations, one ModDown
+// out = sum_t Rot(term_t) with the ModDown deferred across the sum: every rotated term is raised and multiplied
+// into its key, the products are summed over the raised basis and only the sum is brought down;
+// out0 also receives sum_t sigma_g_t(c0_t), and terms with g = 1 are added as they are.
+
+struct RotSumArgs {
+    const u64* c0[HE_MAX_SUM_TERMS];     // rotated terms first (n_rot), then the plain ones (n_plain)
+    const u64* c1[HE_MAX_SUM_TERMS];     // used for the plain terms only
+    uint32_t g[HE_MAX_SUM_TERMS];
+    uint32_t n_rot, n_plain;
+};
+// grid (N/256, L1, 1 or 2).  z = 0: s0[r][n] = sum_rot c0_t[r][sigma-source of n] + sum_plain c0_p[r][n];
+// z = 1 (launched only if there are plain terms): s1[r][n] = sum_plain c1_p[r][n].
+__global__ __launch_bounds__(KS_THREADS) void rot_sum_kernel(RotSumArgs a, u64* __restrict__ s0, u64* __restrict__ s1, const ModConst* mc,
+                                                             uint32_t logN) {
+    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y;
+    const u64 q = mc[r].q;
+    const size_t o = ((size_t)r << logN) + n;
+    u64 v = 0;
+    if (blockIdx.z == 0) {
+        for (uint32_t t = 0; t < a.n_rot; t++) v = addmod(v, a.c0[t][((size_t)r << logN) + galois_src_ks(n, a.g[t], logN)], q);
+        for (uint32_t t = a.n_rot; t < a.n_rot + a.n_plain; t++) v = addmod(v, a.c0[t][o], q);
+        s0[o] = v;
+    } else {
+        for (uint32_t t = a.n_rot; t < a.n_rot + a.n_plain; t++) v = addmod(v, a.c1[t][o], q);
+        s1[o] = v;
+    }
+}
+
+// acc[0] (+)= sum_{t=1..n} acc[t], each [2][R][N]; raised-basis limb r = blockIdx.y % R.  grid (N/256, 2R).
+__global__ __launch_bounds__(KS_THREADS) void acc_sum_kernel(u64* __restrict__ acc, uint32_t n, uint32_t init, const ModConst* mc,
+                                                             uint32_t logN, uint32_t R, uint32_t level, uint32_t nq) {
+    const uint32_t i = blockIdx.x * KS_THREADS + threadIdx.x, cr = blockIdx.y, r = cr % R;
+    const u64 m = mc[r <= level ? r : nq + (r - level - 1)].q;
+    const size_t stride = (size_t)2 * R << logN, o = ((size_t)cr << logN) + i;
+    u64 v = init ? 0 : acc[o];
+    for (uint32_t t = 1; t <= n; t++) v = addmod(v, acc[t * stride + o], m);
+    acc[o] = v;
+}
+
+static uint32_t rot_sum_cb(const he_ctx* c, uint32_t level, uint32_t n_rot) {
+    uint32_t cb, jb;
+    engine_shape(c, level, n_rot ? n_rot : 1, 1, cb, jb);
+    return cb;
+}
+static bool rot_sum_fused(const he_ctx* c, uint32_t level, uint32_t n_rot) {
+    return c->logN == 16 && num_digits(c, level) <= 8 && n_rot <= HE_MAX_KS_JOBS;
+}
+
+// raised[n_rot][beta][R] + tmp_up[cb][L1] + s0[L1] + s1[L1] + tmp_dn[2][k] + conv[2][L1] (+ acc[1 + min(n_rot,16)][2][R]
+// where the accumulators have to be stored)
+size_t ks_rotate_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_rot) {
+    const size_t L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
+    size_t e = (size_t)n_rot * beta * R + (size_t)rot_sum_cb(c, level, n_rot) * L1 + 2 * L1 + 2 * k + 2 * L1;
+    if (!rot_sum_fused(c, level, n_rot)) e += (size_t)(1 + std::min<uint32_t>(n_rot, HE_MAX_KS_JOBS)) * 2 * R;
+    return e * c->N;
+}
+
+int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms, uint32_t n_terms, u64* out0, u64* out1, u64* ws) {
+    const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
+    if (n_terms == 0 || n_terms > HE_MAX_SUM_TERMS) return he_fail(c, HE_ERR_BADARG, "rotation sum: between 1 and %d terms", HE_MAX_SUM_TERMS);
+    if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
+    std::vector<const KsSumTerm*> rot, plain;
+    for (uint32_t t = 0; t < n_terms; t++) (terms[t].g == 1 ? plain : rot).push_back(&terms[t]);
+    const uint32_t n_rot = (uint32_t)rot.size(), n_plain = (uint32_t)plain.size();
+    RotSumArgs ra = {};
+    ra.n_rot = n_rot; ra.n_plain = n_plain;
+    for (uint32_t t = 0; t < n_rot; t++) { ra.c0[t] = rot[t]->c0; ra.c1[t] = rot[t]->c1; ra.g[t] = rot[t]->g; }
+    for (uint32_t t = 0; t < n_plain; t++) { ra.c0[n_rot + t] = plain[t]->c0; ra.c1[n_rot + t] = plain[t]->c1; ra.g[n_rot + t] = 1; }
+    if (n_rot == 0) {                                   // nothing to switch: the plain sum is the result
+        hipLaunchKernelGGL(rot_sum_kernel, dim3(N / KS_THREADS, L1, 2), dim3(KS_THREADS), 0, c->stream, ra, out0, out1, c->d_mc, c->logN);
+        HE_HIP(c, hipGetLastError());
+        return HE_OK;
+    }
+    const uint32_t cb = rot_sum_cb(c, level, n_rot);
+    const bool fused = rot_sum_fused(c, level, n_rot);
+    u64* raised = ws;
+    u64* tmp_up = raised + (size_t)n_rot * beta * R * N;
+    u64* s0 = tmp_up + (size_t)cb * L1 * N;
+    u64* s1 = s0 + (size_t)L1 * N;
+    u64* tmp_dn = s1 + (size_t)L1 * N;
+    u64* conv = tmp_dn + (size_t)2 * k * N;
+    u64* acc = conv + (size_t)2 * L1 * N;               // stored accumulators: [0] the sum, [1..] one group of terms
+    // ModUp of every rotated term's c1
+    std::vector<KsSrc> srcs(n_rot);
+    for (uint32_t t = 0; t < n_rot; t++) srcs[t] = {rot[t]->c0, rot[t]->c1, nullptr, nullptr};
+    for (uint32_t t0 = 0; t0 < n_rot; t0 += cb) {
+        int32_t rc = modup_batch(c, srcs.data() + t0, std::min(cb, n_rot - t0), level, raised + (size_t)t0 * beta * R * N, tmp_up);
+        if (rc != HE_OK) return rc;
+    }
+    // the rotated c0 parts and the plain terms, summed
+    hipLaunchKernelGGL(rot_sum_kernel, dim3(N / KS_THREADS, L1, n_plain ? 2 : 1), dim3(KS_THREADS), 0, c->stream, ra, s0, s1, c->d_mc, c->logN);
+    HE_HIP(c, hipGetLastError());
+    c->cnt.automorph += (uint64_t)n_rot * L1;
+    IpPrologue ip = {};
+    ModDownEpilogue ep = {};
+    ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
+    ep.fused = fused ? 1u : 0u; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M;
+    ep.c0[0] = nullptr; ep.self0[0] = s0; ep.self1[0] = n_plain ? s1 : nullptr;
+    ep.out0[0] = out0; ep.out1[0] = out1; ep.g[0] = 1;
+    if (fused) {
+        ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq; ip.n_terms = n_rot;
+        ep.n_terms = n_rot;
+        for (uint32_t t = 0; t < n_rot; t++) {
+            ip.raised[t] = ep.raised[t] = raised + (size_t)t * beta * R * N;
+            ip.evk[t] = ep.evk[t] = rot[t]->evk;
+            ip.g[t] = ep.g[t] = rot[t]->g;
+            ep.own[t] = rot[t]->c1;
+        }
+        if (c->prof_on) c->prof_key_limbs += (uint64_t)n_rot * 2 * beta * R;
+    } else {
+        for (uint32_t t0 = 0; t0 < n_rot; t0 += HE_MAX_KS_JOBS) {
+            const uint32_t cnt = std::min<uint32_t>(HE_MAX_KS_JOBS, n_rot - t0);
+            IpBatch ib;
+            for (uint32_t i = 0; i < cnt; i++) {
+                ib.raised[i] = raised + (size_t)(t0 + i) * beta * R * N;
+                ib.own[i] = rot[t0 + i]->c1;
+                ib.evk[i] = rot[t0 + i]->evk; ib.g[i] = rot[t0 + i]->g; ib.start[i] = i; ib.count[i] = 1;
+            }
+            int32_t rc = launch_inner_product(c, level, ib, cnt, acc + (size_t)2 * R * N);
+            if (rc != HE_OK) return rc;
+            hipLaunchKernelGGL(acc_sum_kernel, dim3(N / KS_THREADS, 2 * R), dim3(KS_THREADS), 0, c->stream, acc, cnt, t0 == 0 ? 1u : 0u,
+                               c->d_mc, c->logN, R, level, c->nq);
+            HE_HIP(c, hipGetLastError());
+            if (c->prof_on) c->prof_key_limbs += (uint64_t)cnt * 2 * beta * R;
+        }
+    }
+    int32_t rc = moddown_chain(c, level, 1, acc, tmp_dn, conv, fused ? &ip : nullptr, ep);
+    if (rc != HE_OK) return rc;
+    c->cnt.keyswitch += n_rot;
     return HE_OK;
 }
 

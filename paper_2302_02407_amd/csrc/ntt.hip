@@ -174,7 +174,7 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
         gather = 0;
         if (ctx->prof_on) {
             HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
-            ctx->prof_events.push_back({e0, e1, live, 0u});
+            ctx->prof_events.push_back({e0, e1, live, 0u, FWD ? (strided ? 0u : 1u) : (strided ? 5u : 3u)});
         }
     }
     if (FWD) ctx->cnt.ntt_limbs += live; else ctx->cnt.intt_limbs += live;

@@ -253,49 +253,68 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
         }
     } else {
         // digit j of limb r is the switched polynomial itself where limb r belongs to digit j, else the raised
-        // digit; four points at a time so that their loads are in flight together
-        const uint32_t beta = ep.beta, own_j = r / ep.alpha;
-        const u64* own = ep.own[job] + ((size_t)r << 16);
-        const u64* raised = ep.raised[job] + ((size_t)r << 16);
-        const u64* key = ep.evk[job] + ((size_t)(comp * ep.M + r) << 16) + (size_t)b * 256;
+        // digit; four points at a time so that their loads are in flight together.  With ep.n_terms > 0 the
+        // launch serves one output whose accumulator is the sum over n_terms (polynomial, Galois element, key)
+        // terms - a sum of rotations with one ModDown - and the per-job arrays are indexed by term.
+        const uint32_t beta = ep.beta, own_j = r / ep.alpha, n_terms = ep.n_terms ? ep.n_terms : 1u;
         const size_t dig_stride = (size_t)ep.R << 16, key_stride = (size_t)(2 * ep.M) << 16;
 #pragma unroll
         for (int k0 = 0; k0 < 16; k0 += 4) {
-            u128 sum[4];
+            u64 tot[4] = {0, 0, 0, 0};
             uint32_t src[4];
             u64 cv[4], sv[4];
 #pragma unroll
             for (int k = 0; k < 4; k++) {
                 const uint32_t e = t + 16 * (k0 + k);
-                src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
-                sum[k] = 0;
+                src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);     // g = Galois element of the job / of term 0
                 cv[k] = has_c0 ? c0[src[k]] : 0;
                 sv[k] = has_self ? self[e] : 0;
             }
-            for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
-                u64 dv[4][4], kv[4][4];
-#pragma unroll
-                for (uint32_t jj = 0; jj < 4; jj++) {
-                    const uint32_t j = j0 + jj;
-                    const bool live = j < beta;
-                    const u64* dj = j == own_j ? own : raised + (live ? j : 0) * dig_stride;
-                    const u64* kj = key + (live ? j : 0) * key_stride;
+            for (uint32_t term = 0; term < n_terms; term++) {
+                const uint32_t idx = ep.n_terms ? term : job;
+                const u64* own = ep.own[idx] + ((size_t)r << 16);
+                const u64* raised = ep.raised[idx] + ((size_t)r << 16);
+                const u64* key = ep.evk[idx] + ((size_t)(comp * ep.M + r) << 16) + (size_t)b * 256;
+                u128 sum[4];
+                if (term) {
+                    const uint32_t gt = ep.g[idx];
 #pragma unroll
                     for (int k = 0; k < 4; k++) {
-                        dv[jj][k] = live ? dj[src[k]] : 0;
-                        kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
+                        const uint32_t e = t + 16 * (k0 + k);
+                        src[k] = gt == 1 ? b * 256 + e : galois_src16(b * 256 + e, gt);
                     }
                 }
 #pragma unroll
-                for (uint32_t jj = 0; jj < 4; jj++)
+                for (int k = 0; k < 4; k++) sum[k] = 0;
+                for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
+                    u64 dv[4][4], kv[4][4];
 #pragma unroll
-                    for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
+                    for (uint32_t jj = 0; jj < 4; jj++) {
+                        const uint32_t j = j0 + jj;
+                        const bool live = j < beta;
+                        const u64* dj = j == own_j ? own : raised + (live ? j : 0) * dig_stride;
+                        const u64* kj = key + (live ? j : 0) * key_stride;
+#pragma unroll
+                        for (int k = 0; k < 4; k++) {
+                            dv[jj][k] = live ? dj[src[k]] : 0;
+                            kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
+                        }
+                    }
+#pragma unroll
+                    for (uint32_t jj = 0; jj < 4; jj++)
+#pragma unroll
+                        for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const u64 a = barrett128(sum[k], q, m.mu, m.bits);
+                    tot[k] = term == 0 ? a : addmod(tot[k], a, q);
+                }
             }
 #pragma unroll
             for (int k = 0; k < 4; k++) {
                 const uint32_t e = t + 16 * (k0 + k);
-                const u64 a = barrett128(sum[k], q, m.mu, m.bits);
-                const u64 v = shoup_lazy4(a + bias - s[e + k0 + k], pinv, pinv_sh, q) + cv[k] + sv[k];
+                const u64 v = shoup_lazy4(tot[k] + bias - s[e + k0 + k], pinv, pinv_sh, q) + cv[k] + sv[k];
                 out[e] = csub(csub(csub(v, q4), q2), q);
             }
         }
@@ -357,42 +376,54 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
 #pragma unroll
         for (int k = 0; k < 16; k++) s[t + 17 * k] = in[t + 16 * k];
     } else {
+        // with ip.n_terms > 0 the launch serves one output whose accumulator is the sum over n_terms
+        // (polynomial, Galois element, key) terms and the per-job arrays are indexed by term
         const uint32_t pc = limb / ip.k, tp = limb - pc * ip.k, job = pc >> 1, comp = pc & 1u;
-        const uint32_t g = ip.g[job], beta = ip.beta;
-        const u64* raised = ip.raised[job] + ((size_t)(ip.L1 + tp) << 16);
-        const u64* key = ip.evk[job] + ((size_t)(comp * ip.M + ip.nq + tp) << 16) + (size_t)b * 256;
+        const uint32_t beta = ip.beta, n_terms = ip.n_terms ? ip.n_terms : 1u;
         const size_t dig_stride = (size_t)ip.R << 16, key_stride = (size_t)(2 * ip.M) << 16;
 #pragma unroll
         for (int k0 = 0; k0 < 16; k0 += 4) {
-            u128 sum[4];
-            uint32_t src[4];
+            u64 tot[4] = {0, 0, 0, 0};
+            for (uint32_t term = 0; term < n_terms; term++) {
+                const uint32_t idx = ip.n_terms ? term : job;
+                const uint32_t g = ip.g[idx];
+                const u64* raised = ip.raised[idx] + ((size_t)(ip.L1 + tp) << 16);
+                const u64* key = ip.evk[idx] + ((size_t)(comp * ip.M + ip.nq + tp) << 16) + (size_t)b * 256;
+                u128 sum[4];
+                uint32_t src[4];
 #pragma unroll
-            for (int k = 0; k < 4; k++) {
-                const uint32_t e = t + 16 * (k0 + k);
-                src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
-                sum[k] = 0;
-            }
-            for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
-                u64 dv[4][4], kv[4][4];
+                for (int k = 0; k < 4; k++) {
+                    const uint32_t e = t + 16 * (k0 + k);
+                    src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
+                    sum[k] = 0;
+                }
+                for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
+                    u64 dv[4][4], kv[4][4];
 #pragma unroll
-                for (uint32_t jj = 0; jj < 4; jj++) {
-                    const uint32_t j = j0 + jj;
-                    const bool live = j < beta;
-                    const u64* dj = raised + (live ? j : 0) * dig_stride;
-                    const u64* kj = key + (live ? j : 0) * key_stride;
+                    for (uint32_t jj = 0; jj < 4; jj++) {
+                        const uint32_t j = j0 + jj;
+                        const bool live = j < beta;
+                        const u64* dj = raised + (live ? j : 0) * dig_stride;
+                        const u64* kj = key + (live ? j : 0) * key_stride;
 #pragma unroll
-                    for (int k = 0; k < 4; k++) {
-                        dv[jj][k] = live ? dj[src[k]] : 0;
-                        kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
+                        for (int k = 0; k < 4; k++) {
+                            dv[jj][k] = live ? dj[src[k]] : 0;
+                            kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
+                        }
                     }
+#pragma unroll
+                    for (uint32_t jj = 0; jj < 4; jj++)
+#pragma unroll
+                        for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
                 }
 #pragma unroll
-                for (uint32_t jj = 0; jj < 4; jj++)
-#pragma unroll
-                    for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
+                for (int k = 0; k < 4; k++) {
+                    const u64 a = barrett128(sum[k], q, m.mu, m.bits);
+                    tot[k] = term == 0 ? a : addmod(tot[k], a, q);
+                }
             }
 #pragma unroll
-            for (int k = 0; k < 4; k++) s[t + 17 * (k0 + k)] = barrett128(sum[k], q, m.mu, m.bits);
+            for (int k = 0; k < 4; k++) s[t + 17 * (k0 + k)] = tot[k];
         }
     }
     __syncthreads();
@@ -446,6 +477,60 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, L
     }
 #pragma unroll
     for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(csub(x[k], q2), q);
+}
+
+// ---------------------------------------------------------------- butterfly-rate probe
+// The vector-ALU roof of the transforms, measured rather than derived: the register blocks of the passes
+// above (four stages on 16 points, twiddles from a 256-entry table that stays in the first-level cache)
+// run back to back with no other memory traffic.  Values wrap around after a few rounds; the timing does
+// not depend on them.
+template <bool FWD, bool WIDE>
+__global__ __launch_bounds__(T16_THREADS) void bfly_probe_kernel(const u64* __restrict__ tw, const u64* __restrict__ tw_sh, u64 q,
+                                                                 u64* __restrict__ out, uint32_t rounds) {
+    const u64 q4 = 4 * q;
+    const uint32_t t = threadIdx.x & 15;
+    u64 x[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = (u64)(blockIdx.x * T16_THREADS + threadIdx.x) * 16 + k;
+    for (uint32_t r = 0; r < rounds; r++) {
+        if (FWD) fwd_block4<WIDE>(x, tw, tw_sh, 4, t, q, q4);
+        else inv_block4(x, tw, tw_sh, 4, t, q, q4);
+    }
+    u64 v = 0;
+#pragma unroll
+    for (int k = 0; k < 16; k++) v ^= x[k];
+    out[blockIdx.x * T16_THREADS + threadIdx.x] = v;
+}
+
+int32_t probe_butterfly_rates(he_ctx* ctx, u64* d_out, uint32_t groups, double rate_out[3]) {
+    const uint32_t rounds = 64;                          // 32 butterflies per thread per round
+    uint32_t narrow = 0, wide = ctx->M;
+    for (uint32_t i = 0; i < ctx->M; i++) if (ctx->h_mc[i].bits > 57) { wide = i; break; }
+    hipEvent_t e0, e1;
+    HE_HIP(ctx, hipEventCreate(&e0));
+    HE_HIP(ctx, hipEventCreate(&e1));
+    for (int which = 0; which < 3; which++) {
+        const uint32_t mi = which == 2 ? wide : narrow;
+        rate_out[which] = 0.0;
+        if (mi >= ctx->M || (which != 2 && ctx->h_mc[mi].bits > 57)) continue;
+        const u64* tw = (which == 1 ? ctx->d_itw : ctx->d_tw) + (size_t)mi * ctx->N;
+        const u64* tw_sh = (which == 1 ? ctx->d_itw_sh : ctx->d_tw_sh) + (size_t)mi * ctx->N;
+        for (int rep = 0; rep < 2; rep++) {              // the first launch warms up
+            HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
+            if (which == 0) hipLaunchKernelGGL((bfly_probe_kernel<true, false>), dim3(groups), dim3(T16_THREADS), 0, ctx->stream, tw, tw_sh, ctx->mod[mi], d_out, rounds);
+            else if (which == 1) hipLaunchKernelGGL((bfly_probe_kernel<false, false>), dim3(groups), dim3(T16_THREADS), 0, ctx->stream, tw, tw_sh, ctx->mod[mi], d_out, rounds);
+            else hipLaunchKernelGGL((bfly_probe_kernel<true, true>), dim3(groups), dim3(T16_THREADS), 0, ctx->stream, tw, tw_sh, ctx->mod[mi], d_out, rounds);
+            HE_HIP(ctx, hipGetLastError());
+            HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
+            HE_HIP(ctx, hipEventSynchronize(e1));
+        }
+        float ms = 0.f;
+        HE_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+        rate_out[which] = (double)groups * T16_THREADS * 32.0 * rounds / (ms * 1e-3);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return HE_OK;
 }
 
 // ---------------------------------------------------------------- host
@@ -510,7 +595,8 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
             uint32_t dig = 0;
             if (!fwd && pass == 0 && d.ip) dig = d.ip->beta * (live / 2);
             if (fwd && pass == 1 && d.ep && d.ep->fused) dig = d.ep->beta * (live / 2);
-            ctx->prof_events.push_back({e0, e1, live, dig});
+            const uint32_t kind = fwd ? (pass == 0 ? 0u : (d.ep ? 2u : 1u)) : (pass == 0 ? (d.ip ? 4u : 3u) : 5u);
+            ctx->prof_events.push_back({e0, e1, live, dig, kind});
         }
     }
     if (fwd) ctx->cnt.ntt_limbs += live; else ctx->cnt.intt_limbs += live;
