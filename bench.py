@@ -345,8 +345,15 @@ def main():
             keys[0] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
             ctx.he_evk_register(0, keys[0])
         ra_w2 = [w[:level - 1] for w in weights]
-        ms_unit = timed(lambda: blk.ca_square_ra(ctx, 16, 32, 32, 2, level, cts[0], weights, ra_w2, 8192, 8), reps=2)
-        extras["ca_square_ra_ms"] = round(ms_unit, 3)
+        # through the library's fused entry point: all 8 intermediates forwarded as one batch, and one at a time
+        # (the loop order of Algorithm 3, which keeps the fewest ciphertexts alive); Slide_1&Sum_f with one ModDown
+        blk_out = [torch.empty((2, level - 2, N), dtype=torch.uint64, device="cuda")]
+        ctx.he_ws_reserve(ctx.he_ws_query_ca_ra_block(16, 32, 32, 2, 3, 1, 8, level, 0, True))
+        for name, grp in (("ca_square_ra_ms", 0), ("ca_square_ra_forward_one_ms", 1)):
+            ms_unit = timed(lambda: ctx.he_ca_ra_block(16, 32, 32, 2, 3, level, 8192, weights, ra_w2, [cts[0]], blk_out,
+                                                       group=grp, deferred=True), reps=3)
+            extras[name] = round(ms_unit, 3)
+        del blk_out
         conv_weights_h = weights if not args.no_cpu else None
         del weights, conv_out, ra_w, ra_out, ra_w2
         # configs[4]: downsampling block, 16 -> 32 channels, stride 2: 3x3 and 1x1 CAConv (16 outputs each),

@@ -278,6 +278,37 @@ int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* plan, uint64_t
 int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* d_ct_out);
 int32_t he_ws_query_raconv(const he_ctx* ctx, const he_raconv_plan* plan, uint64_t* h_bytes);
 
+/* Fused CAConv -> Square -> RAConv block (Algorithm 3; Section 3.1 for the two convolutions, Section 3.4 for
+ * the square activation).  n_ca channel-aligned ciphertexts in (input k holds channels k*C_a .. (k+1)*C_a-1, one
+ * per block, R replicas each), n_ca channel-aligned ciphertexts out (output l holds output channels
+ * l*C_a .. (l+1)*C_a-1; with R > 1 replica position r holds the partial sum over the intermediate channels of
+ * class r, as he_raconv leaves it), n_ra replication-aligned ciphertexts in between (intermediate j carries
+ * channel (j*R + r) mod c_mid in replica r).  Order of operations, as the algorithm states it: Slide_f of every
+ * input; then for the intermediates, `group` at a time, MulFilter&Sum_f over all inputs and taps, Rescale,
+ * rotate-and-sum over C_a, multiplication by the integer k_in (the lift to the square's working scale; its
+ * residues per limb are given), Square = MulCt with itself + Rescale, and MulFilter&Sum_ci of the result into
+ * the f^2 accumulators of every output ("forwarding": only the n_ca*f^2 rotated inputs and the n_ca*f^2
+ * accumulators stay alive, plus `group` intermediates); finally Slide_1&Sum_f and Rescale per output.
+ * group = 1 is the algorithm's loop exactly; larger groups batch the launches of several intermediates (0 or
+ * >= n_ra: all at once).  Every group size gives the same bits.  Inputs [2][level+1][N] at `level` >= 3, outputs
+ * [2][level-2][N] at level-3.  h_d_w_ca[(j*n_ca + k)*f*f + t]: filter plaintext of (intermediate j, input k,
+ * tap t) at `level`; h_d_w_ra[(l*n_ra + j)*f*f + t]: inversely rotated filter plaintext of (output l,
+ * intermediate j, tap t) at level-2.  Needs the keys of the tap rotations, of the rotate-and-sum amounts
+ * H*W*R*2^t and the relinearisation key (Galois element 0).  Outputs must not overlap inputs. */
+typedef struct {
+    uint32_t C_a, H, W, R;
+    uint32_t f;
+    uint32_t n_ca, n_ra;
+    uint32_t level;
+    uint32_t group;
+    uint32_t deferred_moddown;   /* Slide_1&Sum_f with one ModDown per output (see he_rotate_sum) */
+    const uint64_t* h_k_in;      /* `level` canonical residues: k_in mod q_0 .. q_(level-1) */
+    const uint64_t* const* h_d_w_ca;
+    const uint64_t* const* h_d_w_ra;
+} he_block_plan;
+int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* const* h_d_ct_out);
+int32_t he_ws_query_ca_ra_block(const he_ctx* ctx, const he_block_plan* plan, uint64_t* h_bytes);
+
 #ifdef __cplusplus
 }
 #endif

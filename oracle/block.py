@@ -133,3 +133,55 @@ def gap_sum_replicate(orc, ct, level, R, mask, evks):
         w = orc.add(w, orc.rotate(w, level - 1, orc.galois_elt(slots - t), evks[slots - t]), level - 1)
         t <<= 1
     return w
+
+
+# ---------------------------------------------------------------------------------------------
+# The fused CAConv -> Square -> RAConv block, loop for loop as the paper's Algorithm 3 states it, for any
+# number n_CA of channel-aligned ciphertexts: Slide_f of every input first; then, one replication-aligned
+# intermediate j at a time, MulFilter&Sum_f over all inputs, RaS over C_a, Square, and its products with the
+# inversely rotated RAConv filters added into the f^2 accumulators of every output (the forwarding that keeps
+# only n_CA*f^2 ciphertexts alive); Slide_1&Sum_f of each output's accumulators last.  Rescales sit where the
+# convolutions above put them (after MulFilter&Sum_f, after the square, after Slide_1&Sum_f), and the integer
+# k_in lifts the CAConv output to the working scale of the square.
+#
+# Channel bookkeeping for n_CA > 1: input ciphertext k holds channels k*C_a .. (k+1)*C_a - 1 (one per block);
+# intermediate j holds channel (j*R + r) mod c_mid in replica r of every block; output ciphertext l holds output
+# channels l*C_a .. (l+1)*C_a - 1.  p_ca[j][k] are the f^2 filter plaintexts of (intermediate j, input k) at
+# `level`; p_ra[l][j] the f^2 inversely rotated plaintexts of (output l, intermediate j) at level-2.
+def ca_ra_block(orc, g_ca, g_ra, cts_in, level, p_ca, p_ra, evks, rlk, k_in, deferred=False, keep=False):
+    n_ca, n_ra, taps = len(cts_in), g_ca.n_out, len(g_ca.taps)
+    assert g_ra.n_in == n_ra and len(p_ca) == n_ra and len(p_ra) == n_ca
+    lv = level - 1
+    ct1 = []
+    for ct in cts_in:                                                     # Slide_f of every input
+        raised = orc.modup(ct[1], level)
+        ct1.append([ct.copy() if st == 0 else orc.rotate_from_raised(ct, raised, level, orc.galois_elt(st), evks[st])
+                    for st in g_ca.tap_steps])
+    ct4 = [[None] * taps for _ in range(n_ca)]
+    squares = []
+    for j in range(n_ra):
+        acc = None
+        for k in range(n_ca):                                             # MulFilter&Sum_f over every input
+            for t in range(taps):
+                acc = orc.ptct_mac(acc, ct1[k][t], p_ca[j][k][t], level, init=acc is None)
+        cur = orc.rescale(acc, level)
+        for st in g_ca.ras_steps:                                         # RaS over C_a
+            cur = orc.add(cur, orc.rotate(cur, lv, orc.galois_elt(st), evks[st]), lv)
+        u = orc.affine(cur, lv, [k_in] * (lv + 1), [0] * (lv + 1))
+        sq = orc.rescale(orc.mulct(u, u, lv, rlk), lv)                    # Square
+        squares.append(sq)
+        for l in range(n_ca):                                             # forwarded into every output's accumulators
+            for t in range(taps):
+                ct4[l][t] = orc.ptct_mac(ct4[l][t], sq, p_ra[l][j][t], lv - 1, init=ct4[l][t] is None)
+    outs = []
+    gs = [orc.galois_elt(st) for st in g_ra.tap_steps]
+    for l in range(n_ca):                                                 # Slide_1&Sum_f
+        if deferred:
+            total = orc.rotate_sum_deferred(ct4[l], lv - 1, gs, [evks.get(st) for st in g_ra.tap_steps])
+        else:
+            total = None
+            for t, st in enumerate(g_ra.tap_steps):
+                term = ct4[l][t] if st == 0 else orc.rotate(ct4[l][t], lv - 1, gs[t], evks[st])
+                total = term if total is None else orc.add(total, term, lv - 1)
+        outs.append(orc.rescale(total, lv - 1))
+    return (outs, squares) if keep else outs

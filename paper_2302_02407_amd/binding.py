@@ -19,7 +19,7 @@ EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_addpt", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
-    "he_probe_alu", "he_build_id", "he_rotate_sum", "he_ws_query_raconv", "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
+    "he_probe_alu", "he_build_id", "he_rotate_sum", "he_ws_query_raconv", "he_ca_ra_block", "he_ws_query_ca_ra_block", "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
 ]
 
 
@@ -53,6 +53,13 @@ class ConvPlan(C.Structure):
 class RaConvPlan(C.Structure):
     _fields_ = [("n_in", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32), ("level", C.c_uint32),
                 ("deferred_moddown", C.c_uint32), ("h_d_weights", C.POINTER(C.c_void_p))]
+
+
+class BlockPlan(C.Structure):
+    _fields_ = [("C_a", C.c_uint32), ("H", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32),
+                ("n_ca", C.c_uint32), ("n_ra", C.c_uint32), ("level", C.c_uint32), ("group", C.c_uint32),
+                ("deferred_moddown", C.c_uint32), ("h_k_in", C.POINTER(C.c_uint64)),
+                ("h_d_w_ca", C.POINTER(C.c_void_p)), ("h_d_w_ra", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -97,6 +104,8 @@ def load():
         "he_affine": [vp, vp, u32, u64p, u64p, vp],
         "he_conv2d": [vp, C.POINTER(ConvPlan), vp, C.POINTER(vp)],
         "he_raconv": [vp, C.POINTER(RaConvPlan), C.POINTER(vp), vp],
+        "he_ca_ra_block": [vp, C.POINTER(BlockPlan), C.POINTER(vp), C.POINTER(vp)],
+        "he_ws_query_ca_ra_block": [vp, C.POINTER(BlockPlan), u64p],
         "he_ws_bytes": [vp, u64p],
         "he_ws_reserve": [vp, C.c_uint64],
         "he_ws_query_rotate_batch": [vp, u32, u32, u32, i32, u64p],
@@ -399,3 +408,39 @@ class HEContext:
         plan = RaConvPlan(n_in, W, R, f, level, 1 if deferred else 0, C.cast(wa, C.POINTER(C.c_void_p)))
         self._ck(self._lib.he_raconv(self._h, C.byref(plan), ia, _dev(out)))
         return out
+
+    def _block_plan(self, C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, k_in, w_ca, w_ra):
+        ka = (C.c_uint64 * level)(*[int(k_in) % self.q[r] for r in range(level)])
+        ca = (C.c_void_p * max(1, len(w_ca)))(*[_dev(w).value for w in w_ca])
+        ra = (C.c_void_p * max(1, len(w_ra)))(*[_dev(w).value for w in w_ra])
+        plan = BlockPlan(C_a, H, W, R, f, n_ca, n_ra, level, group, 1 if deferred else 0, ka,
+                         C.cast(ca, C.POINTER(C.c_void_p)), C.cast(ra, C.POINTER(C.c_void_p)))
+        return plan, (ka, ca, ra)
+
+    def he_ws_query_ca_ra_block(self, C_a, H, W, R, f, n_ca, n_ra, level, group=0, deferred=False):
+        v = C.c_uint64()
+        plan, _keep = self._block_plan(C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, 1, [], [])
+        self._ck(self._lib.he_ws_query_ca_ra_block(self._h, C.byref(plan), C.byref(v)))
+        return v.value
+
+    def he_ca_ra_block(self, C_a, H, W, R, f, level, k_in, w_ca, w_ra, cts_in, outs, group=0, deferred=False):
+        """Fused CAConv -> Square -> RAConv block.  w_ca: n_ra*n_ca*f*f plaintexts at `level` ([j][k][tap]); w_ra:
+        n_ca*n_ra*f*f inversely rotated plaintexts at level-2 ([l][j][tap]); cts_in / outs: n_ca tensors at `level` /
+        level-3; k_in: the integer lift before the square (reduced per limb here)."""
+        n_ca = len(cts_in)
+        if len(outs) != n_ca or len(w_ca) % (n_ca * f * f) or len(w_ra) != len(w_ca):
+            raise ValueError("need n_ca outputs and n_ra*n_ca*f*f plaintexts for each convolution")
+        n_ra = len(w_ca) // (n_ca * f * f)
+        for c in cts_in:
+            _need(c, 2 * (level + 1) * self.N, "input")
+        for o in outs:
+            _need(o, 2 * (level - 2) * self.N, "output")
+        for w in w_ca:
+            _need(w, (level + 1) * self.N, "CAConv weight plaintext")
+        for w in w_ra:
+            _need(w, (level - 1) * self.N, "RAConv weight plaintext")
+        plan, _keep = self._block_plan(C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, k_in, w_ca, w_ra)
+        ia = (C.c_void_p * n_ca)(*[_dev(c).value for c in cts_in])
+        oa = (C.c_void_p * n_ca)(*[_dev(o).value for o in outs])
+        self._ck(self._lib.he_ca_ra_block(self._h, C.byref(plan), ia, oa))
+        return outs

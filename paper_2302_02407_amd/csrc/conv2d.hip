@@ -57,16 +57,17 @@ __global__ __launch_bounds__(CV_THREADS) void mac_taps9_kernel(MacTaps taps, Mac
 struct MacTapsAny {
     const u64* ct[CV_MAX_TAPS];
     const u64* pt[CV_MAX_TAPS];
-    uint32_t n;
+    uint32_t n, init;
 };
-// Any number of taps, one output per launch.
+// Any number of (ciphertext, plaintext) products, one output per launch; init = 0 continues from the
+// accumulator's current (canonical) contents.
 __global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTapsAny taps, u64* __restrict__ acc, const ModConst* mc,
                                                               uint32_t logN, uint32_t L1) {
     const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
     const uint32_t limb = blockIdx.y;
     const ModConst m = mc[limb];
     const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n;
-    u128 a0 = 0, a1 = 0;
+    u128 a0 = taps.init ? 0 : acc[o0], a1 = taps.init ? 0 : acc[o1];
     for (uint32_t t = 0; t < taps.n; t++) {
         if (t && (t & 7) == 0) {
             a0 = barrett128(a0, m.q, m.mu, m.bits);
@@ -210,7 +211,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         } else {
             for (uint32_t o = 0; o < n_out; o++) {
                 MacTapsAny mt;
-                mt.n = taps;
+                mt.n = taps; mt.init = 1;
                 for (uint32_t t = 0; t < taps; t++) { mt.ct[t] = tap_ct[t]; mt.pt[t] = (const u64*)plan->h_d_weights[(size_t)o * taps + t]; }
                 hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc + (size_t)o * ct_e, ctx->d_mc, ctx->logN, L1);
                 HE_HIP(ctx, hipGetLastError());
@@ -468,5 +469,253 @@ extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint
     }
     u64* rout = (u64*)d_ct_out;
     return rescale_batch(ctx, &rin, &rout, 1, level, rs_ws);
+    });
+}
+
+// ---------------------------------------------------------------- fused block (Algorithm 3)
+struct BlockShape {
+    uint32_t taps, n_rot, n_ras, G;
+    size_t eng_e, rs_e, ct1_e, ct4_e, grp_e, total;
+};
+static BlockShape block_shape(const he_ctx* ctx, const he_block_plan* p, uint32_t n_rot) {
+    BlockShape b;
+    const size_t N = ctx->N;
+    const uint32_t level = p->level;
+    b.taps = p->f * p->f; b.n_rot = n_rot;
+    b.n_ras = 0;
+    for (uint32_t s = 1; s < p->C_a; s <<= 1) b.n_ras++;
+    b.G = (p->group == 0 || p->group > p->n_ra) ? p->n_ra : p->group;
+    const size_t ct_hi = 2 * (size_t)(level + 1) * N, ct_mid = 2 * (size_t)level * N, ct_lo = 2 * (size_t)(level - 1) * N;
+    b.eng_e = n_rot ? ks_engine_ws_elems(ctx, level, p->n_ca, p->n_ca * n_rot) : 0;
+    b.eng_e = std::max(b.eng_e, ks_engine_ws_elems(ctx, level - 1, b.G, b.G));
+    b.eng_e = std::max(b.eng_e, slide1_sum_ws_elems(ctx, level - 2, n_rot, p->deferred_moddown != 0));
+    b.rs_e = rescale_ws_elems(ctx, level, b.G);
+    b.ct1_e = (size_t)p->n_ca * n_rot * ct_hi;
+    b.ct4_e = (size_t)p->n_ca * b.taps * ct_lo;
+    // per forwarded group: accumulators at `level`, two buffers at level-1 (rotate-and-sum ping-pong, then the square),
+    // the tensor product (3 polynomials per ciphertext at level-1), the squares at level-2; plus one sum at level-2
+    b.grp_e = (size_t)b.G * (ct_hi + 2 * ct_mid + 3 * (ct_mid / 2) + ct_lo) + ct_lo;
+    b.total = b.eng_e + b.rs_e + b.ct1_e + b.ct4_e + b.grp_e;
+    return b;
+}
+
+static int32_t block_check(const he_ctx* ctx, const he_block_plan* p) {
+    if (p->level < 3 || p->level >= ctx->nq) return HE_ERR_LEVEL;
+    if ((p->f & 1u) == 0 || p->f * p->f > CV_MAX_TAPS || p->n_ca == 0 || p->n_ra == 0) return HE_ERR_BADARG;
+    if (p->C_a == 0 || (p->C_a & (p->C_a - 1)) || (u64)p->C_a * p->H * p->W * p->R != ctx->N / 2) return HE_ERR_BADARG;
+    if ((u64)p->n_ca * p->f * p->f > 4096) return HE_ERR_BADARG;
+    return HE_OK;
+}
+
+extern "C" int32_t he_ws_query_ca_ra_block(const he_ctx* ctx, const he_block_plan* plan, uint64_t* h_bytes) {
+    return he_guard(ctx, "he_ws_query_ca_ra_block: host allocation failed", [&]() -> int32_t {
+    if (!ctx || !plan || !h_bytes) return HE_ERR_BADARG;
+    int32_t rc = block_check(ctx, plan);
+    if (rc != HE_OK) return rc;
+    uint32_t n_rot = 0;
+    for (uint32_t st : tap_slot_steps(plan->W, plan->R, plan->f, ctx->N / 2)) n_rot += st != 0;
+    *h_bytes = block_shape(ctx, plan, n_rot).total * sizeof(u64);
+    return HE_OK;
+    });
+}
+
+extern "C" int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const uint64_t* const* h_d_ct_in, uint64_t* const* h_d_ct_out) {
+    return he_guard(ctx, "he_ca_ra_block: host allocation failed", [&]() -> int32_t {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!plan || !h_d_ct_in || !h_d_ct_out || !plan->h_d_w_ca || !plan->h_d_w_ra || !plan->h_k_in)
+        return he_fail(ctx, HE_ERR_BADARG, "he_ca_ra_block: null argument");
+    if (ctx->np == 0) return he_fail(ctx, HE_ERR_BADARG, "he_ca_ra_block: context has no special primes");
+    int32_t rc = block_check(ctx, plan);
+    if (rc == HE_ERR_LEVEL) return he_fail(ctx, rc, "he_ca_ra_block: level %u outside 3..%u", plan->level, ctx->nq - 1);
+    if (rc != HE_OK) return he_fail(ctx, rc, "he_ca_ra_block: bad geometry (odd f <= 7, C_a a power of two, C_a*H*W*R = N/2, n_ca, n_ra > 0)");
+    const uint32_t N = ctx->N, slots = N / 2, level = plan->level, f = plan->f, taps = f * f, n_ca = plan->n_ca, n_ra = plan->n_ra;
+    const uint32_t lv = level - 1, lo = level - 2;
+    const bool deferred = plan->deferred_moddown != 0;
+    // keys: Slide taps, rotate-and-sum amounts, relinearisation
+    const std::vector<uint32_t> steps = tap_slot_steps(plan->W, plan->R, f, slots);
+    std::vector<uint32_t> tap_g(taps), ras_g;
+    std::vector<const u64*> tap_key(taps, nullptr), ras_key;
+    uint32_t n_rot = 0;
+    for (uint32_t t = 0; t < taps; t++) {
+        tap_g[t] = h_galois_of_step(ctx, (int32_t)steps[t]);
+        if (tap_g[t] == 1) continue;
+        auto it = ctx->evk.find(tap_g[t]);
+        if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_ca_ra_block: no key for tap rotation %u", steps[t]);
+        tap_key[t] = it->second;
+        n_rot++;
+    }
+    for (uint32_t s = 1; s < plan->C_a; s <<= 1) {
+        const uint32_t step = plan->H * plan->W * plan->R * s, g = h_galois_of_step(ctx, (int32_t)step);
+        auto it = ctx->evk.find(g);
+        if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_ca_ra_block: no key for rotate-and-sum amount %u", step);
+        ras_g.push_back(g);
+        ras_key.push_back(it->second);
+    }
+    auto rl = ctx->evk.find(0);
+    if (rl == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_ca_ra_block: no relinearisation key registered (Galois element 0)");
+    for (uint32_t k = 0; k < n_ca; k++)
+        if (!h_d_ct_in[k] || !h_d_ct_out[k]) return he_fail(ctx, HE_ERR_BADARG, "he_ca_ra_block: input or output %u is null", k);
+    for (size_t i = 0; i < (size_t)n_ra * n_ca * taps; i++)
+        if (!plan->h_d_w_ca[i] || !plan->h_d_w_ra[i]) return he_fail(ctx, HE_ERR_BADARG, "he_ca_ra_block: weight plaintext %zu is null", i);
+    for (uint32_t r = 0; r <= lv; r++)
+        if (plan->h_k_in[r] >= ctx->mod[r]) return he_fail(ctx, HE_ERR_BADARG, "he_ca_ra_block: k_in of limb %u is not a canonical residue", r);
+    const BlockShape bs = block_shape(ctx, plan, n_rot);
+    rc = he_ensure_ws(ctx, bs.total * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    const uint32_t G = bs.G, n_ras = bs.n_ras;
+    const size_t ct_hi = 2 * (size_t)(level + 1) * N, ct_mid = 2 * (size_t)level * N, ct_lo = 2 * (size_t)lv * N, pe_mid = (size_t)level * N;
+    u64* rs_ws = ctx->d_ws + bs.eng_e;
+    u64* ct1 = rs_ws + bs.rs_e;                           // [n_ca][n_rot] rotated inputs at `level`
+    u64* ct4 = ct1 + bs.ct1_e;                            // [n_ca][taps] accumulators at level-2
+    u64* acc = ct4 + bs.ct4_e;                            // [G] at `level`
+    u64* pa = acc + (size_t)G * ct_hi;                    // [G] at level-1
+    u64* pb = pa + (size_t)G * ct_mid;                    // [G] at level-1
+    u64* tens = pb + (size_t)G * ct_mid;                  // [G][3] polynomials at level-1
+    u64* ct3 = tens + (size_t)G * 3 * pe_mid;             // [G] squares at level-2
+    u64* total = ct3 + (size_t)G * ct_lo;                 // one sum at level-2
+
+    // Slide_f of every input: one ModUp per input shared by its taps, all inputs in one batch
+    std::vector<const u64*> slid((size_t)n_ca * taps);
+    {
+        std::vector<KsSrc> srcs(n_ca);
+        std::vector<KsJob> jobs;
+        for (uint32_t k = 0; k < n_ca; k++) {
+            const u64* in = (const u64*)h_d_ct_in[k];
+            srcs[k] = {in, in + (size_t)(level + 1) * N, nullptr, nullptr};
+            uint32_t nb = 0;
+            for (uint32_t t = 0; t < taps; t++) {
+                if (tap_g[t] == 1) { slid[(size_t)k * taps + t] = in; continue; }
+                u64* out = ct1 + ((size_t)k * n_rot + nb++) * ct_hi;
+                jobs.push_back({k, tap_g[t], tap_key[t], out, out + (size_t)(level + 1) * N, 0});
+                slid[(size_t)k * taps + t] = out;
+            }
+        }
+        if (!jobs.empty()) {
+            rc = ks_engine(ctx, level, srcs.data(), n_ca, jobs.data(), (uint32_t)jobs.size());
+            if (rc != HE_OK) return rc;
+        }
+    }
+    AffineConst kin;                                      // integer lift before the square, per limb
+    for (uint32_t r = 0; r <= lv; r++) { kin.mul[r] = plan->h_k_in[r]; kin.add[r] = 0; }
+    for (uint32_t j0 = 0; j0 < n_ra; j0 += G) {
+        const uint32_t g = std::min(G, n_ra - j0);
+        // MulFilter&Sum_f over every input and tap, for the g intermediates of this group
+        {
+            dim3 grid(N / CV_THREADS, level + 1), block(CV_THREADS);
+            if (n_ca == 1 && taps <= 9) {
+                for (uint32_t o0 = 0; o0 < g; o0 += CV_MAX_OUT_PER_LAUNCH) {
+                    MacTaps mt;
+                    MacWeights mw;
+                    mt.n_taps = taps;
+                    mt.n_out = std::min<uint32_t>(CV_MAX_OUT_PER_LAUNCH, g - o0);
+                    for (uint32_t t = 0; t < taps; t++) mt.ct[t] = slid[t];
+                    for (uint32_t o = 0; o < mt.n_out; o++) {
+                        mt.acc[o] = acc + (size_t)(o0 + o) * ct_hi;
+                        for (uint32_t t = 0; t < taps; t++) mw.pt[o * 9 + t] = (const u64*)plan->h_d_w_ca[(size_t)(j0 + o0 + o) * taps + t];
+                    }
+                    hipLaunchKernelGGL(mac_taps9_kernel, grid, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, level + 1);
+                    HE_HIP(ctx, hipGetLastError());
+                }
+            } else {
+                const size_t terms = (size_t)n_ca * taps;
+                for (uint32_t o = 0; o < g; o++)
+                    for (size_t i0 = 0; i0 < terms; i0 += CV_MAX_TAPS) {
+                        MacTapsAny mt;
+                        mt.n = (uint32_t)std::min<size_t>(CV_MAX_TAPS, terms - i0);
+                        mt.init = i0 == 0;
+                        for (uint32_t i = 0; i < mt.n; i++) {
+                            mt.ct[i] = slid[i0 + i];                                       // [k][tap] flattened
+                            mt.pt[i] = (const u64*)plan->h_d_w_ca[(size_t)(j0 + o) * terms + i0 + i];
+                        }
+                        hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc + (size_t)o * ct_hi, ctx->d_mc, ctx->logN, level + 1);
+                        HE_HIP(ctx, hipGetLastError());
+                    }
+            }
+            ctx->cnt.mac += (uint64_t)g * n_ca * taps;
+        }
+        // Rescale, then rotate-and-sum over C_a (ping-pong so that the last step lands in pa)
+        std::vector<const u64*> accs(g);
+        std::vector<u64*> cur(g), nxt(g);
+        for (uint32_t o = 0; o < g; o++) {
+            accs[o] = acc + (size_t)o * ct_hi;
+            u64 *a = pa + (size_t)o * ct_mid, *b = pb + (size_t)o * ct_mid;
+            cur[o] = (n_ras & 1u) ? b : a;
+            nxt[o] = (n_ras & 1u) ? a : b;
+        }
+        rc = rescale_batch(ctx, accs.data(), cur.data(), g, level, rs_ws);
+        if (rc != HE_OK) return rc;
+        for (uint32_t s = 0; s < n_ras; s++) {
+            std::vector<KsSrc> srcs(g);
+            std::vector<KsJob> jobs(g);
+            for (uint32_t o = 0; o < g; o++) {
+                srcs[o] = {cur[o], cur[o] + pe_mid, cur[o], cur[o] + pe_mid};
+                jobs[o] = {o, ras_g[s], ras_key[s], nxt[o], nxt[o] + pe_mid, 1};
+            }
+            rc = ks_engine(ctx, lv, srcs.data(), g, jobs.data(), g);
+            if (rc != HE_OK) return rc;
+            std::swap(cur, nxt);
+        }
+        // Square: integer lift, tensor product, relinearisation of all g at once, Rescale -> ct3
+        {
+            std::vector<KsSrc> srcs(g);
+            std::vector<KsJob> jobs(g);
+            std::vector<const u64*> sq(g);
+            std::vector<u64*> outs(g);
+            for (uint32_t o = 0; o < g; o++) {
+                u64* u = cur[o];                          // == pa + o*ct_mid
+                rc = launch_affine(ctx, u, lv, kin, u);
+                if (rc != HE_OK) return rc;
+                u64* d = tens + (size_t)o * 3 * pe_mid;
+                rc = launch_tensor(ctx, u, u, lv, d);
+                if (rc != HE_OK) return rc;
+                u64* res = nxt[o];                        // the other level-1 buffer
+                srcs[o] = {nullptr, d + 2 * pe_mid, d, d + pe_mid};
+                jobs[o] = {o, 1, rl->second, res, res + pe_mid, 1};
+                sq[o] = res;
+                outs[o] = ct3 + (size_t)o * ct_lo;
+            }
+            rc = ks_engine(ctx, lv, srcs.data(), g, jobs.data(), g);
+            if (rc != HE_OK) return rc;
+            rc = rescale_batch(ctx, sq.data(), outs.data(), g, lv, rs_ws);
+            if (rc != HE_OK) return rc;
+        }
+        // forwarded into the f^2 accumulators of every output: MulFilter&Sum_ci with the inversely rotated filters
+        {
+            dim3 grid(N / CV_THREADS, lo + 1), block(CV_THREADS);
+            for (uint32_t l = 0; l < n_ca; l++)
+                for (uint32_t t0 = 0; t0 < taps; t0 += 9)
+                    for (uint32_t i0 = 0; i0 < g; i0 += RA_IN_PER_LAUNCH) {
+                        RaMac a;
+                        a.n_taps = std::min<uint32_t>(9, taps - t0);
+                        a.n_in = std::min<uint32_t>(RA_IN_PER_LAUNCH, g - i0);
+                        a.init = (j0 == 0 && i0 == 0);
+                        for (uint32_t t = 0; t < a.n_taps; t++) a.acc[t] = ct4 + ((size_t)l * taps + t0 + t) * ct_lo;
+                        for (uint32_t i = 0; i < a.n_in; i++) {
+                            a.ct[i] = ct3 + (size_t)(i0 + i) * ct_lo;
+                            for (uint32_t t = 0; t < a.n_taps; t++)
+                                a.pt[i * 9 + t] = (const u64*)plan->h_d_w_ra[((size_t)l * n_ra + j0 + i0 + i) * taps + t0 + t];
+                        }
+                        hipLaunchKernelGGL(ra_mac9_kernel, grid, block, 0, ctx->stream, a, ctx->d_mc, ctx->logN, lo + 1);
+                        HE_HIP(ctx, hipGetLastError());
+                    }
+            ctx->cnt.mac += (uint64_t)g * n_ca * taps;
+        }
+    }
+    // Slide_1&Sum_f of every output's accumulators, then its Rescale
+    for (uint32_t l = 0; l < n_ca; l++) {
+        std::vector<const u64*> cts(taps);
+        for (uint32_t t = 0; t < taps; t++) cts[t] = ct4 + ((size_t)l * taps + t) * ct_lo;
+        const u64* rin = cts[0];
+        if (taps > 1) {
+            u64* tot = deferred ? total : (u64*)cts[0];
+            rc = slide1_sum(ctx, lo, cts.data(), tap_g.data(), tap_key.data(), taps, deferred, tot, ctx->d_ws);
+            if (rc != HE_OK) return rc;
+            rin = tot;
+        }
+        u64* rout = (u64*)h_d_ct_out[l];
+        rc = rescale_batch(ctx, &rin, &rout, 1, lo, rs_ws);
+        if (rc != HE_OK) return rc;
+    }
+    return HE_OK;
     });
 }

@@ -167,6 +167,7 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
         c->itw1[i] = h_powmod(ipsi, N / 2, m);
         mc.ninv_w = h_mulmod(mc.ninv, c->itw1[i], m);
         mc.ninv_w_sh = h_shoup(mc.ninv_w, m);
+        mc.one_sh = h_shoup(1, m);
         mc.pad = 0;
     }
     size_t tb = (size_t)M * N * sizeof(u64);

@@ -93,11 +93,11 @@ int32_t launch_tensor(he_ctx* ctx, const u64* a, const u64* b, uint32_t level, u
     return HE_OK;
 }
 
+// out_c[r] = ct_c[r] * mul[r] (+ add[r] on component 0).  grid: (N/256, 2*(level+1)).
 struct AffineArgs {
     u64 mul[HE_MAX_MODULI], mul_sh[HE_MAX_MODULI], add[HE_MAX_MODULI];
 };
-// out_c[r] = ct_c[r] * mul[r] (+ add[r] on component 0).  grid: (N/256, 2*(level+1)).
-__global__ __launch_bounds__(EW_THREADS) void affine_kernel(const u64* __restrict__ ct, u64* __restrict__ out, AffineArgs aa,
+__global__ __launch_bounds__(EW_THREADS) void affine_kernel(const u64* ct, u64* out, AffineArgs aa,
                                                             const ModConst* mc, uint32_t logN, uint32_t L1) {
     const uint32_t n = blockIdx.x * EW_THREADS + threadIdx.x;
     const uint32_t r = blockIdx.y % L1, comp = blockIdx.y / L1;
@@ -106,6 +106,20 @@ __global__ __launch_bounds__(EW_THREADS) void affine_kernel(const u64* __restric
     u64 v = shoup_mul(ct[o], aa.mul[r], aa.mul_sh[r], q);
     if (comp == 0) v = addmod(v, aa.add[r], q);
     out[o] = v;
+}
+
+// k.mul / k.add: canonical residues of limbs 0..level; out may alias ct.
+int32_t launch_affine(he_ctx* ctx, const u64* ct, uint32_t level, const AffineConst& k, u64* out) {
+    AffineArgs aa;
+    for (uint32_t r = 0; r <= level; r++) {
+        aa.mul[r] = k.mul[r];
+        aa.mul_sh[r] = h_shoup(k.mul[r], ctx->mod[r]);
+        aa.add[r] = k.add[r];
+    }
+    dim3 grid(ctx->N / EW_THREADS, 2 * (level + 1)), block(EW_THREADS);
+    hipLaunchKernelGGL(affine_kernel, grid, block, 0, ctx->stream, ct, out, aa, ctx->d_mc, ctx->logN, level + 1);
+    HE_HIP(ctx, hipGetLastError());
+    return HE_OK;
 }
 
 int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g) {
@@ -186,17 +200,13 @@ int32_t he_affine(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, const uint6
     if (!ctx) return HE_ERR_BADARG;
     if (!d_ct || !d_out || !h_mul || !h_add) return he_fail(ctx, HE_ERR_BADARG, "he_affine: null argument");
     if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_affine: level %u above L=%u", level, ctx->nq - 1);
-    AffineArgs aa;
+    AffineConst k;
     for (uint32_t r = 0; r <= level; r++) {
         if (h_mul[r] >= ctx->mod[r] || h_add[r] >= ctx->mod[r]) return he_fail(ctx, HE_ERR_BADARG, "he_affine: constant of limb %u is not a canonical residue", r);
-        aa.mul[r] = h_mul[r];
-        aa.mul_sh[r] = h_shoup(h_mul[r], ctx->mod[r]);
-        aa.add[r] = h_add[r];
+        k.mul[r] = h_mul[r];
+        k.add[r] = h_add[r];
     }
-    dim3 grid(ctx->N / EW_THREADS, 2 * (level + 1)), block(EW_THREADS);
-    hipLaunchKernelGGL(affine_kernel, grid, block, 0, ctx->stream, (const u64*)d_ct, (u64*)d_out, aa, ctx->d_mc, ctx->logN, level + 1);
-    HE_HIP(ctx, hipGetLastError());
-    return HE_OK;
+    return launch_affine(ctx, (const u64*)d_ct, level, k, (u64*)d_out);
     });
 }
 

@@ -24,6 +24,7 @@ struct ModConst {
     u64 ninv_sh;    // Shoup companion floor(ninv * 2^64 / q)
     u64 ninv_w;     // N^-1 * psi^-(N/2): scaling folded into the twiddle of the last inverse stage
     u64 ninv_w_sh;
+    u64 one_sh;     // floor(2^64 / q): Shoup companion of the constant 1 (a quotient step for any 64-bit value)
     uint32_t bits;  // bit length of q
     uint32_t pad;
 };
@@ -191,6 +192,10 @@ int32_t launch_moddown_final(he_ctx* ctx, const u64* conv, uint32_t n_jobs, cons
 int32_t launch_ntt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n);
 int32_t launch_intt(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint32_t n, const ScaleList* scale);
 int32_t launch_automorph_ntt(he_ctx* ctx, const u64* in, u64* out, uint32_t n_limbs, uint32_t g);
+struct AffineConst {
+    u64 mul[HE_MAX_MODULI], add[HE_MAX_MODULI];
+};
+int32_t launch_affine(he_ctx* ctx, const u64* ct, uint32_t level, const AffineConst& k, u64* out);   // out may alias ct
 int32_t launch_tensor(he_ctx* ctx, const u64* a, const u64* b, uint32_t level, u64* d);   // d = [d0][d1][d2], each [level+1][N]
 int32_t launch_automorph_coef(he_ctx* ctx, const u64* in, u64* out, const uint32_t* mod_idx, uint32_t n, uint32_t g);
 

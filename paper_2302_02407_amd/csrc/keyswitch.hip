@@ -624,7 +624,14 @@ int32_t ks_engine(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t n_src, 
         rc = modup_batch(c, srcs + s0, ns, level, raised, tmp_up);
         if (rc != HE_OK) return rc;
         while (pos < end) {
-            const uint32_t J = (uint32_t)std::min<size_t>(jb, end - pos);
+            uint32_t J = (uint32_t)std::min<size_t>(jb, end - pos);
+            // do not split a run of same-key jobs across two launch sets (each set would pass over the key once) when
+            // the set can end at a key boundary in its second half instead
+            if (pos + J < end && jobs[order[pos + J - 1]].evk == jobs[order[pos + J]].evk) {
+                uint32_t b = J;
+                while (b > 1 && jobs[order[pos + b - 1]].evk == jobs[order[pos + b]].evk) b--;
+                if (2 * b >= J) J = b;
+            }
             KsJob chunk[HE_MAX_KS_JOBS];
             const u64* raised_of[HE_MAX_KS_JOBS];
             for (uint32_t i = 0; i < J; i++) {

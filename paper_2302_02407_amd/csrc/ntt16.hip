@@ -117,6 +117,34 @@ __device__ __forceinline__ void inv_block4(u64 (&x)[16], const u64* __restrict__
     }
 }
 
+// Inverse stages for moduli below 2^54 with no reduction at all: sums are left to grow and differences are taken
+// against a multiple of q that covers the inputs.  With inputs below 2^log_b * q a stage leaves sums below
+// 2^(log_b+1) * q and twiddle products below 4q, so the bound of the next stage is 2^max(log_b+1, 2) * q.  Eight
+// stages from canonical inputs stay below 512 q < 2^63.
+template <int STAGES>
+__device__ __forceinline__ void inv_block_lazy(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh,
+                                               uint32_t s0, uint32_t G, u64 q, uint32_t log_b) {
+#pragma unroll
+    for (int u = 3; u > 3 - STAGES; u--) {
+        const int dist = 8 >> u;
+        const uint32_t base = (1u << (s0 + u)) + (G << u);
+        const u64 bq = q << log_b;                       // covers every input of this stage
+#pragma unroll
+        for (int g = 0; g < (1 << u); g++) {
+            const u64 w = tw[base + g], w_sh = tw_sh[base + g];
+#pragma unroll
+            for (int k = 0; k < dist; k++) {
+                const int a = g * 2 * dist + k;
+                const u64 X = x[a], Y = x[a + dist];
+                x[a] = X + Y;
+                x[a + dist] = shoup_lazy4((X + bq) - Y, w, w_sh, q);
+            }
+        }
+        // sums double the bound; twiddle products are below 4q
+        log_b = log_b + 1 < 2 ? 2 : log_b + 1;
+    }
+}
+
 // Inverse stages 3, 2, 1 of the limb (the first three of the last register block); stage 0 is done by
 // the caller together with the output scaling.
 __device__ __forceinline__ void inv_block3(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh, u64 q, u64 q4) {
@@ -305,11 +333,10 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
 #pragma unroll
                         for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
                 }
+                // each term's sum is reduced to [0, 5q) only (three-product quotient, no correction); up to 16 of
+                // them add up below 80q, and the P^-1 product below takes any 64-bit value
 #pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const u64 a = barrett128(sum[k], q, m.mu, m.bits);
-                    tot[k] = term == 0 ? a : addmod(tot[k], a, q);
-                }
+                for (int k = 0; k < 4; k++) tot[k] += barrett128_lazy(sum[k], q, m.mu, m.bits);
             }
 #pragma unroll
             for (int k = 0; k < 4; k++) {
@@ -429,14 +456,25 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) x[j] = s[17 * t + j];
-    inv_block4(x, tw, tw_sh, 12, 16 * b + t, q, q4);
+    // moduli below 2^54: no reduction inside the pass.  Canonical inputs: bounds (in units of q) 1 -> 4 -> 8 -> 16
+    // -> 32 after the first block, -> 512 after the second; one quotient step brings the outputs back below 4q.
+    const bool lazy = m.bits <= 54;
+    if (lazy) inv_block_lazy<4>(x, tw, tw_sh, 12, 16 * b + t, q, 0);
+    else inv_block4(x, tw, tw_sh, 12, 16 * b + t, q, q4);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 16; j++) s[17 * t + j] = x[j];
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = s[t + 17 * k];
-    inv_block4(x, tw, tw_sh, 8, b, q, q4);
+    if (lazy) {
+        inv_block_lazy<4>(x, tw, tw_sh, 8, b, q, 5);
+        const u64 one_sh = m.one_sh;                     // floor(2^64 / q): the Shoup companion of the constant 1
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = shoup_lazy4(x[k], 1, one_sh, q);
+    } else {
+        inv_block4(x, tw, tw_sh, 8, b, q, q4);
+    }
 #pragma unroll
     for (int k = 0; k < 16; k++) out[t + 16 * k] = x[k];
 }
@@ -494,7 +532,8 @@ __global__ __launch_bounds__(T16_THREADS) void bfly_probe_kernel(const u64* __re
     for (int k = 0; k < 16; k++) x[k] = (u64)(blockIdx.x * T16_THREADS + threadIdx.x) * 16 + k;
     for (uint32_t r = 0; r < rounds; r++) {
         if (FWD) fwd_block4<WIDE>(x, tw, tw_sh, 4, t, q, q4);
-        else inv_block4(x, tw, tw_sh, 4, t, q, q4);
+        else if (WIDE) inv_block4(x, tw, tw_sh, 4, t, q, q4);
+        else inv_block_lazy<4>(x, tw, tw_sh, 4, t, q, 2);
     }
     u64 v = 0;
 #pragma unroll
@@ -518,6 +557,7 @@ int32_t probe_butterfly_rates(he_ctx* ctx, u64* d_out, uint32_t groups, double r
         for (int rep = 0; rep < 2; rep++) {              // the first launch warms up
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
             if (which == 0) hipLaunchKernelGGL((bfly_probe_kernel<true, false>), dim3(groups), dim3(T16_THREADS), 0, ctx->stream, tw, tw_sh, ctx->mod[mi], d_out, rounds);
+            else if (which == 1 && ctx->h_mc[mi].bits > 54) hipLaunchKernelGGL((bfly_probe_kernel<false, true>), dim3(groups), dim3(T16_THREADS), 0, ctx->stream, tw, tw_sh, ctx->mod[mi], d_out, rounds);
             else if (which == 1) hipLaunchKernelGGL((bfly_probe_kernel<false, false>), dim3(groups), dim3(T16_THREADS), 0, ctx->stream, tw, tw_sh, ctx->mod[mi], d_out, rounds);
             else hipLaunchKernelGGL((bfly_probe_kernel<true, true>), dim3(groups), dim3(T16_THREADS), 0, ctx->stream, tw, tw_sh, ctx->mod[mi], d_out, rounds);
             HE_HIP(ctx, hipGetLastError());
