@@ -16,8 +16,45 @@ one half carried in the scale: two levels per application.
 import torch
 
 
+class BufferPool:
+    """Ciphertext buffers handed out in call order and reused across calls: a caller that runs the same block
+    repeatedly (a serving loop, a timed region) allocates on the first pass only.  reset() rewinds to the first
+    buffer; a buffer is reused only if the same position asks for the same level again."""
+
+    def __init__(self):
+        self._bufs, self._pos = [], 0
+
+    def reset(self):
+        self._pos = 0
+
+    def ct(self, level, N):
+        i = self._pos
+        self._pos += 1
+        if i < len(self._bufs) and self._bufs[i].shape == (2, level + 1, N):
+            return self._bufs[i]
+        t = torch.empty((2, level + 1, N), dtype=torch.uint64, device="cuda")
+        if i < len(self._bufs):
+            self._bufs[i] = t
+        else:
+            self._bufs.append(t)
+        return t
+
+
+_pool = None
+
+
+def use_pool(pool):
+    """Route the buffers of the functions below through `pool` (None: allocate afresh every time)."""
+    global _pool
+    _pool = pool
+    if pool is not None:
+        pool.reset()
+
+
 def _ct(level, N):
     """Uninitialised ciphertext buffer (every use below overwrites it completely)."""
+    if _pool is not None:
+        return _pool.ct(level, N)
     return torch.empty((2, level + 1, N), dtype=torch.uint64, device="cuda")
 
 
@@ -35,7 +72,8 @@ def activation_step(ctx, u, level, k3):
     sq = ctx.he_mulct(u, u, level, _ct(level, N))
     w = ctx.he_rescale(sq, level, _ct(level - 1, N))
     ctx.he_affine(w, level - 1, [-1] * level, [k3] * level, w)
-    u_low = u[:, :level, :].contiguous()           # forget limb q_level (a slice, no arithmetic)
+    u_low = _ct(level - 1, N)
+    u_low.copy_(u[:, :level, :])                   # forget limb q_level (a slice, no arithmetic)
     prod = ctx.he_mulct(u_low, w, level - 1, _ct(level - 1, N))
     return ctx.he_rescale(prod, level - 1, _ct(level - 2, N))
 
@@ -58,7 +96,8 @@ def downsampling_block(ctx, C_a, H, W, R, level, ct_in, w3, w1, masks_main, mask
     a2 = activation_step(ctx, a1, lv - 2, k3[1])
     short = merge_outputs(ctx, conv1, masks_short, level - 1)
     lo = lv - 4
-    s_low = short[:, :lo + 1, :].contiguous()
+    s_low = _ct(lo, N)
+    s_low.copy_(short[:, :lo + 1, :])
     ctx.he_affine(s_low, lo, [k_short] * (lo + 1), [0] * (lo + 1), s_low)
     out = ctx.he_add(a2, s_low, lo, _ct(lo, N))
     if keep:
