@@ -54,7 +54,16 @@ def uniform_dev(torch, gen, moduli, N, lead=()):
 def run_only(args, torch, ctx, prm, gen):
     """One extra workload in isolation: configs[1] NTT round trip or configs[3] CAConv."""
     N, level = prm.N, len(prm.q) - 1
-    if args.only == "ntt":
+    if args.only == "crot5":
+        # one rotation of a 6-limb ciphertext (the levels the paper's networks work at), in isolation
+        key = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+        ctx.he_evk_register(ctx.galois_elt(1), key)
+        lo_ct = uniform_dev(torch, gen, prm.q[:6], N, lead=(2,))
+        lo_out = torch.empty_like(lo_ct)
+
+        def fn():
+            ctx.he_rotate(lo_ct, 5, 1, lo_out)
+    elif args.only == "ntt":
         idx = list(range(level + 1)) * 16
         data = uniform_dev(torch, gen, prm.q, N, lead=(16,))
 
@@ -92,7 +101,7 @@ def main():
     ap.add_argument("--batch", type=int, default=64, help="ciphertexts per step (configs[2] names 64)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the NTT and conv2d extra measurements")
-    ap.add_argument("--only", choices=["ntt", "conv2d"], help="run just this extra workload --steps times (for profiling "
+    ap.add_argument("--only", choices=["ntt", "conv2d", "conv0", "crot5"], help="run just this extra workload --steps times (for profiling "
                     "it in isolation) and print its own small JSON line instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -121,6 +130,28 @@ def main():
     calib_dst.copy_(calib_src)
     del calib_src, calib_dst
 
+    if args.only == "conv0":
+        # configs[0]: tiny CAConv at N = 2^12 in isolation (for a kernel trace of the latency path)
+        prm0 = config_params(0)
+        ctx0 = HEContext.from_params(prm0)
+        N0, lv0 = prm0.N, len(prm0.q) - 1
+        keys0 = []
+        for s in sorted(set(((dy * 8 + dx) * 8) % (N0 // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0} | {512, 1024}):
+            keys0.append(uniform_dev(torch, gen, prm0.moduli, N0, lead=(prm0.dnum, 2)))
+            ctx0.he_evk_register(ctx0.galois_elt(s), keys0[-1])
+        ct0 = uniform_dev(torch, gen, prm0.q, N0, lead=(2,))
+        w0 = [uniform_dev(torch, gen, prm0.q, N0) for _ in range(9)]
+        out0 = [torch.empty((2, lv0, N0), dtype=torch.uint64, device="cuda")]
+        for _ in range(args.warmup):
+            ctx0.he_conv2d(4, 8, 8, 8, 3, lv0, w0, ct0, out0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ctx0.he_conv2d(4, 8, 8, 8, 3, lv0, w0, ct0, out0)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": "conv0", "steps": args.steps, "warmup": args.warmup,
+                          "us": round((time.perf_counter() - t0) / args.steps * 1e6, 2)}))
+        return
     if args.only:
         run_only(args, torch, ctx, prm, gen)
         return

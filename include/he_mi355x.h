@@ -72,6 +72,8 @@ typedef struct {
     uint32_t f;                  /* odd filter width (1, 3, 5, ...) */
     uint32_t n_out;              /* number of output ciphertexts */
     uint32_t level;              /* level of the input; outputs are at level-1 */
+    uint32_t skip_ras;           /* != 0: stop after the Rescale (no rotate-and-sum over C_a, no keys needed for it); the
+                                    caller sums later with he_ras, e.g. after merging outputs into the stride gap */
     const uint64_t* const* h_d_weights; /* host array of n_out*f*f device pointers */
 } he_conv_plan;
 
@@ -268,6 +270,14 @@ int32_t he_rescale_noalloc(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, ui
  * every rotate-and-sum amount.  Grows the context workspace on first use (allocates). */
 int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64_t* d_ct_in, uint64_t* const* h_d_ct_out);
 int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* plan, uint64_t* h_bytes);
+
+/* Rotate-and-sum on a batch of ciphertexts (Section 2.2 RaS_{c_i}; Section 3.2 and the cost table of Section 3.1
+ * for the sums and re-replications inside the gap, RaS_g / IR_g): for every step s in the order given,
+ * ct <- ct + CRot(ct; h_steps[s]), applied to the n_ct ciphertexts h_d_ct[i] ([2][level+1][N]) at once (one launch
+ * set per step; the ciphertexts share the step's key pass); results in h_d_out[i], inputs unchanged.  No output may
+ * overlap an input or another output.  n_ct*n_steps key switches.  Grows the workspace with n_ct. */
+int32_t he_ras(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level, const int32_t* h_steps,
+               uint32_t n_steps, uint64_t* const* h_d_out);
 
 /* Replication-aligned convolution, reordered (Section 3.1; Algorithm 2): MulFilter&Sum_ci -
  * for every tap the sum over the n_in inputs of input x inversely rotated filter plaintext

@@ -19,7 +19,7 @@ EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_addpt", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
-    "he_probe_alu", "he_build_id", "he_rotate_sum", "he_ws_query_raconv", "he_ca_ra_block", "he_ws_query_ca_ra_block", "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
+    "he_probe_alu", "he_build_id", "he_rotate_sum", "he_ws_query_raconv", "he_ca_ra_block", "he_ws_query_ca_ra_block", "he_ras", "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
 ]
 
 
@@ -47,7 +47,7 @@ class AluProbe(C.Structure):
 
 class ConvPlan(C.Structure):
     _fields_ = [("C_a", C.c_uint32), ("H", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32),
-                ("n_out", C.c_uint32), ("level", C.c_uint32), ("h_d_weights", C.POINTER(C.c_void_p))]
+                ("n_out", C.c_uint32), ("level", C.c_uint32), ("skip_ras", C.c_uint32), ("h_d_weights", C.POINTER(C.c_void_p))]
 
 
 class RaConvPlan(C.Structure):
@@ -95,6 +95,7 @@ def load():
         "he_rotate": [vp, vp, u32, i32, vp],
         "he_rotate_sum": [vp, C.POINTER(vp), u32, u32, i32p, vp, i32],
         "he_ws_query_raconv": [vp, C.POINTER(RaConvPlan), u64p],
+        "he_ras": [vp, C.POINTER(vp), u32, u32, i32p, u32, C.POINTER(vp)],
         "he_conjugate": [vp, vp, u32, vp],
         "he_ptct_mac": [vp, vp, vp, vp, u32, i32],
         "he_add": [vp, vp, vp, u32, vp],
@@ -237,7 +238,7 @@ class HEContext:
 
     def he_ws_query_conv2d(self, C_a, H, W, R, f, level, n_out):
         v = C.c_uint64()
-        plan = ConvPlan(C_a, H, W, R, f, n_out, level, None)
+        plan = ConvPlan(C_a, H, W, R, f, n_out, level, 0, None)
         self._ck(self._lib.he_ws_query_conv2d(self._h, C.byref(plan), C.byref(v)))
         return v.value
 
@@ -370,7 +371,20 @@ class HEContext:
         return out
 
     # ---- convolution
-    def he_conv2d(self, C_a, H, W, R, f, level, weights, ct_in, outs):
+    def he_ras(self, cts, level, steps, outs):
+        """outs[i] = cts[i] after ct <- ct + CRot(ct; s) for every s in steps, all ciphertexts batched."""
+        steps = [int(s) for s in steps]
+        if len(outs) != len(cts):
+            raise ValueError("one output per ciphertext")
+        for t in list(cts) + list(outs):
+            _need(t, 2 * (level + 1) * self.N, "ciphertext")
+        sa = (C.c_int32 * max(1, len(steps)))(*steps)
+        ca = (C.c_void_p * max(1, len(cts)))(*[_dev(c).value for c in cts])
+        oa = (C.c_void_p * max(1, len(outs)))(*[_dev(o).value for o in outs])
+        self._ck(self._lib.he_ras(self._h, ca, len(cts), level, sa, len(steps), oa))
+        return outs
+
+    def he_conv2d(self, C_a, H, W, R, f, level, weights, ct_in, outs, skip_ras=False):
         """weights: list of n_out*f*f device tensors [level+1][N]; outs: n_out tensors [2][level][N]."""
         n_out = len(outs)
         if len(weights) != n_out * f * f:
@@ -382,7 +396,7 @@ class HEContext:
             _need(o, 2 * level * self.N, "output")
         wa = (C.c_void_p * len(weights))(*[_dev(w).value for w in weights])
         oa = (C.c_void_p * n_out)(*[_dev(o).value for o in outs])
-        plan = ConvPlan(C_a, H, W, R, f, n_out, level, C.cast(wa, C.POINTER(C.c_void_p)))
+        plan = ConvPlan(C_a, H, W, R, f, n_out, level, 1 if skip_ras else 0, C.cast(wa, C.POINTER(C.c_void_p)))
         self._ck(self._lib.he_conv2d(self._h, C.byref(plan), _dev(ct_in), oa))
         return outs
 

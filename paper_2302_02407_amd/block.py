@@ -143,3 +143,55 @@ def gap_sum_replicate(ctx, ct, level, R, mask):
         w = ctx.he_add(w, rot, level - 1, rot)
         t <<= 1
     return w
+
+
+def strided_gap_sum_replicate(ctx, cts, level, count, stride, mask):
+    """For every ciphertext of the batch: sum `count` gap positions lying `stride` slots apart into the first
+    (RaS_g: log2(count) rotations), keep it (MulPt with `mask`, Rescale), copy it back into the others (IR_g).
+    level -> level-1.  Needs keys for stride*2^t and N/2 - stride*2^t."""
+    N, slots = ctx.N, ctx.N // 2
+    fwd, back, t = [], [], 1
+    while t < count:
+        fwd.append(stride * t)
+        back.append(slots - stride * t)
+        t <<= 1
+    summed = ctx.he_ras(cts, level, fwd, [_ct(level, N) for _ in cts])
+    kept = []
+    for w in summed:
+        acc = ctx.he_ptct_mac(_ct(level, N), w, mask, level, True)
+        kept.append(ctx.he_rescale(acc, level, _ct(level - 1, N)))
+    return ctx.he_ras(kept, level - 1, back, [_ct(level - 1, N) for _ in kept])
+
+
+def downsample_handoff(ctx, C_a, Hp, Wp, R0, level, ct_in, p1, p2, mask_kappa, p3, mask_a, keep=False):
+    """2-D gap packing across a stride-2 layer (Section 3.2), three layers on one input ciphertext in format
+    (m, d) = (1, R0) with C_a channels on Hp x Wp:
+      1. strided CAConv to 2*C_a channels (void-packed filters p1, 2*C_a/R0 outputs, no rotate-and-sum yet); pairs
+         of outputs merged into the gap by one rotation each; rotate-and-sum over C_a on the merged ciphertexts and
+         one more rotate-and-add that replicates over the freed rows: 2*C_a/(2*R0) ciphertexts carrying d' = 2*R0
+         channels and m' = 2 replicas;
+      2. RAConv on the logical Hp/2 x Wp/2 grid (p2) into one ciphertext, sum over the d' channel positions, mask,
+         re-replication: format (m', d');
+      3. CAConv on that multiplexed format (p3), rotate-and-sum over C_a, sum over the m' row positions, mask,
+         re-replication.
+    Levels: level -> level-1 -> level-3 -> level-5.  Returns the outputs of layer 3 (with keep=True every stage)."""
+    N, slots = ctx.N, ctx.N // 2
+    d, m = 2 * R0, 2
+    n1, n = 2 * C_a // R0, 2 * C_a // d
+    lv = level - 1
+    ras_steps = []
+    s = 1
+    while s < C_a:
+        ras_steps.append(Hp * Wp * R0 * s)
+        s <<= 1
+    row_step = Wp * R0
+    conv1 = ctx.he_conv2d(C_a, Hp, Wp, R0, 3, level, p1, ct_in, [_ct(lv, N) for _ in range(n1)], skip_ras=True)
+    merged = [ctx.he_rotate_sum([conv1[2 * o], conv1[2 * o + 1]], lv, [0, slots - R0], _ct(lv, N)) for o in range(n)]
+    l1 = ctx.he_ras(merged, lv, ras_steps + [slots - row_step], [_ct(lv, N) for _ in range(n)])
+    ra = ctx.he_raconv(Wp, 2 * R0, 3, lv, p2, l1, _ct(lv - 1, N))
+    l2 = gap_sum_replicate(ctx, ra, lv - 1, d, mask_kappa)
+    ca = ctx.he_conv2d(C_a, Hp // 2, Wp, 2 * R0, 3, lv - 2, p3, l2, [_ct(lv - 3, N) for _ in range(n)])
+    l3 = strided_gap_sum_replicate(ctx, ca, lv - 3, m, row_step, mask_a)
+    if keep:
+        return l3, {"l1_conv": conv1, "l1": l1, "l2_conv": ra, "l2": l2, "l3_conv": ca, "l3": l3}
+    return l3

@@ -140,7 +140,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
             tap_key[t] = it->second;
         }
     }
-    for (uint32_t s = 1; s < plan->C_a; s <<= 1) {
+    for (uint32_t s = 1; s < plan->C_a && !plan->skip_ras; s <<= 1) {
         uint32_t step = plan->H * plan->W * plan->R * s;
         uint32_t g = h_galois_of_step(ctx, (int32_t)step);
         auto it = ctx->evk.find(g);
@@ -715,6 +715,69 @@ extern "C" int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const 
         u64* rout = (u64*)h_d_ct_out[l];
         rc = rescale_batch(ctx, &rin, &rout, 1, lo, rs_ws);
         if (rc != HE_OK) return rc;
+    }
+    return HE_OK;
+    });
+}
+
+// ---------------------------------------------------------------- batched rotate-and-sum
+extern "C" int32_t he_ras(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level, const int32_t* h_steps,
+                          uint32_t n_steps, uint64_t* const* h_d_out) {
+    return he_guard(ctx, "he_ras: host allocation failed", [&]() -> int32_t {
+    if (!ctx) return HE_ERR_BADARG;
+    if (n_ct == 0) return HE_OK;
+    if (!h_d_ct || !h_d_out || (n_steps && !h_steps)) return he_fail(ctx, HE_ERR_BADARG, "he_ras: null argument");
+    if (ctx->np == 0) return he_fail(ctx, HE_ERR_BADARG, "he_ras: context has no special primes");
+    if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_ras: level %u above L=%u", level, ctx->nq - 1);
+    const uint32_t N = ctx->N, L1 = level + 1;
+    const size_t ct_e = (size_t)2 * L1 * N, ct_b = ct_e * sizeof(u64);
+    std::vector<uint32_t> gs(n_steps);
+    std::vector<const u64*> keys(n_steps);
+    for (uint32_t s = 0; s < n_steps; s++) {
+        gs[s] = h_galois_of_step(ctx, h_steps[s]);
+        if (gs[s] == 1) return he_fail(ctx, HE_ERR_BADARG, "he_ras: step %u is a multiple of the slot count", s);
+        auto it = ctx->evk.find(gs[s]);
+        if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_ras: no key for step %d (Galois element %u)", h_steps[s], gs[s]);
+        keys[s] = it->second;
+    }
+    {   // no output may overlap an input or another output
+        struct Buf { const char* p; bool out; };
+        std::vector<Buf> bufs;
+        for (uint32_t i = 0; i < n_ct; i++) {
+            if (!h_d_ct[i] || !h_d_out[i]) return he_fail(ctx, HE_ERR_BADARG, "he_ras: ciphertext %u is null", i);
+            bufs.push_back({(const char*)h_d_ct[i], false});
+            bufs.push_back({(const char*)h_d_out[i], true});
+        }
+        std::sort(bufs.begin(), bufs.end(), [](const Buf& a, const Buf& b) { return a.p < b.p; });
+        for (size_t i = 1; i < bufs.size(); i++)
+            if (bufs[i].p < bufs[i - 1].p + ct_b && (bufs[i].out || bufs[i - 1].out))
+                return he_fail(ctx, HE_ERR_BADARG, "he_ras: an output overlaps an input or another output");
+    }
+    if (n_steps == 0) {
+        for (uint32_t i = 0; i < n_ct; i++) HE_HIP(ctx, hipMemcpyAsync(h_d_out[i], h_d_ct[i], ct_b, hipMemcpyDeviceToDevice, ctx->stream));
+        return HE_OK;
+    }
+    // workspace: [engine region][n_ct temporaries]; the steps ping-pong so that the last one lands in the outputs
+    const size_t ks_e = ks_engine_ws_elems(ctx, level, n_ct, n_ct);
+    int32_t rc = he_ensure_ws(ctx, (ks_e + (n_steps > 1 ? (size_t)n_ct * ct_e : 0)) * sizeof(u64));
+    if (rc != HE_OK) return rc;
+    u64* tmp = ctx->d_ws + ks_e;
+    std::vector<const u64*> cur(n_ct);
+    for (uint32_t i = 0; i < n_ct; i++) cur[i] = (const u64*)h_d_ct[i];
+    for (uint32_t s = 0; s < n_steps; s++) {
+        const bool to_out = ((n_steps - 1 - s) & 1u) == 0;
+        std::vector<KsSrc> srcs(n_ct);
+        std::vector<KsJob> jobs(n_ct);
+        std::vector<const u64*> nxt(n_ct);
+        for (uint32_t i = 0; i < n_ct; i++) {
+            u64* dst = to_out ? (u64*)h_d_out[i] : tmp + (size_t)i * ct_e;
+            srcs[i] = {cur[i], cur[i] + (size_t)L1 * N, cur[i], cur[i] + (size_t)L1 * N};
+            jobs[i] = {i, gs[s], keys[s], dst, dst + (size_t)L1 * N, 1};
+            nxt[i] = dst;
+        }
+        rc = ks_engine(ctx, level, srcs.data(), n_ct, jobs.data(), n_ct);
+        if (rc != HE_OK) return rc;
+        cur = nxt;
     }
     return HE_OK;
     });

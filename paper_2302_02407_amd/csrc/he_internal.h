@@ -229,5 +229,10 @@ struct KsSumTerm {
 };
 size_t ks_rotate_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_rot);
 int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms, uint32_t n_terms, u64* out0, u64* out1, u64* ws);
+// Latency path for rings whose limb fits one work group's LDS (smallring.hip)
+bool small_ring_path(const he_ctx* c, uint32_t level);
+int32_t sr_modup(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t level, u64* raised);
+int32_t sr_moddown(he_ctx* c, uint32_t level, uint32_t J, const ModDownEpilogue& ep);
+int32_t sr_rescale(he_ctx* c, const u64* const* cts, u64* const* outs, uint32_t n, uint32_t level);
 size_t rescale_ws_elems(const he_ctx* c, uint32_t level, uint32_t n);
 int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint32_t n, uint32_t level, u64* ws);

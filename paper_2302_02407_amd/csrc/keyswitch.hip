@@ -389,6 +389,7 @@ size_t ks_engine_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_src, uint3
 // ModUp of `cb` sources at once.  raised [cb][beta][R][N] (own limbs left unwritten), tmp [cb][L1][N].
 static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t level, u64* raised, u64* tmp) {
     const uint32_t N = c->N, L1 = level + 1, R = L1 + c->np, beta = num_digits(c, level), al = c->alpha;
+    if (small_ring_path(c, level)) return sr_modup(c, srcs, cb, level, raised);   // one launch: every output limb start to finish
     // coefficient form of all limbs, each pre-multiplied by N^-1 * (Q_j/q_i)^-1
     ScaleList sc;
     for (uint32_t i = 0; i < L1; i++) {
@@ -566,11 +567,13 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
     // computed by the first pass of their inverse transform, the q-limbs inside the ModDown epilogue (they would
     // only be written here and read back there).  Other rings run the stand-alone kernel.
     const bool fused = c->logN == 16 && beta <= 8;
+    // small rings: inner product, ModDown and epilogue of every output limb in one work group, one launch
+    const bool small = !fused && small_ring_path(c, level);
     IpPrologue ip = {};
     if (fused) {
         ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq;
         for (uint32_t i = 0; i < J; i++) { ip.raised[i] = raised_of[i]; ip.evk[i] = jobs[i].evk; ip.g[i] = jobs[i].g; }
-    } else {
+    } else if (!small) {
         int32_t rc = launch_inner_product(c, level, ib, groups, acc);
         if (rc != HE_OK) return rc;
     }
@@ -587,7 +590,7 @@ static int32_t inner_moddown_batch(he_ctx* c, uint32_t level, const KsSrc* srcs,
         ep.g[i] = jobs[i].g;
         if (ep.c0[i]) c->cnt.automorph += L1;
     }
-    int32_t rc = moddown_chain(c, level, J, acc, tmp_dn, conv, fused ? &ip : nullptr, ep);
+    int32_t rc = small ? sr_moddown(c, level, J, ep) : moddown_chain(c, level, J, acc, tmp_dn, conv, fused ? &ip : nullptr, ep);
     if (rc != HE_OK) return rc;
     c->cnt.keyswitch += J;
     return HE_OK;
@@ -791,6 +794,7 @@ size_t rescale_ws_elems(const he_ctx* c, uint32_t level, uint32_t n) {
 // cts[i] [2][level+1][N] -> outs[i] [2][level][N] for i < n, batched HE_MAX_KS_JOBS at a time.
 int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint32_t n, uint32_t level, u64* ws) {
     const uint32_t N = ctx->N, L1 = level + 1;
+    if (ctx->logN <= 12) return sr_rescale(ctx, cts, outs, n, level);   // limb fits LDS: one launch, no scratch
     for (uint32_t b0 = 0; b0 < n; b0 += HE_MAX_KS_JOBS) {
         const uint32_t nb = std::min<uint32_t>(HE_MAX_KS_JOBS, n - b0);
         u64* tmp = ws;
