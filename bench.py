@@ -76,8 +76,10 @@ def run_only(args, torch, ctx, prm, gen):
                         | {2048, 4096, 8192, 16384}):
             held.append(uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2)))
             ctx.he_evk_register(ctx.galois_elt(s), held[-1])
-        ct = uniform_dev(torch, gen, prm.q, N, lead=(2,))
-        weights = [uniform_dev(torch, gen, prm.q, N) for _ in range(8 * 9)]
+        if args.only == "conv5":                         # the same layer on a 6-limb ciphertext
+            level = 5
+        ct = uniform_dev(torch, gen, prm.q[:level + 1], N, lead=(2,))
+        weights = [uniform_dev(torch, gen, prm.q[:level + 1], N) for _ in range(8 * 9)]
         outs = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
 
         def fn():
@@ -101,7 +103,7 @@ def main():
     ap.add_argument("--batch", type=int, default=64, help="ciphertexts per step (configs[2] names 64)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the NTT and conv2d extra measurements")
-    ap.add_argument("--only", choices=["ntt", "conv2d", "conv0", "crot5"], help="run just this extra workload --steps times (for profiling "
+    ap.add_argument("--only", choices=["ntt", "conv2d", "conv0", "crot5", "conv5"], help="run just this extra workload --steps times (for profiling "
                     "it in isolation) and print its own small JSON line instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:

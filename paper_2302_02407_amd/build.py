@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhe_mi355x.so")
 SOURCES = ["ctx.hip", "ntt.hip", "ntt16.hip", "elementwise.hip", "keyswitch.hip", "conv2d.hip", "noalloc.hip", "smallring.hip"]
-HEADERS = ["he_internal.h", "modarith.h", os.path.join("..", "..", "include", "he_mi355x.h")]
+HEADERS = ["he_internal.h", "modarith.h", "ntt_blocks.h", os.path.join("..", "..", "include", "he_mi355x.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

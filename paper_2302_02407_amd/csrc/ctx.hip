@@ -136,6 +136,10 @@ int32_t he_ctx_create(he_ctx** out, uint32_t logN, const uint64_t* h_q, uint32_t
     c->d_up_hat = c->d_dn_hat = c->d_pinv = c->d_pinv_sh = c->d_qlinv = c->d_qlinv_sh = nullptr;
     memset(&c->cnt, 0, sizeof(c->cnt));
     c->prof_on = false;
+    // latency path of the N = 2^16 conversions; HE_COLFUSE_GROUPS=0 switches it off (for measurements)
+    c->cf_max_groups = 4; c->cf_max_targets = 16;
+    if (const char* e = getenv("HE_COLFUSE_GROUPS")) c->cf_max_groups = (uint32_t)strtoul(e, nullptr, 10);
+    if (const char* e = getenv("HE_COLFUSE_TARGETS")) c->cf_max_targets = (uint32_t)strtoul(e, nullptr, 10);
     if (hipGetDevice(&c->device) != hipSuccess) {
         return he_fail(nullptr, HE_ERR_HIP, "he_ctx_create: no HIP device");
     }

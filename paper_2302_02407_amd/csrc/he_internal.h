@@ -82,6 +82,7 @@ struct he_ctx {
     bool prof_on;                       // time every transform launch with an event pair
     std::vector<ProfSpan> prof_events;
     uint64_t prof_key_limbs;            // key limbs the inner products had to read while timing was on (one pass per key per chunk)
+    uint32_t cf_max_groups, cf_max_targets;   // N = 2^16 latency path: largest conversion (groups, targets per group) that takes the single-launch column kernel
     std::string err;
 };
 
@@ -180,7 +181,34 @@ struct TransformDesc {
     const IpPrologue* ip;        // inverse on the N = 2^16 path only, or nullptr: inputs are computed, not read
     bool lazy_out;               // forward only: outputs may stay unreduced (below 2^7 q) where the
                                  // consumers' 128-bit accumulations leave room; internal buffers only
+    uint32_t only_pass;          // N = 2^16 path: 0 = both passes; 1 = the first pass only (inverse: rows, reading the
+                                 // sources; forward: columns); 2 = the second pass only, in place at dst
 };
+
+// N = 2^16 latency path: [inverse column pass -> basis conversion -> forward column pass] of several groups in one launch.
+// Group g: sources src + i*N (i < ns, moduli mod0 + i, output scaling sc entry sc0 + i) in the state the inverse row
+// pass leaves them; targets of its set: target t has modulus tgt_mod[set][t] and is written, in the state the forward
+// column pass leaves it, at dst + tgt_limb[set][t]*N; conversion constants hat[modulus*hat_w + i].
+#define CF_MAX_GROUPS 32
+#define CF_MAX_SETS 4
+// Per-group fields are all 32 or 64 bits wide on purpose.  The group index is uniform, so the compiler reads these
+// through scalar loads, and it is free to split an aligned address into a base register and an offset register
+// that are each misaligned (it did, for byte-sized per-group arrays: base = args + g, offset = 7g).  The hardware
+// drops the two low bits of each register separately, and the load then returns the wrong words.
+struct CfGroup {
+    const u64* src;
+    u64* dst;
+    const u64* hat;
+    uint32_t ns, mod0, sc0, set;
+};
+struct ColFuse {
+    CfGroup grp[CF_MAX_GROUPS];
+    uint32_t hat_w, n_groups;
+    uint32_t nt[CF_MAX_SETS];
+    uint8_t tgt_limb[CF_MAX_SETS][HE_MAX_MODULI];     // indexed per wavefront: vector loads
+    uint8_t tgt_mod[CF_MAX_SETS][HE_MAX_MODULI];
+};
+int32_t launch_colfuse(he_ctx* ctx, const ColFuse& cf, const ScaleList& sc, uint32_t limb_passes);   // ntt16.hip
 // fills w / w_sh of entry i from s (modulus index mi)
 void scale_entry(const he_ctx* c, ScaleList& sc, uint32_t i, uint32_t mi, u64 s);
 int32_t launch_transform(he_ctx* ctx, const TransformDesc& d);

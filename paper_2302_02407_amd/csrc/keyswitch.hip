@@ -386,6 +386,14 @@ size_t ks_engine_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_src, uint3
     return ((size_t)cb * (beta * R + L1) + (size_t)jb * (2 * R + 2 * k + 2 * L1)) * c->N;
 }
 
+// Whether a conversion of `groups` groups (at most `ns` sources and `nt` targets each, `sets` target sets) takes the
+// single-launch column path: N = 2^16 only, and only while its work groups (256 per group, a few per compute unit)
+// fit the chip about once, beyond which the separate throughput kernels win.
+static bool colfuse_ok(const he_ctx* c, uint32_t groups, uint32_t sets, uint32_t ns, uint32_t nt) {
+    return c->logN == 16 && groups <= c->cf_max_groups && groups <= CF_MAX_GROUPS && sets <= CF_MAX_SETS && ns <= 8 &&
+           nt <= c->cf_max_targets && nt <= HE_MAX_MODULI;
+}
+
 // ModUp of `cb` sources at once.  raised [cb][beta][R][N] (own limbs left unwritten), tmp [cb][L1][N].
 static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t level, u64* raised, u64* tmp) {
     const uint32_t N = c->N, L1 = level + 1, R = L1 + c->np, beta = num_digits(c, level), al = c->alpha;
@@ -397,6 +405,8 @@ static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t l
         u64 qi = c->mod[i];
         scale_entry(c, sc, i, i, h_mulmod(c->h_mc[i].ninv, c->h_up_invhat[(size_t)(j * al + (sz - 1)) * al + (i - lo)], qi));
     }
+    // small launches at N = 2^16: the column passes and the conversion run as one launch between the two row passes
+    const bool cf_on = colfuse_ok(c, cb * beta, beta, al, R) && cb * beta * R <= HE_MAX_LAUNCH_LIMBS;
     {
         std::vector<uint32_t> mods(cb * L1);
         std::vector<uint8_t> seg(cb * L1);
@@ -409,10 +419,50 @@ static int32_t modup_batch(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t l
         }
         t.mod_idx = mods.data(); t.src_seg = seg.data(); t.src_limb = lim.data();
         t.scale = &sc; t.scale_period = L1;
+        t.only_pass = cf_on ? 1u : 0u;
         int32_t rc = launch_transform(c, t);
         if (rc != HE_OK) return rc;
     }
     const uint32_t aw = pad8(al);
+    if (cf_on) {
+        ColFuse cf = {};
+        cf.hat_w = aw; cf.n_groups = cb * beta;
+        uint32_t passes = 0;
+        for (uint32_t j = 0; j < beta; j++) {
+            uint32_t lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1, sz = hi - lo, nt = 0;
+            for (uint32_t r = 0; r < R; r++) {
+                if (r >= lo && r < hi) continue;
+                cf.tgt_limb[j][nt] = (uint8_t)r;
+                cf.tgt_mod[j][nt] = (uint8_t)(r <= level ? r : c->nq + (r - level - 1));
+                nt++;
+            }
+            cf.nt[j] = nt;
+            for (uint32_t s = 0; s < cb; s++) {
+                const uint32_t g = s * beta + j;
+                cf.grp[g].src = tmp + ((size_t)s * L1 + lo) * N;
+                cf.grp[g].dst = raised + ((size_t)s * beta + j) * R * N;
+                cf.grp[g].hat = c->d_up_hat + (size_t)(j * al + (sz - 1)) * c->M * aw;
+                cf.grp[g].ns = sz; cf.grp[g].mod0 = lo; cf.grp[g].sc0 = lo; cf.grp[g].set = j;
+                passes += sz + nt;
+            }
+        }
+        int32_t rc = launch_colfuse(c, cf, sc, passes);
+        if (rc != HE_OK) return rc;
+        std::vector<uint32_t> mods(cb * beta * R);
+        for (uint32_t s = 0; s < cb; s++)
+            for (uint32_t j = 0; j < beta; j++) {
+                uint32_t lo = j * al, hi = (j + 1) * al < L1 ? (j + 1) * al : L1;
+                for (uint32_t r = 0; r < R; r++)
+                    mods[(s * beta + j) * R + r] = (r >= lo && r < hi) ? 0xFFu : (r <= level ? r : c->nq + (r - level - 1));
+            }
+        TransformDesc t = {};
+        t.fwd = true; t.seg[0] = raised; t.n_seg = 1; t.dst = raised; t.n = cb * beta * R; t.mod_idx = mods.data();
+        t.lazy_out = true; t.only_pass = 2;
+        rc = launch_transform(c, t);
+        if (rc != HE_OK) return rc;
+        c->cnt.modup += cb;
+        return HE_OK;
+    }
     for (uint32_t j0 = 0; j0 < beta; j0 += CONV_MAX_JOBS) {
         ConvBatch b;
         b.njobs = beta - j0 < CONV_MAX_JOBS ? beta - j0 : CONV_MAX_JOBS;
@@ -498,6 +548,7 @@ static int32_t launch_inner_product(he_ctx* c, uint32_t level, const IpBatch& ib
 static int32_t moddown_chain(he_ctx* c, uint32_t level, uint32_t J, u64* acc, u64* tmp_dn, u64* conv, const IpPrologue* ip,
                              const ModDownEpilogue& ep) {
     const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k;
+    const bool cf_on = colfuse_ok(c, 2 * J, 1, k, L1) && 2 * J * std::max(k, L1) <= HE_MAX_LAUNCH_LIMBS;
     ScaleList sc;
     for (uint32_t t = 0; t < k; t++) {
         u64 p = c->mod[c->nq + t];
@@ -516,10 +567,24 @@ static int32_t moddown_chain(he_ctx* c, uint32_t level, uint32_t J, u64* acc, u6
         t.fwd = false; t.seg[0] = acc; t.n_seg = 1; t.dst = tmp_dn; t.n = n;
         t.mod_idx = mods.data(); t.src_limb = lim.data(); t.scale = &sc; t.scale_period = k;
         t.ip = ip;
+        t.only_pass = cf_on ? 1u : 0u;
         int32_t rc = launch_transform(c, t);
         if (rc != HE_OK) return rc;
     }
-    {
+    if (cf_on) {
+        ColFuse cf = {};
+        cf.hat_w = pad8(k); cf.n_groups = 2 * J;
+        cf.nt[0] = L1;
+        for (uint32_t r = 0; r < L1; r++) { cf.tgt_limb[0][r] = (uint8_t)r; cf.tgt_mod[0][r] = (uint8_t)r; }
+        for (uint32_t g = 0; g < 2 * J; g++) {
+            cf.grp[g].src = tmp_dn + (size_t)g * k * N;
+            cf.grp[g].dst = conv + (size_t)g * L1 * N;
+            cf.grp[g].hat = c->d_dn_hat;
+            cf.grp[g].ns = k; cf.grp[g].mod0 = c->nq; cf.grp[g].sc0 = 0; cf.grp[g].set = 0;
+        }
+        int32_t rc = launch_colfuse(c, cf, sc, 2 * J * (k + L1));
+        if (rc != HE_OK) return rc;
+    } else {
         ConvBatch b;
         b.njobs = 1; b.reps = 2 * J;
         b.src_stride = (size_t)k * N;
@@ -537,6 +602,7 @@ static int32_t moddown_chain(he_ctx* c, uint32_t level, uint32_t J, u64* acc, u6
         TransformDesc t = {};
         t.fwd = true; t.seg[0] = conv; t.n_seg = 1; t.dst = conv; t.n = n; t.mod_idx = mods.data(); t.ep = &ep;
         t.lazy_out = true;
+        t.only_pass = cf_on ? 2u : 0u;
         int32_t rc = launch_transform(c, t);
         if (rc != HE_OK) return rc;
     }

@@ -16,6 +16,7 @@
 // [0,8q) with one conditional subtraction of 4q per butterfly.  The inverse keeps [0,4q)
 // throughout (sums are reduced, differences re-enter through the twiddle product).
 #include "modarith.h"
+#include "ntt_blocks.h"
 
 #define T16_THREADS 256
 
@@ -58,63 +59,6 @@ __device__ __forceinline__ bool row_sched_decode(const RowSched& rs, uint32_t& l
     tile = rem >> lc;
     limb = rs.order[(pchunk << lc) + (rem & ((1u << lc) - 1u))];
     return limb != 0xFFFFu;
-}
-
-// q4 = 4q throughout this file.
-template <bool WIDE>
-__device__ __forceinline__ void ct_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q4) {
-    if (WIDE) X = csub(X, q4);
-    u64 T = shoup_lazy4(Y, w, w_sh, q);
-    Y = (X + q4) - T;
-    X = X + T;
-}
-
-__device__ __forceinline__ void gs_bfly(u64& X, u64& Y, u64 w, u64 w_sh, u64 q, u64 q4) {
-    u64 s = csub(X + Y, q4);
-    u64 d = (X + q4) - Y;
-    Y = shoup_lazy4(d, w, w_sh, q);
-    X = s;
-}
-
-// Four forward stages on 16 register points; stage u pairs (k, k + (8>>u)); the twiddle of the
-// pair's group g = k >> (4-u) is tw[(1 << (s0+u)) + (G << u) + g], G = group of the 16 points at
-// stage s0.
-template <bool WIDE>
-__device__ __forceinline__ void fwd_block4(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh,
-                                           uint32_t s0, uint32_t G, u64 q, u64 q4) {
-#pragma unroll
-    for (int u = 0; u < 4; u++) {
-        const int dist = 8 >> u;
-        const uint32_t base = (1u << (s0 + u)) + (G << u);
-#pragma unroll
-        for (int g = 0; g < (1 << u); g++) {
-            const u64 w = tw[base + g], w_sh = tw_sh[base + g];
-#pragma unroll
-            for (int k = 0; k < dist; k++) {
-                const int a = g * 2 * dist + k;
-                ct_bfly<WIDE>(x[a], x[a + dist], w, w_sh, q, q4);
-            }
-        }
-    }
-}
-
-// Four inverse stages (point distance 1,2,4,8 in register index), same twiddle indexing.
-__device__ __forceinline__ void inv_block4(u64 (&x)[16], const u64* __restrict__ tw, const u64* __restrict__ tw_sh,
-                                           uint32_t s0, uint32_t G, u64 q, u64 q4) {
-#pragma unroll
-    for (int u = 3; u >= 0; u--) {
-        const int dist = 8 >> u;
-        const uint32_t base = (1u << (s0 + u)) + (G << u);
-#pragma unroll
-        for (int g = 0; g < (1 << u); g++) {
-            const u64 w = tw[base + g], w_sh = tw_sh[base + g];
-#pragma unroll
-            for (int k = 0; k < dist; k++) {
-                const int a = g * 2 * dist + k;
-                gs_bfly(x[a], x[a + dist], w, w_sh, q, q4);
-            }
-        }
-    }
 }
 
 // Inverse stages for moduli below 2^54 with no reduction at all: sums are left to grow and differences are taken
@@ -162,17 +106,6 @@ __device__ __forceinline__ void inv_block3(u64 (&x)[16], const u64* __restrict__
             }
         }
     }
-}
-
-// v mod q for v < 100q: a 7-bit quotient estimated from the top bits (never too large, at most 2
-// too small), then two conditional subtractions.
-__device__ __forceinline__ u64 reduce_small(u64 v, u64 q, uint32_t bits, uint32_t mrec) {
-    const uint32_t sh = bits - 8;                       // q >> sh in [128, 256)
-    uint32_t v1 = (uint32_t)(v >> sh);                  // < 100 * 256
-    uint32_t qh = (v1 * mrec) >> 24;                    // mrec = floor(2^24 / ((q >> sh) + 1))
-    u64 r = v - (u64)qh * q;
-    r = csub(r, 2 * q);
-    return csub(r, q);
 }
 
 // ---------------------------------------------------------------- forward
@@ -286,6 +219,31 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
         // terms - a sum of rotations with one ModDown - and the per-job arrays are indexed by term.
         const uint32_t beta = ep.beta, own_j = r / ep.alpha, n_terms = ep.n_terms ? ep.n_terms : 1u;
         const size_t dig_stride = (size_t)ep.R << 16, key_stride = (size_t)(2 * ep.M) << 16;
+        if (EPI == 3) {
+            // one digit (the low levels the paper's networks run at): every q-limb is the digit's own, and all 16
+            // points' operands are fetched at once - at these sizes a launch is a few work groups per CU and its time
+            // is the length of its dependent load chains
+            const u64* own = ep.own[job] + ((size_t)r << 16);
+            const u64* key = ep.evk[job] + ((size_t)(comp * ep.M + r) << 16) + (size_t)b * 256;
+            u64 dv[16], kv[16], cv[16], sv[16];
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const uint32_t e = t + 16 * k;
+                const uint32_t src = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
+                dv[k] = own[src];
+                kv[k] = key[e];
+                cv[k] = has_c0 ? c0[src] : 0;
+                sv[k] = has_self ? self[e] : 0;
+            }
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const uint32_t e = t + 16 * k;
+                const u64 a = barrett128_lazy((u128)dv[k] * kv[k], q, m.mu, m.bits);
+                const u64 v = shoup_lazy4(a + bias - s[t + 17 * k], pinv, pinv_sh, q) + cv[k] + sv[k];
+                out[e] = csub(csub(csub(v, q4), q2), q);
+            }
+            return;
+        }
 #pragma unroll
         for (int k0 = 0; k0 < 16; k0 += 4) {
             u64 tot[4] = {0, 0, 0, 0};
@@ -408,6 +366,21 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
         const uint32_t pc = limb / ip.k, tp = limb - pc * ip.k, job = pc >> 1, comp = pc & 1u;
         const uint32_t beta = ip.beta, n_terms = ip.n_terms ? ip.n_terms : 1u;
         const size_t dig_stride = (size_t)ip.R << 16, key_stride = (size_t)(2 * ip.M) << 16;
+        if (beta == 1 && ip.n_terms == 0) {
+            // one digit: all 16 points' operands fetched at once (see the epilogue of the forward row pass)
+            const uint32_t g = ip.g[job];
+            const u64* raised = ip.raised[job] + ((size_t)(ip.L1 + tp) << 16);
+            const u64* key = ip.evk[job] + ((size_t)(comp * ip.M + ip.nq + tp) << 16) + (size_t)b * 256;
+            u64 dv[16], kv[16];
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const uint32_t e = t + 16 * k;
+                dv[k] = raised[g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g)];
+                kv[k] = key[e];
+            }
+#pragma unroll
+            for (int k = 0; k < 16; k++) s[t + 17 * k] = barrett128((u128)dv[k] * kv[k], q, m.mu, m.bits);
+        } else
 #pragma unroll
         for (int k0 = 0; k0 < 16; k0 += 4) {
             u64 tot[4] = {0, 0, 0, 0};
@@ -517,6 +490,159 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_a_kernel(Ntt16Args a, L
     for (int k = 0; k < 16; k++) data[(size_t)(t + 16 * k) * 256 + c] = csub(csub(x[k], q2), q);
 }
 
+// ---------------------------------------------------------------- column passes fused around the basis conversion
+// Latency path for small launches (a few limbs: the low levels the paper's networks run at), where the chip is mostly
+// idle and a call is bound by its chain of dependent launches.  The last inverse pass, the basis conversion and the
+// first forward pass all work on columns of the 256 x 256 view, so one work group takes ONE column through all
+// three: every source limb of a group (a digit of ModUp, the special-prime limbs of one ModDown component; at most 8)
+// goes through the inverse column stages and its output scaling into LDS, then every target limb is converted from
+// those (128-bit sums, lazy Barrett), run through the forward column stages and written.  One launch instead of
+// three; the coefficient-form limbs and the converted limbs never exist in memory.  One wavefront per limb, four
+// points per lane (two stages in registers, then an exchange through LDS), so that a conversion of a single digit
+// already spreads over every compute unit; the 8-byte accesses this makes (a column is strided by 2 KiB) cost
+// bandwidth that a launch this small does not need.
+#define CF_THREADS 512
+#define CF_WAVES 8
+#define CF_EX 272            // 256 points + one spare per 16
+
+__device__ __forceinline__ uint32_t cf_pos(uint32_t i) { return i + (i >> 4); }
+
+__global__ __launch_bounds__(CF_THREADS) void ntt16_colfuse_kernel(ColFuse cf, ScaleList sc, const ModConst* mc, const u64* tw,
+                                                                   const u64* tw_sh, const u64* itw, const u64* itw_sh) {
+    __shared__ u64 ys[CF_WAVES * 256];
+    __shared__ u64 ex[CF_WAVES * CF_EX];
+    // work groups go to the XCDs round-robin: give each XCD 32 adjacent columns, so that the sixteen columns that
+    // share a 128-byte line are read and written through one L2
+    const uint32_t g = blockIdx.x >> 8, c = (blockIdx.x & 7) * 32 + ((blockIdx.x >> 3) & 31);
+    const uint32_t w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const CfGroup gp = cf.grp[g];
+    const uint32_t ns = gp.ns, set = gp.set, nt = cf.nt[set];
+    u64* exw = ex + w * CF_EX;
+    u64 x[4];
+    // Everything a wavefront will need is requested before anything is computed, so that the dependent memory round
+    // trips (arguments -> constants of the modulus -> data and twiddles) are paid once, not once per phase: the source
+    // limb's points and all its twiddles, and for the first target limb its modulus and conversion constants.
+    const bool src_on = w < ns;
+    const uint32_t mi = gp.mod0 + (src_on ? w : 0);
+    const u64* data = gp.src + ((size_t)(src_on ? w : 0) << 16) + c;
+    if (src_on) {
+#pragma unroll
+        for (int k = 0; k < 4; k++) x[k] = data[(size_t)(4 * lane + k) * 256];
+    }
+    u64 t1[4][6];
+#pragma unroll
+    for (int blk = 0; blk < 4; blk++) tw_block2(t1[blk], itw + ((size_t)mi << 16), itw_sh + ((size_t)mi << 16), 2 * blk, lane >> (6 - 2 * blk));
+    const ModConst m1 = mc[mi];
+    const uint32_t si = gp.sc0 + (src_on ? w : 0);
+    const u64 cs = sc.s[si], cs_sh = sc.s_sh[si];
+    uint32_t mr = cf.tgt_mod[set][w < nt ? w : 0];
+    ModConst m2 = mc[mr];
+    u64 hat[CF_WAVES];                                       // a row of the table is padded to 8 entries, zeros past ns
+#pragma unroll
+    for (int i = 0; i < CF_WAVES; i++) hat[i] = gp.hat[(size_t)mr * cf.hat_w + i];
+    {   // inverse column stages 7..0 of source w (wavefronts beyond the group's sources idle through the barriers)
+        const u64 q = m1.q, q4 = 2 * m1.q2;
+#pragma unroll
+        for (int blk = 3; blk >= 0; blk--) {
+            const uint32_t s0 = 2 * blk, log_span = 6 - s0, span = 1u << log_span;
+            const uint32_t G = lane >> log_span, base = (G << (8 - s0)) + (lane & (span - 1));
+            if (blk < 3) {
+                __syncthreads();
+                if (src_on) {
+#pragma unroll
+                    for (int k = 0; k < 4; k++) x[k] = exw[cf_pos(base + (k << log_span))];
+                }
+            }
+            if (src_on) {
+                inv_block2_r(x, t1[blk], q, q4);
+                if (blk > 0) {
+#pragma unroll
+                    for (int k = 0; k < 4; k++) exw[cf_pos(base + (k << log_span))] = x[k];
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; k++) ys[w * 256 + lane + 64 * k] = csub(shoup_lazy(x[k], cs, cs_sh, q), q);
+                }
+            }
+        }
+    }
+    for (uint32_t t0 = 0; t0 < nt; t0 += CF_WAVES) {
+        const uint32_t ti = t0 + w;
+        const bool active = ti < nt;
+        if (t0) {                                            // later rounds fetch their constants as they start
+            mr = cf.tgt_mod[set][active ? ti : 0];
+            m2 = mc[mr];
+#pragma unroll
+            for (int i = 0; i < CF_WAVES; i++) hat[i] = gp.hat[(size_t)mr * cf.hat_w + i];
+        }
+        u64 t2[4][6];
+#pragma unroll
+        for (int blk = 0; blk < 4; blk++) tw_block2(t2[blk], tw + ((size_t)mr << 16), tw_sh + ((size_t)mr << 16), 2 * blk, lane >> (6 - 2 * blk));
+        __syncthreads();                                     // the sources are in ys (first round)
+        const u64 q = m2.q, q4 = 2 * m2.q2;
+        const bool wide = m2.bits > 57;
+        if (active) {
+            u128 acc[4] = {};
+#pragma unroll
+            for (int i = 0; i < CF_WAVES; i++) {
+                if ((uint32_t)i < ns) {
+#pragma unroll
+                    for (int k = 0; k < 4; k++) acc[k] += (u128)ys[i * 256 + lane + 64 * k] * hat[i];
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) x[k] = barrett128_lazy(acc[k], q, m2.mu, m2.bits);      // below 5q
+        }
+#pragma unroll
+        for (int blk = 0; blk < 4; blk++) {
+            const uint32_t s0 = 2 * blk, log_span = 6 - s0, span = 1u << log_span;
+            const uint32_t G = lane >> log_span, base = (G << (8 - s0)) + (lane & (span - 1));
+            if (blk > 0) {
+                __syncthreads();
+                if (active) {
+#pragma unroll
+                    for (int k = 0; k < 4; k++) x[k] = exw[cf_pos(base + (k << log_span))];
+                }
+            }
+            if (active) {
+                if (wide) fwd_block2_r<true>(x, t2[blk], q, q4);
+                else fwd_block2_r<false>(x, t2[blk], q, q4);
+                if (blk < 3) {
+#pragma unroll
+                    for (int k = 0; k < 4; k++) exw[cf_pos(base + (k << log_span))] = x[k];
+                }
+            }
+        }
+        if (active) {
+            u64* dst = gp.dst + ((size_t)cf.tgt_limb[set][ti] << 16) + c;
+#pragma unroll
+            for (int k = 0; k < 4; k++) dst[(size_t)(4 * lane + k) * 256] = x[k];
+        }
+    }
+}
+
+int32_t launch_colfuse(he_ctx* ctx, const ColFuse& cf, const ScaleList& sc, uint32_t limb_passes) {
+    if (cf.n_groups == 0) return HE_OK;
+    if (cf.n_groups > CF_MAX_GROUPS) return he_fail(ctx, HE_ERR_BADARG, "column fusion: too many groups");
+    for (uint32_t g = 0; g < cf.n_groups; g++)
+        if (cf.grp[g].ns == 0 || cf.grp[g].ns > CF_WAVES || cf.grp[g].set >= CF_MAX_SETS || cf.grp[g].mod0 + cf.grp[g].ns > ctx->M ||
+            cf.grp[g].sc0 + cf.grp[g].ns > HE_MAX_MODULI || !cf.grp[g].src || !cf.grp[g].dst || !cf.grp[g].hat)
+            return he_fail(ctx, HE_ERR_BADARG, "column fusion: bad group %u", g);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (ctx->prof_on) {
+        HE_HIP(ctx, hipEventCreate(&e0));
+        HE_HIP(ctx, hipEventCreate(&e1));
+        HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
+    }
+    hipLaunchKernelGGL(ntt16_colfuse_kernel, dim3(cf.n_groups * 256), dim3(CF_THREADS), 0, ctx->stream, cf, sc, ctx->d_mc, ctx->d_tw,
+                       ctx->d_tw_sh, ctx->d_itw, ctx->d_itw_sh);
+    HE_HIP(ctx, hipGetLastError());
+    if (ctx->prof_on) {
+        HE_HIP(ctx, hipEventRecord(e1, ctx->stream));
+        ctx->prof_events.push_back({e0, e1, limb_passes, 0u, 0u});
+    }
+    return HE_OK;
+}
+
 // ---------------------------------------------------------------- butterfly-rate probe
 // The vector-ALU roof of the transforms, measured rather than derived: the register blocks of the passes
 // above (four stages on 16 points, twiddles from a 256-entry table that stays in the first-level cache)
@@ -614,6 +740,7 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
     for (uint32_t i = live; i < padded && i < HE_MAX_LAUNCH_LIMBS; i++) rs.order[i] = 0xFFFF;
     dim3 grid_rows(padded * 16);
     for (int pass = 0; pass < 2; pass++) {
+        if (d.only_pass && d.only_pass != (uint32_t)pass + 1) continue;
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (ctx->prof_on) {
             HE_HIP(ctx, hipEventCreate(&e0));
@@ -621,6 +748,8 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
         }
         if (fwd && pass == 0) hipLaunchKernelGGL(ntt16_fwd_a_kernel, grid, block, 0, ctx->stream, a, ll, sl);
+        else if (fwd && d.ep && d.ep->fused && d.ep->beta == 1 && d.ep->n_terms == 0)      // single digit: its own instantiation
+            hipLaunchKernelGGL(ntt16_fwd_b_kernel<3>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
         else if (fwd && d.ep && d.ep->fused) hipLaunchKernelGGL(ntt16_fwd_b_kernel<2>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
         else if (fwd && d.ep) hipLaunchKernelGGL(ntt16_fwd_b_kernel<1>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
         else if (fwd) { ModDownEpilogue none = {}; hipLaunchKernelGGL(ntt16_fwd_b_kernel<0>, grid_rows, block, 0, ctx->stream, a, ll, rs, none); }

@@ -456,3 +456,43 @@ def test_two_pass_generic_rings_key_switching(logN, q_bits, p_bits):
     out = zeros(2, 5, N)
     ctx.he_rotate(dev(ct), 4, 1, out)
     assert np.max(np.abs(cl.decrypt(host(out), 4, scale) - np.roll(z, -1))) < 1e-3
+
+
+def test_low_levels_single_launch_conversions():
+    """N = 2^16 at the low levels the networks run at, where a single key switch is a handful of limbs: the
+    conversions take the single-launch column kernel (inverse column pass, basis conversion and forward column
+    pass in one).  One full digit (levels 5, 7), two digits (8, 15: a one-limb and a full second digit), singly,
+    hoisted in pairs and as a conjugation, bit for bit against the oracle; a batch of three rotations (large
+    enough to take the separate kernels) must give the same bits as the single calls."""
+    from gpu_util import dev, host, zeros
+    prm = config_params(2)
+    rng, orc, ctx, cl = _setup(prm, 77)
+    N = prm.N
+    steps = [1, 2, 4]
+    keys = {s: _key(prm, rng, cl, orc.galois_elt(s)) for s in steps}
+    kc = _key(prm, rng, cl, orc.galois_conj)
+    for s, k in keys.items():
+        ctx.he_evk_register(ctx.galois_elt(s), dev(k))
+    ctx.he_evk_register(2 * N - 1, dev(kc))
+    for level in (5, 7, 8, 15):
+        print("level", level, flush=True)
+        ct = _rand_ct(prm, rng, level)
+        d = dev(ct)
+        want = {s: orc.rotate(ct, level, orc.galois_elt(s), keys[s]) for s in steps}
+        single = {}
+        for s in steps:
+            o = zeros(2, level + 1, N)
+            ctx.he_rotate(d, level, s, o)
+            single[s] = host(o)
+            assert (single[s] == want[s]).all(), (level, s, "single")
+        outs = [zeros(2, level + 1, N) for _ in range(2)]
+        ctx.he_rotate_hoisted(d, level, steps[:2], outs)
+        for s, o in zip(steps[:2], outs):
+            assert (host(o) == want[s]).all(), (level, s, "hoisted pair")
+        outs = [zeros(2, level + 1, N) for _ in steps]
+        ctx.he_rotate_batch([d], level, steps, outs, hoisted=True)
+        for s, o in zip(steps, outs):
+            assert (host(o) == want[s]).all(), (level, s, "batch of three")
+        oc = zeros(2, level + 1, N)
+        ctx.he_conjugate(d, level, oc)
+        assert (host(oc) == orc.rotate(ct, level, orc.galois_conj, kc)).all(), (level, "conj")
