@@ -108,6 +108,35 @@ __device__ __forceinline__ void inv_block3(u64 (&x)[16], const u64* __restrict__
     }
 }
 
+// Inner product of four points over the digits: sum[k] += digit_j[src[k]] * key_j[16 k] for j < beta, JW digits
+// at a time so that their loads are in flight together.  JW = 3 is the exact form for three digits (the paper's
+// dnum at the top levels): no padding digit, no predicates; the caller guarantees beta == 3.  Digit own_j is read
+// from `own` (the switched polynomial's limb itself), the others from raised + j * dig_stride.
+template <int JW>
+__device__ __forceinline__ void ip_accumulate(u128 (&sum)[4], const u64* __restrict__ raised, const u64* __restrict__ own, uint32_t own_j,
+                                              const u64* __restrict__ key, size_t dig_stride, size_t key_stride, uint32_t beta,
+                                              const uint32_t (&src)[4]) {
+    for (uint32_t j0 = 0; j0 < (JW == 3 ? 3u : beta); j0 += JW) {
+        u64 dv[JW][4], kv[JW][4];
+#pragma unroll
+        for (uint32_t jj = 0; jj < (uint32_t)JW; jj++) {
+            const uint32_t j = j0 + jj;
+            const bool live = JW == 3 || j < beta;
+            const u64* dj = j == own_j ? own : raised + (live ? j : 0) * dig_stride;
+            const u64* kj = key + (live ? j : 0) * key_stride;
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                dv[jj][k] = live ? dj[src[k]] : 0;
+                kv[jj][k] = live ? kj[16 * k] : 0;
+            }
+        }
+#pragma unroll
+        for (uint32_t jj = 0; jj < (uint32_t)JW; jj++)
+#pragma unroll
+            for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
+    }
+}
+
 // ---------------------------------------------------------------- forward
 // Pass A: workgroup = 16 adjacent columns x all 256 rows of one limb; tid = t*16 + col.
 template <bool WIDE>
@@ -272,25 +301,8 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
                 }
 #pragma unroll
                 for (int k = 0; k < 4; k++) sum[k] = 0;
-                for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
-                    u64 dv[4][4], kv[4][4];
-#pragma unroll
-                    for (uint32_t jj = 0; jj < 4; jj++) {
-                        const uint32_t j = j0 + jj;
-                        const bool live = j < beta;
-                        const u64* dj = j == own_j ? own : raised + (live ? j : 0) * dig_stride;
-                        const u64* kj = key + (live ? j : 0) * key_stride;
-#pragma unroll
-                        for (int k = 0; k < 4; k++) {
-                            dv[jj][k] = live ? dj[src[k]] : 0;
-                            kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
-                        }
-                    }
-#pragma unroll
-                    for (uint32_t jj = 0; jj < 4; jj++)
-#pragma unroll
-                        for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
-                }
+                if (beta == 3) ip_accumulate<3>(sum, raised, own, own_j, key + t + 16 * k0, dig_stride, key_stride, beta, src);
+                else ip_accumulate<4>(sum, raised, own, own_j, key + t + 16 * k0, dig_stride, key_stride, beta, src);
                 // each term's sum is reduced to [0, 5q) only (three-product quotient, no correction); up to 16 of
                 // them add up below 80q, and the P^-1 product below takes any 64-bit value
 #pragma unroll
@@ -397,25 +409,8 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
                     src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
                     sum[k] = 0;
                 }
-                for (uint32_t j0 = 0; j0 < beta; j0 += 4) {
-                    u64 dv[4][4], kv[4][4];
-#pragma unroll
-                    for (uint32_t jj = 0; jj < 4; jj++) {
-                        const uint32_t j = j0 + jj;
-                        const bool live = j < beta;
-                        const u64* dj = raised + (live ? j : 0) * dig_stride;
-                        const u64* kj = key + (live ? j : 0) * key_stride;
-#pragma unroll
-                        for (int k = 0; k < 4; k++) {
-                            dv[jj][k] = live ? dj[src[k]] : 0;
-                            kv[jj][k] = live ? kj[t + 16 * (k0 + k)] : 0;
-                        }
-                    }
-#pragma unroll
-                    for (uint32_t jj = 0; jj < 4; jj++)
-#pragma unroll
-                        for (int k = 0; k < 4; k++) sum[k] += (u128)dv[jj][k] * kv[jj][k];
-                }
+                if (beta == 3) ip_accumulate<3>(sum, raised, nullptr, 0xFFFFFFFFu, key + t + 16 * k0, dig_stride, key_stride, beta, src);
+                else ip_accumulate<4>(sum, raised, nullptr, 0xFFFFFFFFu, key + t + 16 * k0, dig_stride, key_stride, beta, src);
 #pragma unroll
                 for (int k = 0; k < 4; k++) {
                     const u64 a = barrett128(sum[k], q, m.mu, m.bits);
