@@ -84,6 +84,15 @@ def run_only(args, torch, ctx, prm, gen):
 
         def fn():
             ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, ct, outs)
+        if args.only == "raconv":                        # reordered RAConv on 8 inputs, one ModDown per output
+            lv = level - 1
+            ins = [uniform_dev(torch, gen, prm.q[:lv + 1], N, lead=(2,)) for _ in range(8)]
+            ra_w = [w[:lv + 1] for w in weights]
+            ra_out = torch.empty((2, lv, N), dtype=torch.uint64, device="cuda")
+            ctx.he_ws_reserve(ctx.he_ws_query_raconv(8, 32, 2, 3, lv, deferred=True))
+
+            def fn():
+                ctx.he_raconv(32, 2, 3, lv, ra_w, ins, ra_out, deferred=True)
     for _ in range(args.warmup):
         fn()
     torch.cuda.synchronize()
@@ -103,7 +112,7 @@ def main():
     ap.add_argument("--batch", type=int, default=64, help="ciphertexts per step (configs[2] names 64)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the NTT and conv2d extra measurements")
-    ap.add_argument("--only", choices=["ntt", "conv2d", "conv0", "crot5", "conv5"], help="run just this extra workload --steps times (for profiling "
+    ap.add_argument("--only", choices=["ntt", "conv2d", "conv0", "crot5", "conv5", "raconv"], help="run just this extra workload --steps times (for profiling "
                     "it in isolation) and print its own small JSON line instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:

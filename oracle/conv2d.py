@@ -87,12 +87,95 @@ def encode_weights(orc: Oracle, geo: ConvGeometry, wt, level, pt_scale):
     return pts
 
 
-def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, progress=None):
+def encode_weights_raised(orc: Oracle, geo: ConvGeometry, wt, level, pt_scale):
+    """The same filter plaintexts over the raised basis q_0..q_level, p_0..p_{k-1}: the integer polynomial of
+    each encoding reduced modulo every one of those primes, NTT form: uint64 [n_out][f^2][level+1+k][N].  The
+    first level+1 limbs equal encode_weights' (same polynomial, same primes)."""
+    mods = orc.raised_moduli(level)
+    pts = np.empty((geo.n_out, len(geo.taps), len(mods), orc.N), dtype=np.uint64)
+    for o in range(geo.n_out):
+        for t in range(len(geo.taps)):
+            m = encode(geo.weight_slots(wt, o, t).astype(np.complex128), orc.N, pt_scale)
+            pts[o, t] = orc.ntt(orc.reduce_signed(m, mods), mods)
+    return pts
+
+
+def slide_mac_deferred(orc: Oracle, geo: ConvGeometry, ct, level, pts_raised, evks, keep=False):
+    """Slide_f and MulFilter&Sum_f of Algorithm 1 with the ModDown of the tap rotations deferred across the sum
+    over the taps: the filter plaintexts multiply the key-switch inner products while these are still over the
+    raised basis, and only each output's sum is brought down.  With (c0, c1) the input, d = ModUp(c1), g_t the
+    Galois element of tap t and pt_{o,t} the plaintext of output o and tap t:
+        A_t          = sum_j sigma_{g_t}(d_j) * evk_{g_t},j                       (both components, raised basis)
+        ACC_o        = sum_{t: g_t != 1} pt_{o,t} * A_t                           (raised basis)
+        out_o        = ( ModDown(ACC_o,0) + sum_{t: g_t != 1} pt_{o,t} * sigma_{g_t}(c0) + pt_{o,c} * c0 ,
+                         ModDown(ACC_o,1) + pt_{o,c} * c1 )                       (c = the tap that does not rotate)
+    which is the product-sum of the rotated inputs up to one ModDown rounding per output instead of one per
+    tap scaled by the plaintext.  Returns the n_out accumulators [2][level+1][N] (before Rescale)."""
+    L1, rm = level + 1, orc.raised_moduli(level)
+    qm = list(range(L1))
+    raised = orc.modup(ct[1], level)
+    ips, rot0 = {}, {}
+    for t, step in enumerate(geo.tap_steps):
+        if step == 0:
+            continue
+        g = orc.galois_elt(step)
+        ips[t] = orc.inner_product(orc.automorph_ntt(raised, g), level, evks[step])
+        rot0[t] = orc.automorph_ntt(ct[0], g)
+    outs, inter = [], {"ip": ips, "acc_raised": [], "plain": []}
+    for o in range(geo.n_out):
+        acc = None                                   # [2][R][N] over the raised basis
+        p0 = None                                    # plain (un-switched) part of component 0, [L1][N]
+        p1 = None
+        for t, step in enumerate(geo.tap_steps):
+            w_q = pts_raised[o, t, :L1]
+            if step == 0:
+                a = orc.pointwise_mul(ct[0], w_q, qm)
+                p0 = a if p0 is None else orc.add_limbs(p0, a, qm)
+                p1 = orc.pointwise_mul(ct[1], w_q, qm)
+                continue
+            term = np.stack([orc.pointwise_mul(ips[t][c], pts_raised[o, t], rm) for c in range(2)])
+            acc = term if acc is None else orc.add_limbs(acc, term, rm + rm)
+            a = orc.pointwise_mul(rot0[t], w_q, qm)
+            p0 = a if p0 is None else orc.add_limbs(p0, a, qm)
+        if acc is None:
+            out = np.stack([p0, p1])
+        else:
+            o0 = orc.add_limbs(orc.moddown(acc[0], level), p0, qm)
+            o1 = orc.moddown(acc[1], level)
+            if p1 is not None:
+                o1 = orc.add_limbs(o1, p1, qm)
+            out = np.stack([o0, o1])
+        inter["acc_raised"].append(acc)
+        inter["plain"].append((p0, p1))
+        outs.append(out)
+    return (outs, inter) if keep else outs
+
+
+def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, progress=None, deferred_taps=False):
     """ct [2][level+1][N] -> list of n_out ciphertexts [2][level][N].
 
     evks: dict slot-step -> evaluation key of the Galois element 5^step.
-    With keep=True also returns every intermediate (for limb-by-limb parity checks)."""
+    With keep=True also returns every intermediate (for limb-by-limb parity checks).
+    deferred_taps: Slide_f and MulFilter&Sum_f share one ModDown per output (slide_mac_deferred); `pts` are
+    then the plaintexts over the raised basis (encode_weights_raised)."""
     inter = {"slide": [], "mac": [], "rescaled": [], "ras": []}
+    if deferred_taps:
+        macs = slide_mac_deferred(orc, geo, ct, level, pts, evks)
+        outs = []
+        for o in range(geo.n_out):
+            inter["mac"].append(macs[o])
+            cur = orc.rescale(macs[o], level)
+            inter["rescaled"].append(cur)
+            steps_out = []
+            for step in geo.ras_steps:
+                rot = orc.rotate(cur, level - 1, orc.galois_elt(step), evks[step])
+                cur = orc.add(cur, rot, level - 1)
+                steps_out.append(cur)
+            inter["ras"].append(steps_out)
+            outs.append(cur)
+            if progress:
+                progress("oracle caconv (one ModDown per output): output %d/%d done" % (o + 1, geo.n_out))
+        return (outs, inter) if keep else outs
     # Slide_f: all rotations of the one input share a single ModUp of c1 (same bits as
     # separate rotations by construction)
     raised = orc.modup(ct[1], level)
