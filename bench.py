@@ -359,6 +359,13 @@ def main():
         conv_out = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
         ms_conv = timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, cts[0], conv_out), reps=2)
         extras["conv2d_ms"] = round(ms_conv, 3)
+        # the same layer with Slide_f and MulFilter&Sum_f sharing one ModDown per output (plaintexts over the raised
+        # basis); with n_out = f^2 - 1 = 8 this saves no ModDown here, it pays off for fewer outputs or wider filters
+        w_raised = [uniform_dev(torch, gen, list(prm.q) + list(prm.p), N) for _ in range(8 * 9)]
+        ctx.he_ws_reserve(ctx.he_ws_query_conv2d(16, 32, 32, 2, 3, level, 8, deferred_taps=True))
+        extras["conv2d_one_moddown_per_output_ms"] = round(
+            timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, w_raised, cts[0], conv_out, deferred_taps=True), reps=2), 3)
+        del w_raised
         # the same layer on a 6-limb ciphertext (level 5, where the paper's networks run their convolutions)
         lo_w = [w[:6] for w in weights]
         lo_in = cts[0][:, :6, :].contiguous()
@@ -430,6 +437,12 @@ def main():
         w0 = [uniform_dev(torch, gen, prm0.q, N0) for _ in range(9)]
         out0 = [torch.empty((2, lv0, N0), dtype=torch.uint64, device="cuda")]
         extras["conv2d_config0_us"] = round(1e3 * timed(lambda: ctx0.he_conv2d(4, 8, 8, 8, 3, lv0, w0, ct0, out0), reps=20), 1)
+        # one output and eight rotated taps: one ModDown instead of eight (through the general kernels, not the
+        # single-launch ones the tap-by-tap order takes on this ring)
+        w0r = [uniform_dev(torch, gen, list(prm0.q) + list(prm0.p), N0) for _ in range(9)]
+        ctx0.he_ws_reserve(ctx0.he_ws_query_conv2d(4, 8, 8, 8, 3, lv0, 1, deferred_taps=True))
+        extras["conv2d_config0_one_moddown_us"] = round(
+            1e3 * timed(lambda: ctx0.he_conv2d(4, 8, 8, 8, 3, lv0, w0r, ct0, out0, deferred_taps=True), reps=20), 1)
         del ctx0
 
     cpu = None

@@ -74,6 +74,15 @@ typedef struct {
     uint32_t level;              /* level of the input; outputs are at level-1 */
     uint32_t skip_ras;           /* != 0: stop after the Rescale (no rotate-and-sum over C_a, no keys needed for it); the
                                     caller sums later with he_ras, e.g. after merging outputs into the stride gap */
+    uint32_t deferred_taps;      /* != 0: Slide_f and MulFilter&Sum_f (Algorithm 1) share ONE ModDown per output: the
+                                    hoisted key-switch inner products of the f^2-1 rotated taps stay over the raised
+                                    basis q_0..q_level, p_0..p_{k-1}, the filter plaintexts multiply them there, and
+                                    only each output's sum is brought down (the un-switched parts, plaintext times
+                                    rotated c0 and the tap that does not rotate, are added over the ciphertext
+                                    primes).  Every weight plaintext is then [level+1+k][N]: the same integer
+                                    polynomial reduced modulo the ciphertext primes first, then the special primes.
+                                    Same values up to rounding (one ModDown rounding per output instead of one per
+                                    tap scaled by the plaintext), different bits; n_out ModDowns instead of f^2-1. */
     const uint64_t* const* h_d_weights; /* host array of n_out*f*f device pointers */
 } he_conv_plan;
 

@@ -12,9 +12,11 @@
 #define CV_MAX_OUT_PER_LAUNCH 16
 
 struct MacTaps {
-    const u64* ct[CV_MAX_TAPS];                          // rotated inputs [2][L1][N]
+    const u64* ct[CV_MAX_TAPS];                          // rotated inputs [2][CL][N]
     uint32_t n_taps, n_out;
-    u64* acc[CV_MAX_OUT_PER_LAUNCH];                     // one accumulator [2][L1][N] per output
+    uint32_t c1_tap;                                     // 0xFFFFFFFF: every tap has both components; else only this tap
+                                                         // has a second component (the others are [CL][N])
+    u64* acc[CV_MAX_OUT_PER_LAUNCH];                     // one accumulator [2][CL][N] per output
 };
 struct MacWeights {
     const u64* pt[CV_MAX_OUT_PER_LAUNCH * 9];            // [out][tap] filter plaintexts [L1][N] (9-tap fast path)
@@ -22,18 +24,20 @@ struct MacWeights {
 
 // MulFilter&Sum_f for several output ciphertexts at once (9 taps or fewer): the rotated inputs of a
 // coefficient are loaded once and reused for every output, acc_o,c[limb] = sum_t ct_t,c[limb] *
-// pt_o,t[limb], summed in 128 bits and reduced once per 8 taps.  grid: (N/256, L1).
+// pt_o,t[limb], summed in 128 bits and reduced once per 8 taps.  grid: (N/256, CL).  Operands and outputs have CL
+// limbs per component: the level+1 ciphertext primes, followed by the special primes when the operands are
+// key-switch inner products still over the raised basis (CL = level+1+k).
 __global__ __launch_bounds__(CV_THREADS) void mac_taps9_kernel(MacTaps taps, MacWeights w, const ModConst* mc, uint32_t logN,
-                                                               uint32_t L1) {
+                                                               uint32_t CL, uint32_t level, uint32_t nq) {
     const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
     const uint32_t limb = blockIdx.y;
-    const ModConst m = mc[limb];
-    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n;
+    const ModConst m = mc[limb <= level ? limb : nq + (limb - level - 1)];
+    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + CL) << logN) + n;
     u64 c0[9], c1[9];
 #pragma unroll
     for (uint32_t t = 0; t < 9; t++) {
         c0[t] = t < taps.n_taps ? taps.ct[t][o0] : 0;
-        c1[t] = t < taps.n_taps ? taps.ct[t][o1] : 0;
+        c1[t] = (t < taps.n_taps && (taps.c1_tap == 0xFFFFFFFFu || taps.c1_tap == t)) ? taps.ct[t][o1] : 0;
     }
     for (uint32_t o = 0; o < taps.n_out; o++) {
         u128 a0 = 0, a1 = 0;
@@ -58,15 +62,16 @@ struct MacTapsAny {
     const u64* ct[CV_MAX_TAPS];
     const u64* pt[CV_MAX_TAPS];
     uint32_t n, init;
+    uint32_t c1_tap;                                     // as in MacTaps
 };
 // Any number of (ciphertext, plaintext) products, one output per launch; init = 0 continues from the
-// accumulator's current (canonical) contents.
+// accumulator's current (canonical) contents.  CL, level, nq as in mac_taps9_kernel.
 __global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTapsAny taps, u64* __restrict__ acc, const ModConst* mc,
-                                                              uint32_t logN, uint32_t L1) {
+                                                              uint32_t logN, uint32_t CL, uint32_t level, uint32_t nq) {
     const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
     const uint32_t limb = blockIdx.y;
-    const ModConst m = mc[limb];
-    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n;
+    const ModConst m = mc[limb <= level ? limb : nq + (limb - level - 1)];
+    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + CL) << logN) + n;
     u128 a0 = taps.init ? 0 : acc[o0], a1 = taps.init ? 0 : acc[o1];
     for (uint32_t t = 0; t < taps.n; t++) {
         if (t && (t & 7) == 0) {
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(CV_THREADS) void mac_taps_kernel(MacTapsAny taps, u
         }
         u64 p = taps.pt[t][o0];
         a0 += (u128)taps.ct[t][o0] * p;
-        a1 += (u128)taps.ct[t][o1] * p;
+        if (taps.c1_tap == 0xFFFFFFFFu || taps.c1_tap == t) a1 += (u128)taps.ct[t][o1] * p;
     }
     acc[o0] = barrett128(a0, m.q, m.mu, m.bits);
     acc[o1] = barrett128(a1, m.q, m.mu, m.bits);
@@ -95,8 +100,21 @@ static std::vector<uint32_t> tap_slot_steps(uint32_t W, uint32_t R, uint32_t f, 
 
 // he_conv2d workspace: [key-switch engine region][rescale scratch][rotated inputs][n_out accumulators at `level`]
 // [n_out temporaries at level-1]
-static size_t conv2d_ws_elems(const he_ctx* ctx, uint32_t level, uint32_t n_rot, uint32_t n_out) {
+// With the ModDown deferred across the taps the rotated inputs are replaced by (at the start of the region, where the
+// engine's scratch of the rotate-and-sum steps lives later): [ModUp scratch][n_rot inner products over the raised
+// basis][accumulators of one chunk of outputs over the raised basis][ModDown scratch][n_rot rotated c0][the chunk's
+// plain parts].
+static size_t conv2d_deferred_elems(const he_ctx* ctx, uint32_t level, uint32_t n_rot, uint32_t n_out) {
+    const size_t N = ctx->N, L1 = level + 1, R = L1 + ctx->np, nb = std::min<uint32_t>(n_out, HE_MAX_KS_JOBS);
+    return ks_raised_products_ws_elems(ctx, level) + (size_t)n_rot * 2 * R * N + nb * 2 * R * N + ks_moddown_stored_ws_elems(ctx, level, (uint32_t)nb) +
+           (size_t)n_rot * L1 * N + nb * 2 * L1 * N;
+}
+static size_t conv2d_ws_elems(const he_ctx* ctx, uint32_t level, uint32_t n_rot, uint32_t n_out, bool deferred_taps = false) {
     const size_t N = ctx->N, ct_e = (size_t)2 * (level + 1) * N, ct_lo_e = (size_t)2 * level * N;
+    if (deferred_taps && n_rot) {
+        const size_t head = std::max(conv2d_deferred_elems(ctx, level, n_rot, n_out), ks_engine_ws_elems(ctx, level - 1, n_out, n_out));
+        return head + rescale_ws_elems(ctx, level, n_out) + (size_t)n_out * ct_e + (size_t)n_out * ct_lo_e;
+    }
     const size_t ks_e = std::max(n_rot ? ks_engine_ws_elems(ctx, level, 1, n_rot) : 0, ks_engine_ws_elems(ctx, level - 1, n_out, n_out));
     return ks_e + rescale_ws_elems(ctx, level, n_out) + (size_t)(n_rot + n_out) * ct_e + (size_t)n_out * ct_lo_e;
 }
@@ -108,7 +126,7 @@ extern "C" int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* pla
     if ((plan->f & 1u) == 0 || plan->f * plan->f > CV_MAX_TAPS || plan->n_out == 0) return HE_ERR_BADARG;
     uint32_t n_rot = 0;
     for (uint32_t st : tap_slot_steps(plan->W, plan->R, plan->f, ctx->N / 2)) n_rot += st != 0;
-    *h_bytes = conv2d_ws_elems(ctx, plan->level, n_rot, plan->n_out) * sizeof(u64);
+    *h_bytes = conv2d_ws_elems(ctx, plan->level, n_rot, plan->n_out, plan->deferred_taps != 0) * sizeof(u64);
     return HE_OK;
     });
 }
@@ -157,19 +175,101 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
     uint32_t n_rot = 0;
     for (uint32_t t = 0; t < taps; t++) n_rot += tap_g[t] != 1;
     const size_t ct_e = (size_t)2 * L1 * N, ct_lo_e = (size_t)2 * level * N;
-    const size_t total = conv2d_ws_elems(ctx, level, n_rot, n_out);
+    const bool deferred_taps = plan->deferred_taps != 0 && n_rot > 0;
+    if (deferred_taps && n_rot + 1 != taps)
+        return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: deferred_taps needs exactly one tap that does not rotate (%u of %u do)", taps - n_rot, taps);
+    const size_t total = conv2d_ws_elems(ctx, level, n_rot, n_out, deferred_taps);
     int32_t rc = he_ensure_ws(ctx, total * sizeof(u64));
     if (rc != HE_OK) return rc;
     // laid out from the end of the region: [engine ...][rescale scratch][rotated inputs][accumulators][temporaries]
     u64* tmp = ctx->d_ws + total - (size_t)n_out * ct_lo_e;  // [n_out] ciphertexts at level lo
     u64* acc = tmp - (size_t)n_out * ct_e;                   // [n_out] ciphertexts at `level`
-    u64* slid = acc - (size_t)n_rot * ct_e;                  // [n_rot] rotated inputs
+    u64* slid = acc - (size_t)(deferred_taps ? 0 : n_rot) * ct_e;   // [n_rot] rotated inputs
     u64* rs_ws = slid - rescale_ws_elems(ctx, level, n_out);
     const u64* ct_in = (const u64*)d_ct_in;
 
+    if (deferred_taps) {
+        // Slide_f and MulFilter&Sum_f with one ModDown per output: the plaintexts (given over the raised basis)
+        // multiply the hoisted inner products before these are brought down
+        const uint32_t k = ctx->np, R = L1 + k;
+        u64* prod_ws = ctx->d_ws;
+        u64* A = prod_ws + ks_raised_products_ws_elems(ctx, level);              // [n_rot][2][R][N]
+        const uint32_t nb_max = std::min<uint32_t>(n_out, HE_MAX_KS_JOBS);
+        u64* ACC = A + (size_t)n_rot * 2 * R * N;                                // [nb][2][R][N]
+        u64* md_ws = ACC + (size_t)nb_max * 2 * R * N;
+        u64* rot0 = md_ws + ks_moddown_stored_ws_elems(ctx, level, nb_max);      // [n_rot][L1][N]
+        u64* plain = rot0 + (size_t)n_rot * L1 * N;                              // [nb][2][L1][N]
+        std::vector<uint32_t> gs, rot_tap;                                       // the rotated taps, in tap order
+        std::vector<const u64*> keys;
+        uint32_t centre = 0xFFFFFFFFu;
+        for (uint32_t t = 0; t < taps; t++) {
+            if (tap_g[t] == 1) { centre = t; continue; }
+            gs.push_back(tap_g[t]); keys.push_back(tap_key[t]); rot_tap.push_back(t);
+        }
+        rc = ks_raised_products(ctx, level, ct_in + (size_t)L1 * N, gs.data(), keys.data(), n_rot, A, prod_ws);
+        if (rc != HE_OK) return rc;
+        for (uint32_t i = 0; i < n_rot; i++) {
+            rc = launch_automorph_ntt(ctx, ct_in, rot0 + (size_t)i * L1 * N, L1, gs[i]);
+            if (rc != HE_OK) return rc;
+        }
+        // operand of tap t in the plain part: the rotated c0 (one component) or the input itself (both)
+        std::vector<const u64*> plain_ct(taps);
+        for (uint32_t i = 0; i < n_rot; i++) plain_ct[rot_tap[i]] = rot0 + (size_t)i * L1 * N;
+        if (centre != 0xFFFFFFFFu) plain_ct[centre] = ct_in;
+        dim3 block(CV_THREADS), grid_r(N / CV_THREADS, R), grid_q(N / CV_THREADS, L1);
+        for (uint32_t o0 = 0; o0 < n_out; o0 += nb_max) {
+            const uint32_t nb = std::min<uint32_t>(nb_max, n_out - o0);
+            if (n_rot <= 9 && taps <= 9) {
+                MacTaps mt;
+                MacWeights mw;
+                mt.n_taps = n_rot; mt.n_out = nb; mt.c1_tap = 0xFFFFFFFFu;
+                for (uint32_t i = 0; i < n_rot; i++) mt.ct[i] = A + (size_t)i * 2 * R * N;
+                for (uint32_t o = 0; o < nb; o++) {
+                    mt.acc[o] = ACC + (size_t)o * 2 * R * N;
+                    for (uint32_t i = 0; i < n_rot; i++) mw.pt[o * 9 + i] = (const u64*)plan->h_d_weights[(size_t)(o0 + o) * taps + rot_tap[i]];
+                }
+                hipLaunchKernelGGL(mac_taps9_kernel, grid_r, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, R, level, ctx->nq);
+                HE_HIP(ctx, hipGetLastError());
+                mt.n_taps = taps; mt.c1_tap = centre;
+                for (uint32_t t = 0; t < taps; t++) mt.ct[t] = plain_ct[t];
+                for (uint32_t o = 0; o < nb; o++) {
+                    mt.acc[o] = plain + (size_t)o * 2 * L1 * N;
+                    for (uint32_t t = 0; t < taps; t++) mw.pt[o * 9 + t] = (const u64*)plan->h_d_weights[(size_t)(o0 + o) * taps + t];
+                }
+                hipLaunchKernelGGL(mac_taps9_kernel, grid_q, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, L1, level, ctx->nq);
+                HE_HIP(ctx, hipGetLastError());
+            } else {
+                for (uint32_t o = 0; o < nb; o++) {
+                    MacTapsAny mt;
+                    mt.n = n_rot; mt.init = 1; mt.c1_tap = 0xFFFFFFFFu;
+                    for (uint32_t i = 0; i < n_rot; i++) {
+                        mt.ct[i] = A + (size_t)i * 2 * R * N;
+                        mt.pt[i] = (const u64*)plan->h_d_weights[(size_t)(o0 + o) * taps + rot_tap[i]];
+                    }
+                    hipLaunchKernelGGL(mac_taps_kernel, grid_r, block, 0, ctx->stream, mt, ACC + (size_t)o * 2 * R * N, ctx->d_mc, ctx->logN, R, level, ctx->nq);
+                    HE_HIP(ctx, hipGetLastError());
+                    mt.n = taps; mt.c1_tap = centre;
+                    for (uint32_t t = 0; t < taps; t++) { mt.ct[t] = plain_ct[t]; mt.pt[t] = (const u64*)plan->h_d_weights[(size_t)(o0 + o) * taps + t]; }
+                    hipLaunchKernelGGL(mac_taps_kernel, grid_q, block, 0, ctx->stream, mt, plain + (size_t)o * 2 * L1 * N, ctx->d_mc, ctx->logN, L1, level, ctx->nq);
+                    HE_HIP(ctx, hipGetLastError());
+                }
+            }
+            std::vector<const u64*> a0(nb), a1(nb);
+            std::vector<u64*> o_0(nb), o_1(nb);
+            for (uint32_t o = 0; o < nb; o++) {
+                a0[o] = plain + (size_t)o * 2 * L1 * N;
+                a1[o] = centre != 0xFFFFFFFFu ? a0[o] + (size_t)L1 * N : nullptr;
+                o_0[o] = acc + (size_t)(o0 + o) * ct_e;
+                o_1[o] = o_0[o] + (size_t)L1 * N;
+            }
+            rc = ks_moddown_stored(ctx, level, nb, ACC, a0.data(), a1.data(), o_0.data(), o_1.data(), md_ws);
+            if (rc != HE_OK) return rc;
+        }
+        ctx->cnt.mac += (uint64_t)taps * n_out;
+    }
     // Slide_f: one ModUp of c1 shared by all taps
     std::vector<const u64*> tap_ct(taps);
-    {
+    if (!deferred_taps) {
         KsSrc src = {ct_in, ct_in + (size_t)L1 * N, nullptr, nullptr};
         std::vector<KsJob> jobs;
         uint32_t nb = 0;
@@ -194,30 +294,32 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
     }
     {
         dim3 grid(N / CV_THREADS, L1), block(CV_THREADS);
-        if (taps <= 9) {
+        if (deferred_taps) {
+            // the accumulators are already in place
+        } else if (taps <= 9) {
             for (uint32_t o0 = 0; o0 < n_out; o0 += CV_MAX_OUT_PER_LAUNCH) {
                 MacTaps mt;
                 MacWeights mw;
-                mt.n_taps = taps;
+                mt.n_taps = taps; mt.c1_tap = 0xFFFFFFFFu;
                 mt.n_out = std::min<uint32_t>(CV_MAX_OUT_PER_LAUNCH, n_out - o0);
                 for (uint32_t t = 0; t < taps; t++) mt.ct[t] = tap_ct[t];
                 for (uint32_t o = 0; o < mt.n_out; o++) {
                     mt.acc[o] = acc + (size_t)(o0 + o) * ct_e;
                     for (uint32_t t = 0; t < taps; t++) mw.pt[o * 9 + t] = (const u64*)plan->h_d_weights[(size_t)(o0 + o) * taps + t];
                 }
-                hipLaunchKernelGGL(mac_taps9_kernel, grid, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, L1);
+                hipLaunchKernelGGL(mac_taps9_kernel, grid, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, L1, level, ctx->nq);
                 HE_HIP(ctx, hipGetLastError());
             }
         } else {
             for (uint32_t o = 0; o < n_out; o++) {
                 MacTapsAny mt;
-                mt.n = taps; mt.init = 1;
+                mt.n = taps; mt.init = 1; mt.c1_tap = 0xFFFFFFFFu;
                 for (uint32_t t = 0; t < taps; t++) { mt.ct[t] = tap_ct[t]; mt.pt[t] = (const u64*)plan->h_d_weights[(size_t)o * taps + t]; }
-                hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc + (size_t)o * ct_e, ctx->d_mc, ctx->logN, L1);
+                hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc + (size_t)o * ct_e, ctx->d_mc, ctx->logN, L1, level, ctx->nq);
                 HE_HIP(ctx, hipGetLastError());
             }
         }
-        ctx->cnt.mac += (uint64_t)taps * n_out;
+        if (!deferred_taps) ctx->cnt.mac += (uint64_t)taps * n_out;
         std::vector<const u64*> accs(n_out);
         for (uint32_t o = 0; o < n_out; o++) accs[o] = acc + (size_t)o * ct_e;
         rc = rescale_batch(ctx, accs.data(), cur.data(), n_out, level, rs_ws);
@@ -606,14 +708,14 @@ extern "C" int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const 
                 for (uint32_t o0 = 0; o0 < g; o0 += CV_MAX_OUT_PER_LAUNCH) {
                     MacTaps mt;
                     MacWeights mw;
-                    mt.n_taps = taps;
+                    mt.n_taps = taps; mt.c1_tap = 0xFFFFFFFFu;
                     mt.n_out = std::min<uint32_t>(CV_MAX_OUT_PER_LAUNCH, g - o0);
                     for (uint32_t t = 0; t < taps; t++) mt.ct[t] = slid[t];
                     for (uint32_t o = 0; o < mt.n_out; o++) {
                         mt.acc[o] = acc + (size_t)(o0 + o) * ct_hi;
                         for (uint32_t t = 0; t < taps; t++) mw.pt[o * 9 + t] = (const u64*)plan->h_d_w_ca[(size_t)(j0 + o0 + o) * taps + t];
                     }
-                    hipLaunchKernelGGL(mac_taps9_kernel, grid, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, level + 1);
+                    hipLaunchKernelGGL(mac_taps9_kernel, grid, block, 0, ctx->stream, mt, mw, ctx->d_mc, ctx->logN, level + 1, level, ctx->nq);
                     HE_HIP(ctx, hipGetLastError());
                 }
             } else {
@@ -622,12 +724,12 @@ extern "C" int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const 
                     for (size_t i0 = 0; i0 < terms; i0 += CV_MAX_TAPS) {
                         MacTapsAny mt;
                         mt.n = (uint32_t)std::min<size_t>(CV_MAX_TAPS, terms - i0);
-                        mt.init = i0 == 0;
+                        mt.init = i0 == 0; mt.c1_tap = 0xFFFFFFFFu;
                         for (uint32_t i = 0; i < mt.n; i++) {
                             mt.ct[i] = slid[i0 + i];                                       // [k][tap] flattened
                             mt.pt[i] = (const u64*)plan->h_d_w_ca[(size_t)(j0 + o) * terms + i0 + i];
                         }
-                        hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc + (size_t)o * ct_hi, ctx->d_mc, ctx->logN, level + 1);
+                        hipLaunchKernelGGL(mac_taps_kernel, grid, block, 0, ctx->stream, mt, acc + (size_t)o * ct_hi, ctx->d_mc, ctx->logN, level + 1, level, ctx->nq);
                         HE_HIP(ctx, hipGetLastError());
                     }
             }

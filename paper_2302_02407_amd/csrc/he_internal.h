@@ -257,6 +257,12 @@ struct KsSumTerm {
 };
 size_t ks_rotate_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_rot);
 int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms, uint32_t n_terms, u64* out0, u64* out1, u64* ws);
+// Hoisted inner products kept over the raised basis, and the ModDown of stored accumulators (keyswitch.hip)
+size_t ks_raised_products_ws_elems(const he_ctx* c, uint32_t level);
+int32_t ks_raised_products(he_ctx* c, uint32_t level, const u64* c1, const uint32_t* gs, const u64* const* evks, uint32_t n, u64* acc, u64* ws);
+size_t ks_moddown_stored_ws_elems(const he_ctx* c, uint32_t level, uint32_t J);
+int32_t ks_moddown_stored(he_ctx* c, uint32_t level, uint32_t J, u64* acc, const u64* const* add0, const u64* const* add1,
+                          u64* const* out0, u64* const* out1, u64* ws);
 // Latency path for rings whose limb fits one work group's LDS (smallring.hip)
 bool small_ring_path(const he_ctx* c, uint32_t level);
 int32_t sr_modup(he_ctx* c, const KsSrc* srcs, uint32_t cb, uint32_t level, u64* raised);

@@ -849,6 +849,72 @@ int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms
     return HE_OK;
 }
 
+// ---------------------------------------------------------------- products kept over the raised basis
+// Building blocks of a sum of (plaintext x rotation) terms with one ModDown (the ModDown of Slide_f deferred
+// across MulFilter&Sum_f of Algorithm 1): the hoisted inner products of one polynomial with n keys, stored over
+// the raised basis, and the ModDown of stored accumulators with addends over the ciphertext primes.
+
+// scratch of ks_raised_products: raised [beta][R][N] + tmp [L1][N]
+size_t ks_raised_products_ws_elems(const he_ctx* c, uint32_t level) {
+    const size_t L1 = level + 1, R = L1 + c->np, beta = num_digits(c, level);
+    return (beta * R + L1) * c->N;
+}
+
+// acc[t] = sum_j sigma_{g_t}(ModUp(c1)_j) * evk_t,j for t < n, both components: acc [n][2][R][N], canonical.
+int32_t ks_raised_products(he_ctx* c, uint32_t level, const u64* c1, const uint32_t* gs, const u64* const* evks, uint32_t n, u64* acc,
+                           u64* ws) {
+    const uint32_t N = c->N, L1 = level + 1, R = L1 + c->np, beta = num_digits(c, level);
+    u64* raised = ws;
+    u64* tmp_up = raised + (size_t)beta * R * N;
+    KsSrc src = {nullptr, c1, nullptr, nullptr};
+    int32_t rc = modup_batch(c, &src, 1, level, raised, tmp_up);
+    if (rc != HE_OK) return rc;
+    for (uint32_t t0 = 0; t0 < n; t0 += HE_MAX_KS_JOBS) {
+        const uint32_t cnt = std::min<uint32_t>(HE_MAX_KS_JOBS, n - t0);
+        IpBatch ib;
+        for (uint32_t i = 0; i < cnt; i++) {
+            ib.raised[i] = raised; ib.own[i] = c1;
+            ib.evk[i] = evks[t0 + i]; ib.g[i] = gs[t0 + i]; ib.start[i] = i; ib.count[i] = 1;
+        }
+        rc = launch_inner_product(c, level, ib, cnt, acc + (size_t)t0 * 2 * R * N);
+        if (rc != HE_OK) return rc;
+        if (c->prof_on) c->prof_key_limbs += (uint64_t)cnt * 2 * beta * R;
+    }
+    c->cnt.keyswitch += n;
+    return HE_OK;
+}
+
+// scratch of ks_moddown_stored for up to HE_MAX_KS_JOBS accumulators at once: tmp_dn [J][2][k][N] + conv [J][2][L1][N]
+size_t ks_moddown_stored_ws_elems(const he_ctx* c, uint32_t level, uint32_t J) {
+    const size_t nb = std::min<uint32_t>(J ? J : 1, HE_MAX_KS_JOBS);
+    return nb * (2 * c->np + 2 * (level + 1)) * c->N;
+}
+
+// out_i = ( ModDown(acc_i,0) + add0_i , ModDown(acc_i,1) + add1_i ) for the J stored accumulators acc [J][2][R][N];
+// add0_i / add1_i [L1][N] or null.
+int32_t ks_moddown_stored(he_ctx* c, uint32_t level, uint32_t J, u64* acc, const u64* const* add0, const u64* const* add1,
+                          u64* const* out0, u64* const* out1, u64* ws) {
+    const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k;
+    if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
+    for (uint32_t j0 = 0; j0 < J; j0 += HE_MAX_KS_JOBS) {
+        const uint32_t nb = std::min<uint32_t>(HE_MAX_KS_JOBS, J - j0);
+        u64* a = acc + (size_t)j0 * 2 * R * N;
+        u64* tmp_dn = ws;
+        u64* conv = tmp_dn + (size_t)nb * 2 * k * N;
+        ModDownEpilogue ep = {};
+        ep.acc = a; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
+        ep.fused = 0; ep.beta = num_digits(c, level); ep.alpha = c->alpha; ep.M = c->M;
+        for (uint32_t i = 0; i < nb; i++) {
+            ep.c0[i] = nullptr; ep.g[i] = 1;
+            ep.self0[i] = add0 ? add0[j0 + i] : nullptr; ep.self1[i] = add1 ? add1[j0 + i] : nullptr;
+            ep.out0[i] = out0[j0 + i]; ep.out1[i] = out1[j0 + i];
+        }
+        int32_t rc = moddown_chain(c, level, nb, a, tmp_dn, conv, nullptr, ep);
+        if (rc != HE_OK) return rc;
+    }
+    return HE_OK;
+}
+
 // ---------------------------------------------------------------- rescale
 
 // scratch for rescaling up to HE_MAX_KS_JOBS ciphertexts at once: tmp[2n][N] + delta[n][2][level][N]
