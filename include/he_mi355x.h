@@ -234,6 +234,16 @@ int32_t he_conjugate(he_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t
  * init != 0 overwrites d_acc instead of accumulating.  d_acc may not overlap d_ct / d_pt. */
 int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const uint64_t* d_pt,
                     uint32_t level, int32_t init);
+
+/* d_acc (= | +=) sum_{i<n} ct_i * sigma_{g_i}(pt_i): MulPt-accumulate with each plaintext rotated as it is read (PRot
+ * of Table 1 fused into the product, no key involved).  This is the operation PRCR needs (paper Section 3.3: a
+ * weight plaintext whose fragments are arranged circularly is reused through plaintext rotations instead of being
+ * stored once per use).  h_d_ct[i] [2][level+1][N] and h_d_pt[i] [level+1][N] are device pointers in host arrays,
+ * NTT form; h_galois[i] is odd and below 2N (1 = no rotation; 5^step mod 2N rotates the slots left by step).
+ * init != 0 overwrites d_acc, else accumulates into its canonical contents.  d_acc may not overlap
+ * any operand (HE_ERR_BADARG).  n = 0 with init != 0 clears d_acc. */
+int32_t he_ptct_mac_rot(he_ctx* ctx, uint64_t* d_acc, const uint64_t* const* h_d_ct, const uint64_t* const* h_d_pt,
+                        const uint32_t* h_galois, uint32_t n, uint32_t level, int32_t init);
 /* AddCt: d_out = d_a + d_b on [2][level+1][N]; d_out may alias d_a or d_b. */
 int32_t he_add(he_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, uint64_t* d_out);
 

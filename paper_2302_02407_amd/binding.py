@@ -19,7 +19,7 @@ EXPORTS = [
     "he_ctx_create", "he_ctx_destroy", "he_last_error", "he_ctx_psi", "he_counters", "he_counters_reset", "he_sync", "he_profile_begin", "he_profile_end",
     "he_ntt", "he_intt", "he_automorph", "he_evk_register", "he_keyswitch", "he_rotate_hoisted", "he_rotate_batch", "he_rotate",
     "he_conjugate", "he_ptct_mac", "he_add", "he_addpt", "he_mulct", "he_affine", "he_rescale", "he_conv2d", "he_raconv",
-    "he_probe_alu", "he_build_id", "he_rotate_sum", "he_ws_query_raconv", "he_ca_ra_block", "he_ws_query_ca_ra_block", "he_ras", "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc",
+    "he_probe_alu", "he_build_id", "he_rotate_sum", "he_ws_query_raconv", "he_ca_ra_block", "he_ws_query_ca_ra_block", "he_ras", "he_ws_bytes", "he_ws_reserve", "he_ws_query_rotate_batch", "he_ws_query_conv2d", "he_rescale_noalloc", "he_ptct_mac_rot",
 ]
 
 
@@ -113,6 +113,7 @@ def load():
         "he_ws_query_rotate_batch": [vp, u32, u32, u32, i32, u64p],
         "he_ws_query_conv2d": [vp, C.POINTER(ConvPlan), u64p],
         "he_rescale_noalloc": [vp, vp, u32, vp],
+        "he_ptct_mac_rot": [vp, vp, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(u32), u32, u32, i32],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -401,6 +402,22 @@ class HEContext:
         plan = ConvPlan(C_a, H, W, R, f, n_out, level, 1 if skip_ras else 0, 1 if deferred_taps else 0, C.cast(wa, C.POINTER(C.c_void_p)))
         self._ck(self._lib.he_conv2d(self._h, C.byref(plan), _dev(ct_in), oa))
         return outs
+
+    def he_ptct_mac_rot(self, acc, cts, pts, galois, level, init=True):
+        """acc (= | +=) sum_i cts[i] * sigma_{galois[i]}(pts[i]) (plaintexts rotated on the fly)."""
+        if not (len(cts) == len(pts) == len(galois)):
+            raise ValueError("cts, pts and galois must have the same length")
+        _need(acc, 2 * (level + 1) * self.N, "acc")
+        for c in cts:
+            _need(c, 2 * (level + 1) * self.N, "ciphertext")
+        for p in pts:
+            _need(p, (level + 1) * self.N, "plaintext")
+        n = len(cts)
+        ca = (C.c_void_p * max(1, n))(*[_dev(c).value for c in cts])
+        pa = (C.c_void_p * max(1, n))(*[_dev(p).value for p in pts])
+        ga = (C.c_uint32 * max(1, n))(*[int(g) for g in galois])
+        self._ck(self._lib.he_ptct_mac_rot(self._h, _dev(acc), ca, pa, ga, n, level, 1 if init else 0))
+        return acc
 
     def he_ws_query_raconv(self, n_in, W, R, f, level, deferred=False):
         v = C.c_uint64()

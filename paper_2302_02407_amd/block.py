@@ -195,3 +195,30 @@ def downsample_handoff(ctx, C_a, Hp, Wp, R0, level, ct_in, p1, p2, mask_kappa, p
     if keep:
         return l3, {"l1_conv": conv1, "l1": l1, "l2_conv": ra, "l2": l2, "l3_conv": ca, "l3": l3}
     return l3
+
+
+def prcr_caconv_1x1(ctx, S, frag, level, plaintexts, cts_in, outs):
+    """Pointwise convolution on the rearranged channel-aligned format (paper Section 3.3, PRCR): input ciphertext k
+    holds, on row segment s, channel (k+s) mod S; plaintexts[o] holds Wt[o, s] on segment s and is reused for every
+    input through a plaintext rotation by k fragments (`frag` slots each): out[o] = Rescale(sum_k cts_in[k] *
+    PRot(plaintexts[o], k*frag)) is the whole image of output channel o.  S plaintexts serve the S*S pairs."""
+    N = ctx.N
+    gs = [ctx.galois_elt(k * frag) for k in range(S)]
+    acc = _ct(level, N)
+    for o in range(S):
+        ctx.he_ptct_mac_rot(acc, cts_in, [plaintexts[o]] * S, gs, level, init=True)
+        ctx.he_rescale(acc, level, outs[o])
+    return outs
+
+
+def prcr_raconv_1x1(ctx, S, frag, level, plaintexts, cts_in, outs):
+    """The other direction: cts_in[c] is the whole image of channel c, plaintexts[c] holds Wt[s, c] on segment s;
+    outs[k] = Rescale(sum_c cts_in[c] * PRot(plaintexts[c], k*frag)) is in the rearranged format again (segment s =
+    output channel (k+s) mod S)."""
+    N = ctx.N
+    acc = _ct(level, N)
+    for k in range(S):
+        ctx.he_ptct_mac_rot(acc, cts_in, plaintexts, [ctx.galois_elt(k * frag)] * S, level, init=True)
+        ctx.he_rescale(acc, level, outs[k])
+    return outs
+

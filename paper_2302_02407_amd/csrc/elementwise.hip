@@ -1,4 +1,6 @@
 // Coefficient-wise kernels: Galois permutation, MulPt-accumulate, AddCt, and their entry points.
+#include <algorithm>
+
 #include "modarith.h"
 
 #define EW_THREADS 256
@@ -51,6 +53,36 @@ __global__ __launch_bounds__(EW_THREADS) void ptct_mac_kernel(u64* __restrict__ 
     }
     acc[o0] = r0;
     acc[o1] = r1;
+}
+
+// acc (+)= sum_i ct_i * sigma_{g_i}(pt_i): the plaintext is permuted as it is read (a plaintext rotation fused into
+// the product), products summed in 128 bits and reduced once per 8 terms.  limb = blockIdx.y.
+#define MACROT_MAX 16
+struct MacRot {
+    const u64* ct[MACROT_MAX];   // [2][n_limbs][N]
+    const u64* pt[MACROT_MAX];   // [n_limbs][N]
+    uint32_t g[MACROT_MAX];
+    uint32_t n;
+};
+__global__ __launch_bounds__(EW_THREADS) void ptct_mac_rot_kernel(u64* __restrict__ acc, MacRot mr, const ModConst* mc, uint32_t logN,
+                                                                  uint32_t n_limbs, int init) {
+    const uint32_t n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const uint32_t limb = blockIdx.y;
+    const ModConst m = mc[limb];
+    const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + n_limbs) << logN) + n;
+    u128 a0 = init ? 0 : acc[o0], a1 = init ? 0 : acc[o1];
+    for (uint32_t i = 0; i < mr.n; i++) {
+        if (i && (i & 7) == 0) {
+            a0 = barrett128(a0, m.q, m.mu, m.bits);
+            a1 = barrett128(a1, m.q, m.mu, m.bits);
+        }
+        const uint32_t g = mr.g[i];
+        const u64 p = mr.pt[i][((size_t)limb << logN) + (g == 1 ? n : galois_src(n, g, logN))];
+        a0 += (u128)mr.ct[i][o0] * p;
+        a1 += (u128)mr.ct[i][o1] * p;
+    }
+    acc[o0] = barrett128(a0, m.q, m.mu, m.bits);
+    acc[o1] = barrett128(a1, m.q, m.mu, m.bits);
 }
 
 __global__ __launch_bounds__(EW_THREADS) void add_kernel(const u64* a, const u64* b, u64* out, const ModConst* mc,
@@ -191,6 +223,41 @@ int32_t he_ptct_mac(he_ctx* ctx, uint64_t* d_acc, const uint64_t* d_ct, const ui
                        ctx->d_mc, ctx->logN, level + 1, init);
     HE_HIP(ctx, hipGetLastError());
     ctx->cnt.mac += 1;
+    return HE_OK;
+    });
+}
+
+int32_t he_ptct_mac_rot(he_ctx* ctx, uint64_t* d_acc, const uint64_t* const* h_d_ct, const uint64_t* const* h_d_pt,
+                        const uint32_t* h_galois, uint32_t n, uint32_t level, int32_t init) {
+    return he_guard(ctx, "he_ptct_mac_rot: host allocation failed", [&]() -> int32_t {
+    if (!ctx) return HE_ERR_BADARG;
+    if (!d_acc || (n && (!h_d_ct || !h_d_pt || !h_galois))) return he_fail(ctx, HE_ERR_BADARG, "he_ptct_mac_rot: null argument");
+    if (level >= ctx->nq) return he_fail(ctx, HE_ERR_LEVEL, "he_ptct_mac_rot: level %u above L=%u", level, ctx->nq - 1);
+    const size_t pb = (size_t)(level + 1) * ctx->N * sizeof(u64);
+    for (uint32_t i = 0; i < n; i++) {
+        if (!h_d_ct[i] || !h_d_pt[i]) return he_fail(ctx, HE_ERR_BADARG, "he_ptct_mac_rot: operand %u is null", i);
+        if ((h_galois[i] & 1u) == 0 || h_galois[i] >= 2 * ctx->N)
+            return he_fail(ctx, HE_ERR_BADARG, "he_ptct_mac_rot: Galois element %u is not odd and below 2N", h_galois[i]);
+        const char *a = (const char*)d_acc, *c = (const char*)h_d_ct[i], *p = (const char*)h_d_pt[i];
+        if ((a < c + 2 * pb && c < a + 2 * pb) || (a < p + pb && p < a + 2 * pb))
+            return he_fail(ctx, HE_ERR_BADARG, "he_ptct_mac_rot: the accumulator overlaps operand %u", i);
+    }
+    dim3 grid(ctx->N / EW_THREADS, level + 1), block(EW_THREADS);
+    if (n == 0 && init) {                                  // an empty sum: the accumulator is cleared
+        MacRot mr = {};
+        hipLaunchKernelGGL(ptct_mac_rot_kernel, grid, block, 0, ctx->stream, (u64*)d_acc, mr, ctx->d_mc, ctx->logN, level + 1, 1);
+        HE_HIP(ctx, hipGetLastError());
+    }
+    for (uint32_t i0 = 0; i0 < n; i0 += MACROT_MAX) {
+        MacRot mr = {};
+        mr.n = std::min<uint32_t>(MACROT_MAX, n - i0);
+        for (uint32_t i = 0; i < mr.n; i++) { mr.ct[i] = (const u64*)h_d_ct[i0 + i]; mr.pt[i] = (const u64*)h_d_pt[i0 + i]; mr.g[i] = h_galois[i0 + i]; }
+        hipLaunchKernelGGL(ptct_mac_rot_kernel, grid, block, 0, ctx->stream, (u64*)d_acc, mr, ctx->d_mc, ctx->logN, level + 1,
+                           (init && i0 == 0) ? 1 : 0);
+        HE_HIP(ctx, hipGetLastError());
+    }
+    ctx->cnt.mac += n;
+    for (uint32_t i = 0; i < n; i++) ctx->cnt.automorph += h_galois[i] != 1 ? level + 1 : 0;
     return HE_OK;
     });
 }
