@@ -315,6 +315,7 @@ def main():
         ms_rt = timed(roundtrip, reps=10)
         extras["ntt_roundtrip_ms"] = round(ms_rt, 4)
         extras["ntt_limb_GBps"] = round(384 * N * 8 * 2 * 2 / (ms_rt * 1e-3) / 1e9, 1)
+        extras["ntt_limb_frac_of_hbm_peak"] = round(extras["ntt_limb_GBps"] / HBM_PEAK_GBS, 4)
         del data
         # the streaming operations on one ciphertext at level 23, as GB/s of the bytes they must move
         ct_bytes = 2 * L1 * N * 8

@@ -303,6 +303,7 @@ def test_mac_add_rescale(cfg, level):
     (40, 12, 41, 1, 12, (11, 8, 5, 0)),     # alpha 1, one special prime; 12 and 9 digits take the unfused inner product
     (50, 6, 60, 3, 2, (5, 3, 2)),           # alpha 3 with 60-bit special primes, partial and single digits
     (57, 4, 58, 2, 2, (3, 1)),              # widest narrow-path primes (57 bits) and wide-path special primes
+    (54, 6, 60, 2, 3, (5, 4, 2, 0)),        # alpha 2, three digits: three target sets in one single-launch conversion
 ])
 def test_n65536_other_decompositions(q_bits, nq, p_bits, np_, dnum, levels):
     """The N = 2^16 kernels away from the benchmark's parameter set: other digit widths and counts (fused and
