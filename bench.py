@@ -367,11 +367,23 @@ def main():
         extras["conv2d_one_moddown_per_output_ms"] = round(
             timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, w_raised, cts[0], conv_out, deferred_taps=True), reps=2), 3)
         del w_raised
+        # the same layer with the rotate-and-sum over C_a as one hoisted sum of its 15 rotations per output (one ModUp
+        # and one ModDown per output instead of four of each; needs the keys of every multiple of H*W*R)
+        for i in range(1, 16):
+            s = 2048 * i
+            if s not in keys:
+                keys[s] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+                ctx.he_evk_register(ctx.galois_elt(s), keys[s])
+        ctx.he_ws_reserve(ctx.he_ws_query_conv2d(16, 32, 32, 2, 3, level, 8, hoisted_ras=True))
+        extras["conv2d_hoisted_ras_ms"] = round(
+            timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, cts[0], conv_out, hoisted_ras=True), reps=3), 3)
         # the same layer on a 6-limb ciphertext (level 5, where the paper's networks run their convolutions)
         lo_w = [w[:6] for w in weights]
         lo_in = cts[0][:, :6, :].contiguous()
         lo_outs = [torch.empty((2, 5, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
         extras["conv2d_level5_ms"] = round(timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, 5, lo_w, lo_in, lo_outs), reps=5), 3)
+        extras["conv2d_level5_hoisted_ras_ms"] = round(
+            timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, 5, lo_w, lo_in, lo_outs, hoisted_ras=True), reps=5), 3)
         del lo_w, lo_in, lo_outs
         # the layer that consumes those 8 outputs: reordered RAConv (Algorithm 2), 8 inputs x 9 taps at level 22
         ra_w = [w[:level] for w in weights]

@@ -83,6 +83,12 @@ typedef struct {
                                     polynomial reduced modulo the ciphertext primes first, then the special primes.
                                     Same values up to rounding (one ModDown rounding per output instead of one per
                                     tap scaled by the plaintext), different bits; n_out ModDowns instead of f^2-1. */
+    uint32_t hoisted_ras;        /* != 0: the rotate-and-sum over C_a (Section 2.2) is evaluated as the sum of the C_a-1
+                                    rotations of each rescaled output by i*H*W*R slots (i = 1..C_a-1) plus the output
+                                    itself, with ONE ModUp and ONE ModDown per output and every key shared by all
+                                    outputs, instead of log2(C_a) dependent rotate-and-add steps.  Needs the C_a-1 keys
+                                    (not only the log2(C_a) power-of-two ones); C_a <= 49.  Same sum, one ModDown
+                                    rounding instead of log2(C_a); bits differ from the stepwise form. */
     const uint64_t* const* h_d_weights; /* host array of n_out*f*f device pointers */
 } he_conv_plan;
 

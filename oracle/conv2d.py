@@ -151,13 +151,26 @@ def slide_mac_deferred(orc: Oracle, geo: ConvGeometry, ct, level, pts_raised, ev
     return (outs, inter) if keep else outs
 
 
-def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, progress=None, deferred_taps=False):
+def ras_hoisted(orc: Oracle, geo: ConvGeometry, cur, level, evks):
+    """Rotate-and-sum over C_a (Section 2.2) as the sum of the C_a - 1 rotations of `cur` by i*H*W*R slots plus `cur`
+    itself, the rotations sharing one ModUp (they rotate the same ciphertext) and one ModDown (rotate_sum_deferred):
+    the same sum as the log2(C_a) rotate-and-add steps, with one ModDown rounding instead of log2(C_a)."""
+    base = geo.H * geo.W * geo.R
+    steps = [base * i for i in range(1, geo.C_a)]
+    gs = [1] + [orc.galois_elt(st) for st in steps]
+    return orc.rotate_sum_deferred([cur] * geo.C_a, level, gs, [None] + [evks[st] for st in steps])
+
+
+def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, progress=None, deferred_taps=False,
+           hoisted_ras=False):
     """ct [2][level+1][N] -> list of n_out ciphertexts [2][level][N].
 
     evks: dict slot-step -> evaluation key of the Galois element 5^step.
     With keep=True also returns every intermediate (for limb-by-limb parity checks).
     deferred_taps: Slide_f and MulFilter&Sum_f share one ModDown per output (slide_mac_deferred); `pts` are
-    then the plaintexts over the raised basis (encode_weights_raised)."""
+    then the plaintexts over the raised basis (encode_weights_raised).
+    hoisted_ras: the rotate-and-sum as one hoisted sum of rotations per output (ras_hoisted); evks must then hold
+    the keys of i*H*W*R for every i < C_a."""
     inter = {"slide": [], "mac": [], "rescaled": [], "ras": []}
     if deferred_taps:
         macs = slide_mac_deferred(orc, geo, ct, level, pts, evks)
@@ -167,10 +180,14 @@ def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, pro
             cur = orc.rescale(macs[o], level)
             inter["rescaled"].append(cur)
             steps_out = []
-            for step in geo.ras_steps:
-                rot = orc.rotate(cur, level - 1, orc.galois_elt(step), evks[step])
-                cur = orc.add(cur, rot, level - 1)
+            if hoisted_ras and geo.C_a > 1:
+                cur = ras_hoisted(orc, geo, cur, level - 1, evks)
                 steps_out.append(cur)
+            else:
+                for step in geo.ras_steps:
+                    rot = orc.rotate(cur, level - 1, orc.galois_elt(step), evks[step])
+                    cur = orc.add(cur, rot, level - 1)
+                    steps_out.append(cur)
             inter["ras"].append(steps_out)
             outs.append(cur)
             if progress:
@@ -197,10 +214,14 @@ def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, pro
         cur = orc.rescale(acc, level)
         inter["rescaled"].append(cur)
         steps_out = []
-        for step in geo.ras_steps:
-            rot = orc.rotate(cur, level - 1, orc.galois_elt(step), evks[step])
-            cur = orc.add(cur, rot, level - 1)
+        if hoisted_ras and geo.C_a > 1:
+            cur = ras_hoisted(orc, geo, cur, level - 1, evks)
             steps_out.append(cur)
+        else:
+            for step in geo.ras_steps:
+                rot = orc.rotate(cur, level - 1, orc.galois_elt(step), evks[step])
+                cur = orc.add(cur, rot, level - 1)
+                steps_out.append(cur)
         inter["ras"].append(steps_out)
         outs.append(cur)
         if progress:

@@ -47,7 +47,7 @@ class AluProbe(C.Structure):
 
 class ConvPlan(C.Structure):
     _fields_ = [("C_a", C.c_uint32), ("H", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32),
-                ("n_out", C.c_uint32), ("level", C.c_uint32), ("skip_ras", C.c_uint32), ("deferred_taps", C.c_uint32),
+                ("n_out", C.c_uint32), ("level", C.c_uint32), ("skip_ras", C.c_uint32), ("deferred_taps", C.c_uint32), ("hoisted_ras", C.c_uint32),
                 ("h_d_weights", C.POINTER(C.c_void_p))]
 
 
@@ -238,9 +238,9 @@ class HEContext:
         self._ck(self._lib.he_ws_query_rotate_batch(self._h, level, n_ct, n_steps, 1 if hoisted else 0, C.byref(v)))
         return v.value
 
-    def he_ws_query_conv2d(self, C_a, H, W, R, f, level, n_out, deferred_taps=False):
+    def he_ws_query_conv2d(self, C_a, H, W, R, f, level, n_out, deferred_taps=False, hoisted_ras=False):
         v = C.c_uint64()
-        plan = ConvPlan(C_a, H, W, R, f, n_out, level, 0, 1 if deferred_taps else 0, None)
+        plan = ConvPlan(C_a, H, W, R, f, n_out, level, 0, 1 if deferred_taps else 0, 1 if hoisted_ras else 0, None)
         self._ck(self._lib.he_ws_query_conv2d(self._h, C.byref(plan), C.byref(v)))
         return v.value
 
@@ -386,7 +386,7 @@ class HEContext:
         self._ck(self._lib.he_ras(self._h, ca, len(cts), level, sa, len(steps), oa))
         return outs
 
-    def he_conv2d(self, C_a, H, W, R, f, level, weights, ct_in, outs, skip_ras=False, deferred_taps=False):
+    def he_conv2d(self, C_a, H, W, R, f, level, weights, ct_in, outs, skip_ras=False, deferred_taps=False, hoisted_ras=False):
         """weights: list of n_out*f*f device tensors [level+1][N] ([level+1+np][N], over the raised basis, with
         deferred_taps); outs: n_out tensors [2][level][N]."""
         n_out = len(outs)
@@ -399,7 +399,8 @@ class HEContext:
             _need(o, 2 * level * self.N, "output")
         wa = (C.c_void_p * len(weights))(*[_dev(w).value for w in weights])
         oa = (C.c_void_p * n_out)(*[_dev(o).value for o in outs])
-        plan = ConvPlan(C_a, H, W, R, f, n_out, level, 1 if skip_ras else 0, 1 if deferred_taps else 0, C.cast(wa, C.POINTER(C.c_void_p)))
+        plan = ConvPlan(C_a, H, W, R, f, n_out, level, 1 if skip_ras else 0, 1 if deferred_taps else 0, 1 if hoisted_ras else 0,
+                        C.cast(wa, C.POINTER(C.c_void_p)))
         self._ck(self._lib.he_conv2d(self._h, C.byref(plan), _dev(ct_in), oa))
         return outs
 

@@ -109,14 +109,22 @@ static size_t conv2d_deferred_elems(const he_ctx* ctx, uint32_t level, uint32_t 
     return ks_raised_products_ws_elems(ctx, level) + (size_t)n_rot * 2 * R * N + nb * 2 * R * N + ks_moddown_stored_ws_elems(ctx, level, (uint32_t)nb) +
            (size_t)n_rot * L1 * N + nb * 2 * L1 * N;
 }
-static size_t conv2d_ws_elems(const he_ctx* ctx, uint32_t level, uint32_t n_rot, uint32_t n_out, bool deferred_taps = false) {
+static size_t conv2d_ws_elems(const he_ctx* ctx, uint32_t level, uint32_t n_rot, uint32_t n_out, bool deferred_taps = false,
+                              uint32_t hoisted_ras_terms = 0) {
     const size_t N = ctx->N, ct_e = (size_t)2 * (level + 1) * N, ct_lo_e = (size_t)2 * level * N;
+    // scratch of the rotate-and-sum stage: the engine's (one step at a time) or the hoisted sum's
+    const size_t ras_e = hoisted_ras_terms ? ks_hoisted_sum_ws_elems(ctx, level - 1, n_out, hoisted_ras_terms)
+                                           : ks_engine_ws_elems(ctx, level - 1, n_out, n_out);
     if (deferred_taps && n_rot) {
-        const size_t head = std::max(conv2d_deferred_elems(ctx, level, n_rot, n_out), ks_engine_ws_elems(ctx, level - 1, n_out, n_out));
+        const size_t head = std::max(conv2d_deferred_elems(ctx, level, n_rot, n_out), ras_e);
         return head + rescale_ws_elems(ctx, level, n_out) + (size_t)n_out * ct_e + (size_t)n_out * ct_lo_e;
     }
-    const size_t ks_e = std::max(n_rot ? ks_engine_ws_elems(ctx, level, 1, n_rot) : 0, ks_engine_ws_elems(ctx, level - 1, n_out, n_out));
+    const size_t ks_e = std::max(n_rot ? ks_engine_ws_elems(ctx, level, 1, n_rot) : 0, ras_e);
     return ks_e + rescale_ws_elems(ctx, level, n_out) + (size_t)(n_rot + n_out) * ct_e + (size_t)n_out * ct_lo_e;
+}
+// terms of the hoisted rotate-and-sum of a plan (0: the log2 C_a dependent steps are used)
+static uint32_t hoisted_ras_terms(const he_conv_plan* plan) {
+    return (plan->hoisted_ras && !plan->skip_ras && plan->C_a > 1) ? plan->C_a - 1 : 0;
 }
 
 extern "C" int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* plan, uint64_t* h_bytes) {
@@ -126,7 +134,7 @@ extern "C" int32_t he_ws_query_conv2d(const he_ctx* ctx, const he_conv_plan* pla
     if ((plan->f & 1u) == 0 || plan->f * plan->f > CV_MAX_TAPS || plan->n_out == 0) return HE_ERR_BADARG;
     uint32_t n_rot = 0;
     for (uint32_t st : tap_slot_steps(plan->W, plan->R, plan->f, ctx->N / 2)) n_rot += st != 0;
-    *h_bytes = conv2d_ws_elems(ctx, plan->level, n_rot, plan->n_out, plan->deferred_taps != 0) * sizeof(u64);
+    *h_bytes = conv2d_ws_elems(ctx, plan->level, n_rot, plan->n_out, plan->deferred_taps != 0, hoisted_ras_terms(plan)) * sizeof(u64);
     return HE_OK;
     });
 }
@@ -158,7 +166,9 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
             tap_key[t] = it->second;
         }
     }
-    for (uint32_t s = 1; s < plan->C_a && !plan->skip_ras; s <<= 1) {
+    const uint32_t ras_T = hoisted_ras_terms(plan);
+    if (ras_T > HE_MAX_SUM_TERMS - 1) return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: hoisted_ras supports C_a up to %d", HE_MAX_SUM_TERMS);
+    for (uint32_t s = 1; s < plan->C_a && !plan->skip_ras; s = ras_T ? s + 1 : s << 1) {
         uint32_t step = plan->H * plan->W * plan->R * s;
         uint32_t g = h_galois_of_step(ctx, (int32_t)step);
         auto it = ctx->evk.find(g);
@@ -178,7 +188,7 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
     const bool deferred_taps = plan->deferred_taps != 0 && n_rot > 0;
     if (deferred_taps && n_rot + 1 != taps)
         return he_fail(ctx, HE_ERR_BADARG, "he_conv2d: deferred_taps needs exactly one tap that does not rotate (%u of %u do)", taps - n_rot, taps);
-    const size_t total = conv2d_ws_elems(ctx, level, n_rot, n_out, deferred_taps);
+    const size_t total = conv2d_ws_elems(ctx, level, n_rot, n_out, deferred_taps, ras_T);
     int32_t rc = he_ensure_ws(ctx, total * sizeof(u64));
     if (rc != HE_OK) return rc;
     // laid out from the end of the region: [engine ...][rescale scratch][rotated inputs][accumulators][temporaries]
@@ -289,8 +299,9 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
     for (uint32_t o = 0; o < n_out; o++) {
         u64* a = (u64*)h_d_ct_out[o];
         u64* b = tmp + (size_t)o * ct_lo_e;
-        cur[o] = (n_ras & 1u) ? b : a;
-        nxt[o] = (n_ras & 1u) ? a : b;
+        const uint32_t n_pp = ras_T ? 1u : n_ras;          // buffer swaps until the result must sit in the output
+        cur[o] = (n_pp & 1u) ? b : a;
+        nxt[o] = (n_pp & 1u) ? a : b;
     }
     {
         dim3 grid(N / CV_THREADS, L1), block(CV_THREADS);
@@ -324,6 +335,19 @@ extern "C" int32_t he_conv2d(he_ctx* ctx, const he_conv_plan* plan, const uint64
         for (uint32_t o = 0; o < n_out; o++) accs[o] = acc + (size_t)o * ct_e;
         rc = rescale_batch(ctx, accs.data(), cur.data(), n_out, level, rs_ws);
         if (rc != HE_OK) return rc;
+    }
+    if (ras_T) {
+        // rotate-and-sum as the sum of the C_a - 1 rotations of each rescaled output, sharing one ModUp and one
+        // ModDown per output and the keys between the outputs
+        std::vector<KsSrc> srcs(n_out);
+        std::vector<u64*> o0(n_out), o1(n_out);
+        for (uint32_t o = 0; o < n_out; o++) {
+            srcs[o] = {cur[o], cur[o] + (size_t)level * N, cur[o], cur[o] + (size_t)level * N};
+            o0[o] = nxt[o]; o1[o] = nxt[o] + (size_t)level * N;
+        }
+        rc = ks_hoisted_sum(ctx, lo, srcs.data(), n_out, ras_g.data(), ras_key.data(), ras_T, o0.data(), o1.data(), ctx->d_ws);
+        if (rc != HE_OK) return rc;
+        return HE_OK;
     }
     // rotate-and-sum over the outermost channel dimension: every step is one batch over all
     // outputs (same key), the addition ct + Rot(ct) is done by the ModDown epilogue

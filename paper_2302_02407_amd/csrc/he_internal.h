@@ -148,6 +148,9 @@ struct ModDownEpilogue {
     // (polynomial, Galois element, key) terms, a sum of rotations brought down by one ModDown; raised/own/evk/g
     // are then indexed by term, c0[0] must be null (the rotated c0 parts arrive summed through self0[0]).
     uint32_t n_terms;
+    // hoisted != 0 (with n_terms > 0): several outputs per launch again, every output the sum of the SAME n_terms
+    // (Galois element, key) terms applied to its own polynomial: raised/own are indexed by job, evk/g by term.
+    uint32_t hoisted;
     const u64* raised[HE_MAX_KS_JOBS];  // [beta][R][N]
     const u64* own[HE_MAX_KS_JOBS];     // [L1][N]
     const u64* evk[HE_MAX_KS_JOBS];     // [dnum][2][M][N]
@@ -162,6 +165,7 @@ struct IpPrologue {
     uint32_t g[HE_MAX_KS_JOBS];
     uint32_t beta, R, M, L1, k, nq;
     uint32_t n_terms;                   // as in ModDownEpilogue: > 0 = one output, arrays indexed by term
+    uint32_t hoisted;                   // as in ModDownEpilogue: raised indexed by job, evk/g by term
 };
 
 // One batched transform launch (both passes).  Limb i is read at seg[src_seg[i]] + src_limb[i]*N
@@ -257,6 +261,11 @@ struct KsSumTerm {
 };
 size_t ks_rotate_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t n_rot);
 int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms, uint32_t n_terms, u64* out0, u64* out1, u64* ws);
+// sum over T shared (Galois element, key) terms of the rotations of each of J ciphertexts, one ModUp and one ModDown per
+// ciphertext; srcs[j] = {c0_j, c1_j, addend0_j or null, addend1_j or null} (keyswitch.hip)
+size_t ks_hoisted_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t J, uint32_t T);
+int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J, const uint32_t* gs, const u64* const* evks, uint32_t T,
+                       u64* const* out0, u64* const* out1, u64* ws);
 // Hoisted inner products kept over the raised basis, and the ModDown of stored accumulators (keyswitch.hip)
 size_t ks_raised_products_ws_elems(const he_ctx* c, uint32_t level);
 int32_t ks_raised_products(he_ctx* c, uint32_t level, const u64* c1, const uint32_t* gs, const u64* const* evks, uint32_t n, u64* acc, u64* ws);

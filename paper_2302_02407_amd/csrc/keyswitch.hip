@@ -799,11 +799,18 @@ int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms
     u64* tmp_dn = s1 + (size_t)L1 * N;
     u64* conv = tmp_dn + (size_t)2 * k * N;
     u64* acc = conv + (size_t)2 * L1 * N;               // stored accumulators: [0] the sum, [1..] one group of terms
-    // ModUp of every rotated term's c1
-    std::vector<KsSrc> srcs(n_rot);
-    for (uint32_t t = 0; t < n_rot; t++) srcs[t] = {rot[t]->c0, rot[t]->c1, nullptr, nullptr};
-    for (uint32_t t0 = 0; t0 < n_rot; t0 += cb) {
-        int32_t rc = modup_batch(c, srcs.data() + t0, std::min(cb, n_rot - t0), level, raised + (size_t)t0 * beta * R * N, tmp_up);
+    // ModUp of every rotated term's c1; terms that rotate the same polynomial share its raised digits (hoisting)
+    std::vector<KsSrc> srcs;
+    std::vector<uint32_t> src_of(n_rot);
+    for (uint32_t t = 0; t < n_rot; t++) {
+        uint32_t u = 0;
+        while (u < srcs.size() && srcs[u].c1 != rot[t]->c1) u++;
+        if (u == srcs.size()) srcs.push_back({rot[t]->c0, rot[t]->c1, nullptr, nullptr});
+        src_of[t] = u;
+    }
+    const uint32_t n_src = (uint32_t)srcs.size();
+    for (uint32_t t0 = 0; t0 < n_src; t0 += cb) {
+        int32_t rc = modup_batch(c, srcs.data() + t0, std::min(cb, n_src - t0), level, raised + (size_t)t0 * beta * R * N, tmp_up);
         if (rc != HE_OK) return rc;
     }
     // the rotated c0 parts and the plain terms, summed
@@ -820,7 +827,7 @@ int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms
         ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq; ip.n_terms = n_rot;
         ep.n_terms = n_rot;
         for (uint32_t t = 0; t < n_rot; t++) {
-            ip.raised[t] = ep.raised[t] = raised + (size_t)t * beta * R * N;
+            ip.raised[t] = ep.raised[t] = raised + (size_t)src_of[t] * beta * R * N;
             ip.evk[t] = ep.evk[t] = rot[t]->evk;
             ip.g[t] = ep.g[t] = rot[t]->g;
             ep.own[t] = rot[t]->c1;
@@ -831,7 +838,7 @@ int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms
             const uint32_t cnt = std::min<uint32_t>(HE_MAX_KS_JOBS, n_rot - t0);
             IpBatch ib;
             for (uint32_t i = 0; i < cnt; i++) {
-                ib.raised[i] = raised + (size_t)(t0 + i) * beta * R * N;
+                ib.raised[i] = raised + (size_t)src_of[t0 + i] * beta * R * N;
                 ib.own[i] = rot[t0 + i]->c1;
                 ib.evk[i] = rot[t0 + i]->evk; ib.g[i] = rot[t0 + i]->g; ib.start[i] = i; ib.count[i] = 1;
             }
@@ -846,6 +853,106 @@ int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms
     int32_t rc = moddown_chain(c, level, 1, acc, tmp_dn, conv, fused ? &ip : nullptr, ep);
     if (rc != HE_OK) return rc;
     c->cnt.keyswitch += n_rot;
+    return HE_OK;
+}
+
+// ---------------------------------------------------------------- the same sum of rotations of several ciphertexts
+// out_j = ct_j' + sum_{t<T} Rot(ct_j; g_t) for j < J with ONE ModUp and ONE ModDown per ciphertext (rotate-and-sum over
+// C_a, Section 2.2, evaluated as the sum of its C_a - 1 rotations of the input instead of log2 C_a dependent steps):
+//   A_j   = sum_t sum_i sigma_{g_t}(ModUp(c1_j)_i) * evk_t,i
+//   out_j = ( sum_t sigma_{g_t}(c0_j) + ModDown(A_j,0) + s0_j , ModDown(A_j,1) + s1_j )     (s0_j, s1_j: addends or null)
+// The T keys are shared by all J ciphertexts; at N = 2^16 the inner products run inside the ModDown transforms with
+// several ciphertexts per launch, elsewhere one ciphertext at a time through ks_rotate_sum_deferred.
+
+// grid (N/256, L1, J): s0_j[r][n] = sum_t c0_j[r][sigma_t-source of n] (+ add_j[r][n])
+struct HoistC0 {
+    const u64* c0[HE_MAX_KS_JOBS];
+    const u64* add[HE_MAX_KS_JOBS];
+    u64* s0[HE_MAX_KS_JOBS];
+    uint32_t g[HE_MAX_KS_JOBS];
+    uint32_t T;
+};
+__global__ __launch_bounds__(KS_THREADS) void hoist_c0_sum_kernel(HoistC0 a, const ModConst* mc, uint32_t logN) {
+    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y, j = blockIdx.z;
+    const u64 q = mc[r].q;
+    const size_t o = ((size_t)r << logN) + n;
+    const u64* c0 = a.c0[j] + ((size_t)r << logN);
+    u64 v = a.add[j] ? a.add[j][o] : 0;
+    for (uint32_t t = 0; t < a.T; t++) v = addmod(v, c0[galois_src_ks(n, a.g[t], logN)], q);
+    a.s0[j][o] = v;
+}
+
+static bool hoisted_sum_fused(const he_ctx* c, uint32_t level, uint32_t T) {
+    return c->logN == 16 && num_digits(c, level) <= 8 && T >= 1 && T <= HE_MAX_KS_JOBS;
+}
+
+size_t ks_hoisted_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t J, uint32_t T) {
+    const size_t L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
+    if (!hoisted_sum_fused(c, level, T)) return ks_rotate_sum_ws_elems(c, level, T);
+    uint32_t cb, jb;
+    engine_shape(c, level, J, J, cb, jb);
+    // raised [jb][beta][R] + tmp_up [cb][L1] + s0 [jb][L1] + tmp_dn [jb][2][k] + conv [jb][2][L1]
+    return ((size_t)jb * beta * R + (size_t)cb * L1 + (size_t)jb * L1 + (size_t)jb * 2 * k + (size_t)jb * 2 * L1) * c->N;
+}
+
+int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J, const uint32_t* gs, const u64* const* evks, uint32_t T,
+                       u64* const* out0, u64* const* out1, u64* ws) {
+    const uint32_t N = c->N, L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
+    if (T == 0 || T > HE_MAX_SUM_TERMS - 1) return he_fail(c, HE_ERR_BADARG, "hoisted rotation sum: between 1 and %d terms", HE_MAX_SUM_TERMS - 1);
+    for (uint32_t t = 0; t < T; t++)
+        if (gs[t] == 1 || !evks[t]) return he_fail(c, HE_ERR_BADARG, "hoisted rotation sum: term %u does not rotate or has no key", t);
+    if (!hoisted_sum_fused(c, level, T)) {
+        std::vector<KsSumTerm> terms(T + 1);
+        for (uint32_t j = 0; j < J; j++) {
+            for (uint32_t t = 0; t < T; t++) terms[t] = {srcs[j].c0, srcs[j].c1, gs[t], evks[t]};
+            uint32_t n = T;
+            if (srcs[j].s0) terms[n++] = {srcs[j].s0, srcs[j].s1, 1u, nullptr};
+            int32_t rc = ks_rotate_sum_deferred(c, level, terms.data(), n, out0[j], out1[j], ws);
+            if (rc != HE_OK) return rc;
+        }
+        return HE_OK;
+    }
+    if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
+    uint32_t cb, jb;
+    engine_shape(c, level, J, J, cb, jb);
+    u64* raised = ws;
+    u64* tmp_up = raised + (size_t)jb * beta * R * N;
+    u64* s0 = tmp_up + (size_t)cb * L1 * N;
+    u64* tmp_dn = s0 + (size_t)jb * L1 * N;
+    u64* conv = tmp_dn + (size_t)jb * 2 * k * N;
+    for (uint32_t j0 = 0; j0 < J; j0 += jb) {
+        const uint32_t nb = std::min(jb, J - j0);
+        for (uint32_t t0 = 0; t0 < nb; t0 += cb) {
+            int32_t rc = modup_batch(c, srcs + j0 + t0, std::min(cb, nb - t0), level, raised + (size_t)t0 * beta * R * N, tmp_up);
+            if (rc != HE_OK) return rc;
+        }
+        HoistC0 hc = {};
+        hc.T = T;
+        for (uint32_t t = 0; t < T; t++) hc.g[t] = gs[t];
+        for (uint32_t j = 0; j < nb; j++) { hc.c0[j] = srcs[j0 + j].c0; hc.add[j] = srcs[j0 + j].s0; hc.s0[j] = s0 + (size_t)j * L1 * N; }
+        hipLaunchKernelGGL(hoist_c0_sum_kernel, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
+        HE_HIP(c, hipGetLastError());
+        c->cnt.automorph += (uint64_t)nb * T * L1;
+        IpPrologue ip = {};
+        ModDownEpilogue ep = {};
+        ep.acc = nullptr; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
+        ep.fused = 1; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M; ep.n_terms = T; ep.hoisted = 1;
+        ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq; ip.n_terms = T; ip.hoisted = 1;
+        for (uint32_t t = 0; t < T; t++) { ip.evk[t] = ep.evk[t] = evks[t]; ip.g[t] = ep.g[t] = gs[t]; }
+        for (uint32_t j = 0; j < nb; j++) {
+            ip.raised[j] = ep.raised[j] = raised + (size_t)j * beta * R * N;
+            ep.own[j] = srcs[j0 + j].c1;
+            ep.c0[j] = nullptr;
+            ep.self0[j] = s0 + (size_t)j * L1 * N;
+            ep.self1[j] = srcs[j0 + j].s1;
+            ep.out0[j] = out0[j0 + j]; ep.out1[j] = out1[j0 + j];
+        }
+        if (c->prof_on) c->prof_key_limbs += (uint64_t)T * 2 * beta * R;
+        // no accumulator is stored: the transforms compute it; the pointer only has to be a valid address
+        int32_t rc = moddown_chain(c, level, nb, raised, tmp_dn, conv, &ip, ep);
+        if (rc != HE_OK) return rc;
+        c->cnt.keyswitch += (uint64_t)nb * T;
+    }
     return HE_OK;
 }
 

@@ -151,3 +151,33 @@ def test_single_tap_is_the_plain_product():
     out = CV.slide_mac_deferred(orc, geo, ct, level, pts, {})[0]
     want = orc.ptct_mac(None, ct, np.ascontiguousarray(pts[0, 0, :level + 1]), level, init=True)
     assert (out == want).all()
+
+
+def test_hoisted_rotate_and_sum_is_the_same_sum():
+    """RaS over C_a as one hoisted sum of its C_a - 1 rotations (one ModUp, one ModDown per output): decrypts to the
+    float64 convolution, leaves the sum in every channel block, agrees with the stepwise form far below the
+    tolerance and is not the same bits.  (The sum of rotations with one ModDown is pinned in exact integers by the
+    tests of rotate_sum_deferred; that the hoisted form feeds it the right rotations is what this test fixes: a
+    missing or repeated multiple of H*W*R breaks the replication across blocks.)"""
+    prm = toy_params(logN=8, q_bits=40, nq=3, p_bits=41, np_=1, dnum=3, scale=2.0 ** 30, hamming=16, seed=56)
+    rng = S.make_rng(56)
+    o = Oracle.from_params(prm)
+    cl = K.Client(o, S.ternary_secret(rng, prm.N, prm.hamming))
+    level = 2
+    geo = CV.ConvGeometry(prm.N, 8, 2, 2, 4)                    # C_a = 8: 7 rotations instead of 3 steps
+    x, wt = S.conv_tensors(rng, 8, 4, 2, 2, 3, 0.2)
+    base = geo.H * geo.W * geo.R
+    steps = sorted(set(s for s in geo.tap_steps if s) | set(base * i for i in range(1, geo.C_a)))
+    evks = _keys(o, cl, prm, rng, steps)
+    ct = cl.encrypt(geo.pack_input(x).astype(np.complex128), prm.scale, level,
+                    S.uniform_limbs(rng, prm.q[:level + 1], prm.N)[0], S.gaussian_error(rng, prm.N, prm.sigma)[0])
+    pts = CV.encode_weights(o, geo, wt, level, float(prm.q[level]))
+    a = CV.caconv(o, geo, ct, level, pts, evks, hoisted_ras=True)
+    b = CV.caconv(o, geo, ct, level, pts, evks)
+    da = [cl.decrypt(c, level - 1, prm.scale) for c in a]
+    db = [cl.decrypt(c, level - 1, prm.scale) for c in b]
+    got, spread = geo.unpack_output(da)
+    assert np.max(np.abs(got - CV.conv2d_float(x, wt))) < 1e-3 and spread < 1e-3
+    assert max(np.max(np.abs(np.asarray(u) - np.asarray(v))) for u, v in zip(da, db)) < 1e-3
+    assert any((u != v).any() for u, v in zip(a, b))
+
