@@ -76,14 +76,20 @@ def run_only(args, torch, ctx, prm, gen):
                         | {2048, 4096, 8192, 16384}):
             held.append(uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2)))
             ctx.he_evk_register(ctx.galois_elt(s), held[-1])
-        if args.only == "conv5":                         # the same layer on a 6-limb ciphertext
+        hoisted_ras = args.only in ("convh", "conv5h")    # rotate-and-sum as one hoisted sum per output
+        if hoisted_ras:
+            for i in range(1, 16):
+                if 2048 * i not in (2048, 4096, 8192, 16384):
+                    held.append(uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2)))
+                    ctx.he_evk_register(ctx.galois_elt(2048 * i), held[-1])
+        if args.only in ("conv5", "conv5h"):             # the same layer on a 6-limb ciphertext
             level = 5
         ct = uniform_dev(torch, gen, prm.q[:level + 1], N, lead=(2,))
         weights = [uniform_dev(torch, gen, prm.q[:level + 1], N) for _ in range(8 * 9)]
         outs = [torch.empty((2, level, N), dtype=torch.uint64, device="cuda") for _ in range(8)]
 
         def fn():
-            ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, ct, outs)
+            ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, ct, outs, hoisted_ras=hoisted_ras)
         if args.only == "raconv":                        # reordered RAConv on 8 inputs, one ModDown per output
             lv = level - 1
             ins = [uniform_dev(torch, gen, prm.q[:lv + 1], N, lead=(2,)) for _ in range(8)]
@@ -112,7 +118,7 @@ def main():
     ap.add_argument("--batch", type=int, default=64, help="ciphertexts per step (configs[2] names 64)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the NTT and conv2d extra measurements")
-    ap.add_argument("--only", choices=["ntt", "conv2d", "conv0", "crot5", "conv5", "raconv"], help="run just this extra workload --steps times (for profiling "
+    ap.add_argument("--only", choices=["ntt", "conv2d", "conv0", "crot5", "conv5", "raconv", "convh", "conv5h"], help="run just this extra workload --steps times (for profiling "
                     "it in isolation) and print its own small JSON line instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -415,6 +421,11 @@ def main():
             ms_unit = timed(lambda: ctx.he_ca_ra_block(16, 32, 32, 2, 3, level, 8192, weights, ra_w2, [cts[0]], blk_out,
                                                        group=grp, deferred=True), reps=3)
             extras[name] = round(ms_unit, 3)
+        # all intermediates batched, rotate-and-sum over C_a as one hoisted sum per intermediate
+        ctx.he_ws_reserve(ctx.he_ws_query_ca_ra_block(16, 32, 32, 2, 3, 1, 8, level, 0, True, True))
+        extras["ca_square_ra_hoisted_ras_ms"] = round(
+            timed(lambda: ctx.he_ca_ra_block(16, 32, 32, 2, 3, level, 8192, weights, ra_w2, [cts[0]], blk_out, group=0, deferred=True,
+                                             hoisted_ras=True), reps=3), 3)
         del blk_out
         conv_weights_h = weights if not args.no_cpu else None
         del weights, conv_out, ra_w, ra_out, ra_w2

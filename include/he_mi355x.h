@@ -337,6 +337,8 @@ typedef struct {
     uint32_t level;
     uint32_t group;
     uint32_t deferred_moddown;   /* Slide_1&Sum_f with one ModDown per output (see he_rotate_sum) */
+    uint32_t hoisted_ras;        /* rotate-and-sum over C_a as one hoisted sum per intermediate (see he_conv_plan); needs
+                                    the keys of i*H*W*R for every i < C_a */
     const uint64_t* h_k_in;      /* `level` canonical residues: k_in mod q_0 .. q_(level-1) */
     const uint64_t* const* h_d_w_ca;
     const uint64_t* const* h_d_w_ra;

@@ -148,7 +148,7 @@ def gap_sum_replicate(orc, ct, level, R, mask, evks):
 # intermediate j holds channel (j*R + r) mod c_mid in replica r of every block; output ciphertext l holds output
 # channels l*C_a .. (l+1)*C_a - 1.  p_ca[j][k] are the f^2 filter plaintexts of (intermediate j, input k) at
 # `level`; p_ra[l][j] the f^2 inversely rotated plaintexts of (output l, intermediate j) at level-2.
-def ca_ra_block(orc, g_ca, g_ra, cts_in, level, p_ca, p_ra, evks, rlk, k_in, deferred=False, keep=False):
+def ca_ra_block(orc, g_ca, g_ra, cts_in, level, p_ca, p_ra, evks, rlk, k_in, deferred=False, keep=False, hoisted_ras=False):
     n_ca, n_ra, taps = len(cts_in), g_ca.n_out, len(g_ca.taps)
     assert g_ra.n_in == n_ra and len(p_ca) == n_ra and len(p_ra) == n_ca
     lv = level - 1
@@ -165,8 +165,11 @@ def ca_ra_block(orc, g_ca, g_ra, cts_in, level, p_ca, p_ra, evks, rlk, k_in, def
             for t in range(taps):
                 acc = orc.ptct_mac(acc, ct1[k][t], p_ca[j][k][t], level, init=acc is None)
         cur = orc.rescale(acc, level)
-        for st in g_ca.ras_steps:                                         # RaS over C_a
-            cur = orc.add(cur, orc.rotate(cur, lv, orc.galois_elt(st), evks[st]), lv)
+        if hoisted_ras and g_ca.C_a > 1:                                  # RaS over C_a as one hoisted sum of rotations
+            cur = CV.ras_hoisted(orc, g_ca, cur, lv, evks)
+        else:
+            for st in g_ca.ras_steps:                                     # RaS over C_a
+                cur = orc.add(cur, orc.rotate(cur, lv, orc.galois_elt(st), evks[st]), lv)
         u = orc.affine(cur, lv, [k_in] * (lv + 1), [0] * (lv + 1))
         sq = orc.rescale(orc.mulct(u, u, lv, rlk), lv)                    # Square
         squares.append(sq)

@@ -59,7 +59,7 @@ class RaConvPlan(C.Structure):
 class BlockPlan(C.Structure):
     _fields_ = [("C_a", C.c_uint32), ("H", C.c_uint32), ("W", C.c_uint32), ("R", C.c_uint32), ("f", C.c_uint32),
                 ("n_ca", C.c_uint32), ("n_ra", C.c_uint32), ("level", C.c_uint32), ("group", C.c_uint32),
-                ("deferred_moddown", C.c_uint32), ("h_k_in", C.POINTER(C.c_uint64)),
+                ("deferred_moddown", C.c_uint32), ("hoisted_ras", C.c_uint32), ("h_k_in", C.POINTER(C.c_uint64)),
                 ("h_d_w_ca", C.POINTER(C.c_void_p)), ("h_d_w_ra", C.POINTER(C.c_void_p))]
 
 
@@ -443,21 +443,21 @@ class HEContext:
         self._ck(self._lib.he_raconv(self._h, C.byref(plan), ia, _dev(out)))
         return out
 
-    def _block_plan(self, C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, k_in, w_ca, w_ra):
+    def _block_plan(self, C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, k_in, w_ca, w_ra, hoisted_ras=False):
         ka = (C.c_uint64 * level)(*[int(k_in) % self.q[r] for r in range(level)])
         ca = (C.c_void_p * max(1, len(w_ca)))(*[_dev(w).value for w in w_ca])
         ra = (C.c_void_p * max(1, len(w_ra)))(*[_dev(w).value for w in w_ra])
-        plan = BlockPlan(C_a, H, W, R, f, n_ca, n_ra, level, group, 1 if deferred else 0, ka,
+        plan = BlockPlan(C_a, H, W, R, f, n_ca, n_ra, level, group, 1 if deferred else 0, 1 if hoisted_ras else 0, ka,
                          C.cast(ca, C.POINTER(C.c_void_p)), C.cast(ra, C.POINTER(C.c_void_p)))
         return plan, (ka, ca, ra)
 
-    def he_ws_query_ca_ra_block(self, C_a, H, W, R, f, n_ca, n_ra, level, group=0, deferred=False):
+    def he_ws_query_ca_ra_block(self, C_a, H, W, R, f, n_ca, n_ra, level, group=0, deferred=False, hoisted_ras=False):
         v = C.c_uint64()
-        plan, _keep = self._block_plan(C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, 1, [], [])
+        plan, _keep = self._block_plan(C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, 1, [], [], hoisted_ras)
         self._ck(self._lib.he_ws_query_ca_ra_block(self._h, C.byref(plan), C.byref(v)))
         return v.value
 
-    def he_ca_ra_block(self, C_a, H, W, R, f, level, k_in, w_ca, w_ra, cts_in, outs, group=0, deferred=False):
+    def he_ca_ra_block(self, C_a, H, W, R, f, level, k_in, w_ca, w_ra, cts_in, outs, group=0, deferred=False, hoisted_ras=False):
         """Fused CAConv -> Square -> RAConv block.  w_ca: n_ra*n_ca*f*f plaintexts at `level` ([j][k][tap]); w_ra:
         n_ca*n_ra*f*f inversely rotated plaintexts at level-2 ([l][j][tap]); cts_in / outs: n_ca tensors at `level` /
         level-3; k_in: the integer lift before the square (reduced per limb here)."""
@@ -473,7 +473,7 @@ class HEContext:
             _need(w, (level + 1) * self.N, "CAConv weight plaintext")
         for w in w_ra:
             _need(w, (level - 1) * self.N, "RAConv weight plaintext")
-        plan, _keep = self._block_plan(C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, k_in, w_ca, w_ra)
+        plan, _keep = self._block_plan(C_a, H, W, R, f, n_ca, n_ra, level, group, deferred, k_in, w_ca, w_ra, hoisted_ras)
         ia = (C.c_void_p * n_ca)(*[_dev(c).value for c in cts_in])
         oa = (C.c_void_p * n_ca)(*[_dev(o).value for o in outs])
         self._ck(self._lib.he_ca_ra_block(self._h, C.byref(plan), ia, oa))

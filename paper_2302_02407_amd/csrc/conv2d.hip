@@ -613,7 +613,8 @@ static BlockShape block_shape(const he_ctx* ctx, const he_block_plan* p, uint32_
     b.G = (p->group == 0 || p->group > p->n_ra) ? p->n_ra : p->group;
     const size_t ct_hi = 2 * (size_t)(level + 1) * N, ct_mid = 2 * (size_t)level * N, ct_lo = 2 * (size_t)(level - 1) * N;
     b.eng_e = n_rot ? ks_engine_ws_elems(ctx, level, p->n_ca, p->n_ca * n_rot) : 0;
-    b.eng_e = std::max(b.eng_e, ks_engine_ws_elems(ctx, level - 1, b.G, b.G));
+    b.eng_e = std::max(b.eng_e, (p->hoisted_ras && p->C_a > 1) ? ks_hoisted_sum_ws_elems(ctx, level - 1, b.G, p->C_a - 1)
+                                                                : ks_engine_ws_elems(ctx, level - 1, b.G, b.G));
     b.eng_e = std::max(b.eng_e, slide1_sum_ws_elems(ctx, level - 2, n_rot, p->deferred_moddown != 0));
     b.rs_e = rescale_ws_elems(ctx, level, b.G);
     b.ct1_e = (size_t)p->n_ca * n_rot * ct_hi;
@@ -670,7 +671,9 @@ extern "C" int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const 
         tap_key[t] = it->second;
         n_rot++;
     }
-    for (uint32_t s = 1; s < plan->C_a; s <<= 1) {
+    const bool hoisted_ras = plan->hoisted_ras != 0 && plan->C_a > 1;
+    if (hoisted_ras && plan->C_a > HE_MAX_SUM_TERMS) return he_fail(ctx, HE_ERR_BADARG, "he_ca_ra_block: hoisted_ras supports C_a up to %d", HE_MAX_SUM_TERMS);
+    for (uint32_t s = 1; s < plan->C_a; s = hoisted_ras ? s + 1 : s << 1) {
         const uint32_t step = plan->H * plan->W * plan->R * s, g = h_galois_of_step(ctx, (int32_t)step);
         auto it = ctx->evk.find(g);
         if (it == ctx->evk.end()) return he_fail(ctx, HE_ERR_NOKEY, "he_ca_ra_block: no key for rotate-and-sum amount %u", step);
@@ -765,12 +768,25 @@ extern "C" int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const 
         for (uint32_t o = 0; o < g; o++) {
             accs[o] = acc + (size_t)o * ct_hi;
             u64 *a = pa + (size_t)o * ct_mid, *b = pb + (size_t)o * ct_mid;
-            cur[o] = (n_ras & 1u) ? b : a;
-            nxt[o] = (n_ras & 1u) ? a : b;
+            const uint32_t n_pp = hoisted_ras ? 1u : n_ras;
+            cur[o] = (n_pp & 1u) ? b : a;
+            nxt[o] = (n_pp & 1u) ? a : b;
         }
         rc = rescale_batch(ctx, accs.data(), cur.data(), g, level, rs_ws);
         if (rc != HE_OK) return rc;
-        for (uint32_t s = 0; s < n_ras; s++) {
+        if (hoisted_ras) {
+            // one hoisted sum of the C_a - 1 rotations per intermediate (one ModUp, one ModDown each)
+            std::vector<KsSrc> srcs(g);
+            std::vector<u64*> o0(g), o1(g);
+            for (uint32_t o = 0; o < g; o++) {
+                srcs[o] = {cur[o], cur[o] + pe_mid, cur[o], cur[o] + pe_mid};
+                o0[o] = nxt[o]; o1[o] = nxt[o] + pe_mid;
+            }
+            rc = ks_hoisted_sum(ctx, lv, srcs.data(), g, ras_g.data(), ras_key.data(), plan->C_a - 1, o0.data(), o1.data(), ctx->d_ws);
+            if (rc != HE_OK) return rc;
+            std::swap(cur, nxt);
+        }
+        for (uint32_t s = 0; s < n_ras && !hoisted_ras; s++) {
             std::vector<KsSrc> srcs(g);
             std::vector<KsJob> jobs(g);
             for (uint32_t o = 0; o < g; o++) {

@@ -882,17 +882,100 @@ __global__ __launch_bounds__(KS_THREADS) void hoist_c0_sum_kernel(HoistC0 a, con
     a.s0[j][o] = v;
 }
 
-static bool hoisted_sum_fused(const he_ctx* c, uint32_t level, uint32_t T) {
-    return c->logN == 16 && num_digits(c, level) <= 8 && T >= 1 && T <= HE_MAX_KS_JOBS;
+// Inner products of a hoisted sum for up to HS_JOBS ciphertexts at once, register-tiled: a thread owns one point of
+// one raised-basis limb for all the ciphertexts and both components; per (term, digit) it loads the two key values
+// once and one gathered digit value per ciphertext, and feeds 2*J multiply-accumulates.  Against one work group per
+// (ciphertext, component) that is J/(J+2)... the loads per product fall from 2 to (J+2)/(2J), which is what bounds
+// these sums (they are L2-bandwidth-bound: every term gathers other rows of the digits).
+// acc [J][2][R][N] (canonical); init = 0 continues from its contents (more than HS_TERMS terms).  grid (N/256, R).
+#define HS_JOBS 8
+#define HS_TERMS 16
+struct HoistIp {
+    const u64* raised[HS_JOBS];   // [beta][R][N], own limbs not materialised
+    const u64* own[HS_JOBS];      // the switched polynomial [L1][N]
+    const u64* evk[HS_TERMS];
+    uint32_t g[HS_TERMS];
+    uint32_t J, T;
+};
+__global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_kernel(HoistIp a, u64* __restrict__ acc, const ModConst* mc, uint32_t logN,
+                                                                    uint32_t R, uint32_t beta, uint32_t M, uint32_t level, uint32_t nq,
+                                                                    uint32_t alpha, uint32_t init) {
+    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y;
+    const uint32_t mi = r <= level ? r : nq + (r - level - 1);
+    const ModConst m = mc[mi];
+    const size_t ro = ((size_t)r << logN) + n, cstride = (size_t)R << logN;
+    u128 s0[HS_JOBS], s1[HS_JOBS];
+    u64 t0[HS_JOBS], t1[HS_JOBS];
+#pragma unroll
+    for (int i = 0; i < HS_JOBS; i++) {
+        s0[i] = s1[i] = 0;
+        t0[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i) * cstride + ro] : 0;
+        t1[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i + 1) * cstride + ro] : 0;
+    }
+    uint32_t pending = 0;
+    for (uint32_t t = 0; t < a.T; t++) {
+        const uint32_t g = a.g[t];
+        const uint32_t src = g == 1 ? n : galois_src_ks(n, g, logN);
+        const u64* evk = a.evk[t];
+        for (uint32_t j = 0; j < beta; j++) {
+            if (pending == 8) {          // eight products of (possibly unreduced) digits are what 128 bits hold
+#pragma unroll
+                for (int i = 0; i < HS_JOBS; i++) {
+                    t0[i] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
+                    t1[i] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
+                    s0[i] = s1[i] = 0;
+                }
+                pending = 0;
+            }
+            const u64 kb = evk[((size_t)((j * 2 + 0) * M + mi) << logN) + n];
+            const u64 ka = evk[((size_t)((j * 2 + 1) * M + mi) << logN) + n];
+            const bool own_digit = r <= level && r / alpha == j;
+            const size_t doff = own_digit ? ((size_t)r << logN) + src : ((size_t)(j * R + r) << logN) + src;
+#pragma unroll
+            for (int i = 0; i < HS_JOBS; i++) {
+                if ((uint32_t)i < a.J) {
+                    const u64 d = (own_digit ? a.own[i] : a.raised[i])[doff];
+                    s0[i] += (u128)d * kb;
+                    s1[i] += (u128)d * ka;
+                }
+            }
+            pending++;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < HS_JOBS; i++) {
+        if ((uint32_t)i < a.J) {
+            acc[(size_t)(2 * i) * cstride + ro] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
+            acc[(size_t)(2 * i + 1) * cstride + ro] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
+        }
+    }
+}
+
+// Which of the two forms the inner products of a hoisted sum over `nb` ciphertexts take.  The register-tiled kernel
+// reuses every key value nb times but gathers, for each term, other rows of all nb*beta digit limbs of the raised-basis
+// limb it works on: that set (nb*beta*N*8 bytes) has to stay in an XCD's 4 MiB L2, or the gathers stream from memory
+// (measured at N = 2^16: 8 ciphertexts x 1 digit 0.26 ms against 0.61 ms fused; 8 x 3 digits 1.96 ms against 1.44 ms).
+// Otherwise, at N = 2^16, the sums run inside the ModDown transforms, one work group per (ciphertext, component),
+// whose digits (beta*N*8 bytes) do stay in L2.
+static bool hoisted_sum_fused(const he_ctx* c, uint32_t level, uint32_t T, uint32_t nb) {
+    const uint32_t beta = num_digits(c, level);
+    return c->logN == 16 && beta <= 8 && T >= 1 && T <= HE_MAX_KS_JOBS && (size_t)nb * beta * c->N * sizeof(u64) > ((size_t)4 << 20);
+}
+
+static uint32_t hoisted_sum_jb(const he_ctx* c, uint32_t level, uint32_t J) {
+    uint32_t cb, jb;
+    engine_shape(c, level, J, J, cb, jb);
+    return std::min<uint32_t>(jb, HS_JOBS);
 }
 
 size_t ks_hoisted_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t J, uint32_t T) {
     const size_t L1 = level + 1, k = c->np, R = L1 + k, beta = num_digits(c, level);
-    if (!hoisted_sum_fused(c, level, T)) return ks_rotate_sum_ws_elems(c, level, T);
+    (void)T;
     uint32_t cb, jb;
     engine_shape(c, level, J, J, cb, jb);
-    // raised [jb][beta][R] + tmp_up [cb][L1] + s0 [jb][L1] + tmp_dn [jb][2][k] + conv [jb][2][L1]
-    return ((size_t)jb * beta * R + (size_t)cb * L1 + (size_t)jb * L1 + (size_t)jb * 2 * k + (size_t)jb * 2 * L1) * c->N;
+    jb = hoisted_sum_jb(c, level, J);
+    // raised [jb][beta][R] + tmp_up [cb][L1] + s0 [jb][L1] + acc [jb][2][R] + tmp_dn [jb][2][k] + conv [jb][2][L1]
+    return ((size_t)jb * beta * R + (size_t)cb * L1 + (size_t)jb * L1 + (size_t)jb * 2 * R + (size_t)jb * 2 * k + (size_t)jb * 2 * L1) * c->N;
 }
 
 int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J, const uint32_t* gs, const u64* const* evks, uint32_t T,
@@ -901,55 +984,66 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
     if (T == 0 || T > HE_MAX_SUM_TERMS - 1) return he_fail(c, HE_ERR_BADARG, "hoisted rotation sum: between 1 and %d terms", HE_MAX_SUM_TERMS - 1);
     for (uint32_t t = 0; t < T; t++)
         if (gs[t] == 1 || !evks[t]) return he_fail(c, HE_ERR_BADARG, "hoisted rotation sum: term %u does not rotate or has no key", t);
-    if (!hoisted_sum_fused(c, level, T)) {
-        std::vector<KsSumTerm> terms(T + 1);
-        for (uint32_t j = 0; j < J; j++) {
-            for (uint32_t t = 0; t < T; t++) terms[t] = {srcs[j].c0, srcs[j].c1, gs[t], evks[t]};
-            uint32_t n = T;
-            if (srcs[j].s0) terms[n++] = {srcs[j].s0, srcs[j].s1, 1u, nullptr};
-            int32_t rc = ks_rotate_sum_deferred(c, level, terms.data(), n, out0[j], out1[j], ws);
-            if (rc != HE_OK) return rc;
-        }
-        return HE_OK;
-    }
     if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
     uint32_t cb, jb;
     engine_shape(c, level, J, J, cb, jb);
+    jb = hoisted_sum_jb(c, level, J);
     u64* raised = ws;
     u64* tmp_up = raised + (size_t)jb * beta * R * N;
     u64* s0 = tmp_up + (size_t)cb * L1 * N;
-    u64* tmp_dn = s0 + (size_t)jb * L1 * N;
+    u64* acc = s0 + (size_t)jb * L1 * N;
+    u64* tmp_dn = acc + (size_t)jb * 2 * R * N;
     u64* conv = tmp_dn + (size_t)jb * 2 * k * N;
     for (uint32_t j0 = 0; j0 < J; j0 += jb) {
         const uint32_t nb = std::min(jb, J - j0);
+        const bool fused = hoisted_sum_fused(c, level, T, nb);
         for (uint32_t t0 = 0; t0 < nb; t0 += cb) {
             int32_t rc = modup_batch(c, srcs + j0 + t0, std::min(cb, nb - t0), level, raised + (size_t)t0 * beta * R * N, tmp_up);
             if (rc != HE_OK) return rc;
         }
         HoistC0 hc = {};
-        hc.T = T;
-        for (uint32_t t = 0; t < T; t++) hc.g[t] = gs[t];
-        for (uint32_t j = 0; j < nb; j++) { hc.c0[j] = srcs[j0 + j].c0; hc.add[j] = srcs[j0 + j].s0; hc.s0[j] = s0 + (size_t)j * L1 * N; }
-        hipLaunchKernelGGL(hoist_c0_sum_kernel, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
-        HE_HIP(c, hipGetLastError());
+        hc.T = std::min<uint32_t>(T, HE_MAX_KS_JOBS);
+        for (uint32_t j = 0; j < nb; j++) { hc.c0[j] = srcs[j0 + j].c0; hc.s0[j] = s0 + (size_t)j * L1 * N; }
+        for (uint32_t t0 = 0; t0 < T; t0 += HE_MAX_KS_JOBS) {                 // the rotated c0 parts, 16 terms per launch
+            hc.T = std::min<uint32_t>(HE_MAX_KS_JOBS, T - t0);
+            for (uint32_t t = 0; t < hc.T; t++) hc.g[t] = gs[t0 + t];
+            for (uint32_t j = 0; j < nb; j++) hc.add[j] = t0 == 0 ? srcs[j0 + j].s0 : hc.s0[j];
+            hipLaunchKernelGGL(hoist_c0_sum_kernel, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
+            HE_HIP(c, hipGetLastError());
+        }
         c->cnt.automorph += (uint64_t)nb * T * L1;
         IpPrologue ip = {};
         ModDownEpilogue ep = {};
-        ep.acc = nullptr; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
-        ep.fused = 1; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M; ep.n_terms = T; ep.hoisted = 1;
-        ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq; ip.n_terms = T; ip.hoisted = 1;
-        for (uint32_t t = 0; t < T; t++) { ip.evk[t] = ep.evk[t] = evks[t]; ip.g[t] = ep.g[t] = gs[t]; }
+        ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
+        ep.fused = fused ? 1u : 0u; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M;
         for (uint32_t j = 0; j < nb; j++) {
-            ip.raised[j] = ep.raised[j] = raised + (size_t)j * beta * R * N;
-            ep.own[j] = srcs[j0 + j].c1;
-            ep.c0[j] = nullptr;
+            ep.c0[j] = nullptr; ep.g[j] = 1;
             ep.self0[j] = s0 + (size_t)j * L1 * N;
             ep.self1[j] = srcs[j0 + j].s1;
             ep.out0[j] = out0[j0 + j]; ep.out1[j] = out1[j0 + j];
         }
+        if (fused) {
+            ep.n_terms = T; ep.hoisted = 1;
+            ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq; ip.n_terms = T; ip.hoisted = 1;
+            for (uint32_t t = 0; t < T; t++) { ip.evk[t] = ep.evk[t] = evks[t]; ip.g[t] = ep.g[t] = gs[t]; }
+            for (uint32_t j = 0; j < nb; j++) {
+                ip.raised[j] = ep.raised[j] = raised + (size_t)j * beta * R * N;
+                ep.own[j] = srcs[j0 + j].c1;
+            }
+        } else {
+            // the inner products of all the chunk's ciphertexts, register-tiled, into stored accumulators
+            for (uint32_t t0 = 0; t0 < T; t0 += HS_TERMS) {
+                HoistIp hi = {};
+                hi.J = nb; hi.T = std::min<uint32_t>(HS_TERMS, T - t0);
+                for (uint32_t t = 0; t < hi.T; t++) { hi.evk[t] = evks[t0 + t]; hi.g[t] = gs[t0 + t]; }
+                for (uint32_t j = 0; j < nb; j++) { hi.raised[j] = raised + (size_t)j * beta * R * N; hi.own[j] = srcs[j0 + j].c1; }
+                hipLaunchKernelGGL(hoisted_sum_ip_kernel, dim3(N / KS_THREADS, R), dim3(KS_THREADS), 0, c->stream, hi, acc, c->d_mc, c->logN, R,
+                                   beta, c->M, level, c->nq, c->alpha, t0 == 0 ? 1u : 0u);
+                HE_HIP(c, hipGetLastError());
+            }
+        }
         if (c->prof_on) c->prof_key_limbs += (uint64_t)T * 2 * beta * R;
-        // no accumulator is stored: the transforms compute it; the pointer only has to be a valid address
-        int32_t rc = moddown_chain(c, level, nb, raised, tmp_dn, conv, &ip, ep);
+        int32_t rc = moddown_chain(c, level, nb, acc, tmp_dn, conv, fused ? &ip : nullptr, ep);
         if (rc != HE_OK) return rc;
         c->cnt.keyswitch += (uint64_t)nb * T;
     }

@@ -285,13 +285,19 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
                 cv[k] = has_c0 ? c0[src[k]] : 0;
                 sv[k] = has_self ? self[e] : 0;
             }
+            // The products of all terms and digits go into one 128-bit sum per point, reduced whenever eight
+            // products are pending (the raised digits may be unreduced, below 69q: eight products stay below
+            // 2^(bits+63)).  Partial sums are reduced to [0, 5q) only (three-product quotient, no correction) and added
+            // up: at most 7 of them (16 terms of 3 digits), below 35q, and the P^-1 product below takes any 64-bit
+            // value; for the widest moduli they are kept canonical instead.
+            u128 sum[4] = {0, 0, 0, 0};
+            uint32_t pending = 0;
             for (uint32_t term = 0; term < n_terms; term++) {
                 const uint32_t idx = ep.n_terms ? term : job;          // key and Galois element
                 const uint32_t si = ep.hoisted ? job : idx;            // polynomial and its raised digits
                 const u64* own = ep.own[si] + ((size_t)r << 16);
                 const u64* raised = ep.raised[si] + ((size_t)r << 16);
                 const u64* key = ep.evk[idx] + ((size_t)(comp * ep.M + r) << 16) + (size_t)b * 256;
-                u128 sum[4];
                 if (term) {
                     const uint32_t gt = ep.g[idx];
 #pragma unroll
@@ -299,16 +305,22 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
                         const uint32_t e = t + 16 * (k0 + k);
                         src[k] = gt == 1 ? b * 256 + e : galois_src16(b * 256 + e, gt);
                     }
-                }
+                    if (pending + beta > 8) {
 #pragma unroll
-                for (int k = 0; k < 4; k++) sum[k] = 0;
+                        for (int k = 0; k < 4; k++) {
+                            tot[k] = WIDE ? addmod(tot[k], barrett128(sum[k], q, m.mu, m.bits), q) : tot[k] + barrett128_lazy(sum[k], q, m.mu, m.bits);
+                            sum[k] = 0;
+                        }
+                        pending = 0;
+                    }
+                }
                 if (beta == 3) ip_accumulate<3>(sum, raised, own, own_j, key + t + 16 * k0, dig_stride, key_stride, beta, src);
                 else ip_accumulate<4>(sum, raised, own, own_j, key + t + 16 * k0, dig_stride, key_stride, beta, src);
-                // each term's sum is reduced to [0, 5q) only (three-product quotient, no correction); up to 16 of
-                // them add up below 80q, and the P^-1 product below takes any 64-bit value
-#pragma unroll
-                for (int k = 0; k < 4; k++) tot[k] += barrett128_lazy(sum[k], q, m.mu, m.bits);
+                pending += beta;
             }
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                tot[k] = WIDE ? addmod(tot[k], barrett128(sum[k], q, m.mu, m.bits), q) : tot[k] + barrett128_lazy(sum[k], q, m.mu, m.bits);
 #pragma unroll
             for (int k = 0; k < 4; k++) {
                 const uint32_t e = t + 16 * (k0 + k);
@@ -396,30 +408,36 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
         } else
 #pragma unroll
         for (int k0 = 0; k0 < 16; k0 += 4) {
+            // all terms and digits into one 128-bit sum per point, reduced (to the canonical residue the transform
+            // expects) whenever eight products are pending
             u64 tot[4] = {0, 0, 0, 0};
+            u128 sum[4] = {0, 0, 0, 0};
+            uint32_t pending = 0;
             for (uint32_t term = 0; term < n_terms; term++) {
                 const uint32_t idx = ip.n_terms ? term : job;
                 const uint32_t g = ip.g[idx];
                 const u64* raised = ip.raised[ip.hoisted ? job : idx] + ((size_t)(ip.L1 + tp) << 16);
                 const u64* key = ip.evk[idx] + ((size_t)(comp * ip.M + ip.nq + tp) << 16) + (size_t)b * 256;
-                u128 sum[4];
                 uint32_t src[4];
 #pragma unroll
                 for (int k = 0; k < 4; k++) {
                     const uint32_t e = t + 16 * (k0 + k);
                     src[k] = g == 1 ? b * 256 + e : galois_src16(b * 256 + e, g);
-                    sum[k] = 0;
+                }
+                if (pending + beta > 8) {
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        tot[k] = addmod(tot[k], barrett128(sum[k], q, m.mu, m.bits), q);
+                        sum[k] = 0;
+                    }
+                    pending = 0;
                 }
                 if (beta == 3) ip_accumulate<3>(sum, raised, nullptr, 0xFFFFFFFFu, key + t + 16 * k0, dig_stride, key_stride, beta, src);
                 else ip_accumulate<4>(sum, raised, nullptr, 0xFFFFFFFFu, key + t + 16 * k0, dig_stride, key_stride, beta, src);
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const u64 a = barrett128(sum[k], q, m.mu, m.bits);
-                    tot[k] = term == 0 ? a : addmod(tot[k], a, q);
-                }
+                pending += beta;
             }
 #pragma unroll
-            for (int k = 0; k < 4; k++) s[t + 17 * (k0 + k)] = tot[k];
+            for (int k = 0; k < 4; k++) s[t + 17 * (k0 + k)] = addmod(tot[k], barrett128(sum[k], q, m.mu, m.bits), q);
         }
     }
     __syncthreads();

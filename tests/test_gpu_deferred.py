@@ -90,6 +90,13 @@ def test_rotate_sum_n65536(level, steps):
     _sum_case(config_params(3), 72 + level, level, steps)
 
 
+def test_rotate_sum_n65536_widest_primes():
+    """60-bit ciphertext primes: the partial sums of the fused inner products must stay canonical (twelve terms of
+    lazily reduced partial sums would not fit 64 bits)."""
+    prm = toy_params(logN=16, q_bits=60, nq=4, p_bits=59, np_=2, dnum=2, hamming=64, seed=73)
+    _sum_case(prm, 73, 3, [1, 2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 0])
+
+
 def test_rotate_sum_errors():
     from gpu_util import dev, zeros
     from paper_2302_02407_amd.binding import HEError

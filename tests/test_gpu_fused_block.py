@@ -15,12 +15,12 @@ def _say(msg):
     print(msg, file=sys.__stdout__, flush=True)
 
 
-def _case(prm, C_a, H, W, c_in, c_mid, level, std, seed, groups, deferred_modes=(False, True)):
+def _case(prm, C_a, H, W, c_in, c_mid, level, std, seed, groups, deferred_modes=(False, True), hoisted_ras=False):
     from gpu_util import dev, host, zeros
     from oracle import block as OB
     from test_oracle_fused_block import check_fused_output, fused_inputs
     from paper_2302_02407_amd.binding import HEContext
-    d = fused_inputs(prm, C_a, H, W, c_in, c_mid, level, std, seed)
+    d = fused_inputs(prm, C_a, H, W, c_in, c_mid, level, std, seed, all_ras_multiples=hoisted_ras)
     orc, g_ca, g_ra, n_ca = d["orc"], d["g_ca"], d["g_ra"], d["n_ca"]
     n_ra, N = g_ca.n_out, prm.N
     ctx = HEContext.from_params(prm)
@@ -30,16 +30,19 @@ def _case(prm, C_a, H, W, c_in, c_mid, level, std, seed, groups, deferred_modes=
     w_ca = [dev(d["p_ca"][j][k][t]) for j in range(n_ra) for k in range(n_ca) for t in range(9)]
     w_ra = [dev(d["p_ra"][l][j][t]) for l in range(n_ca) for j in range(n_ra) for t in range(9)]
     cts = [dev(c) for c in d["cts"]]
-    n_ras = len(g_ca.ras_steps)
+    n_ras = (C_a - 1) if hoisted_ras else len(g_ca.ras_steps)      # key switches of one rotate-and-sum
+    ras_md = 1 if hoisted_ras else n_ras                            # its ModUps and ModDowns
     for deferred in deferred_modes:
         _say("fused block: running the oracle (n_ca=%d, n_ra=%d, one ModDown per output: %s)" % (n_ca, n_ra, deferred))
-        want = OB.ca_ra_block(orc, g_ca, g_ra, d["cts"], level, d["p_ca"], d["p_ra"], d["evks"], d["rlk"], d["k_in"], deferred=deferred)
+        want = OB.ca_ra_block(orc, g_ca, g_ra, d["cts"], level, d["p_ca"], d["p_ra"], d["evks"], d["rlk"], d["k_in"], deferred=deferred,
+                              hoisted_ras=hoisted_ras)
         for group in groups:
-            ctx.he_ws_reserve(ctx.he_ws_query_ca_ra_block(C_a, H, W, g_ca.R, 3, n_ca, n_ra, level, group, deferred))
+            ctx.he_ws_reserve(ctx.he_ws_query_ca_ra_block(C_a, H, W, g_ca.R, 3, n_ca, n_ra, level, group, deferred, hoisted_ras))
             ws = ctx.he_ws_bytes()
             outs = [zeros(2, level - 2, N) for _ in range(n_ca)]
             ctx.he_counters_reset()
-            ctx.he_ca_ra_block(C_a, H, W, g_ca.R, 3, level, d["k_in"], w_ca, w_ra, cts, outs, group=group, deferred=deferred)
+            ctx.he_ca_ra_block(C_a, H, W, g_ca.R, 3, level, d["k_in"], w_ca, w_ra, cts, outs, group=group, deferred=deferred,
+                               hoisted_ras=hoisted_ras)
             cnt = ctx.he_counters()
             for l in range(n_ca):
                 assert (host(outs[l]) == want[l]).all(), (deferred, group, l)
@@ -47,8 +50,8 @@ def _case(prm, C_a, H, W, c_in, c_mid, level, std, seed, groups, deferred_modes=
             # rotations: f^2-1 per input (Slide_f), log2(C_a) per intermediate (RaS), f^2-1 per output (Slide_1);
             # one relinearisation per intermediate
             assert cnt["keyswitch"] == 8 * n_ca + n_ras * n_ra + n_ra + 8 * n_ca, cnt
-            assert cnt["modup"] == n_ca + n_ras * n_ra + n_ra + 8 * n_ca
-            assert cnt["moddown"] == 8 * n_ca + n_ras * n_ra + n_ra + (n_ca if deferred else 8 * n_ca)
+            assert cnt["modup"] == n_ca + ras_md * n_ra + n_ra + 8 * n_ca
+            assert cnt["moddown"] == 8 * n_ca + ras_md * n_ra + n_ra + (n_ca if deferred else 8 * n_ca)
             assert cnt["mac"] == 2 * 9 * n_ca * n_ra and cnt["rescale"] == 2 * n_ra + n_ca
     err = check_fused_output(d, [host(o) for o in outs], level)
     _say("fused block: max |dec - float64| = %.3g" % err)
@@ -68,3 +71,15 @@ def test_fused_block_resnet20_unit():
     algorithm's loop exactly (group 1), and all intermediates batched."""
     _case(config_params(3), C_a=16, H=32, W=32, c_in=16, c_mid=16, level=23, std=(2.0 / (9 * 16)) ** 0.5, seed=6,
           groups=(1, 0), deferred_modes=(True,))
+
+
+def test_fused_block_hoisted_rotate_and_sum_small_ring():
+    prm = toy_params(logN=9, q_bits=40, nq=5, p_bits=41, np_=2, dnum=3, scale=2.0 ** 30, hamming=32, seed=97)
+    _case(prm, C_a=4, H=4, W=4, c_in=4, c_mid=8, level=4, std=0.2, seed=97, groups=(1, 0), hoisted_ras=True)
+
+
+@pytest.mark.timeout(1100)
+def test_fused_block_hoisted_rotate_and_sum_resnet20_unit():
+    _case(config_params(3), C_a=16, H=32, W=32, c_in=16, c_mid=16, level=23, std=(2.0 / (9 * 16)) ** 0.5, seed=6,
+          groups=(0,), deferred_modes=(True,), hoisted_ras=True)
+

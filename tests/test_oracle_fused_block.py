@@ -12,8 +12,9 @@ from oracle import conv2d as CV
 from oracle.he_oracle import Oracle
 
 
-def fused_inputs(prm, C_a, H, W, c_in, c_mid, level, std, seed):
-    """Everything the block consumes, for n_CA = c_in / C_a input ciphertexts (shared with the GPU parity test)."""
+def fused_inputs(prm, C_a, H, W, c_in, c_mid, level, std, seed, all_ras_multiples=False):
+    """Everything the block consumes, for n_CA = c_in / C_a input ciphertexts (shared with the GPU parity test).
+    all_ras_multiples: also the keys of every multiple of H*W*R below C_a (the hoisted rotate-and-sum), drawn last."""
     rng = S.make_rng(seed)
     orc = Oracle.from_params(prm)
     cl = K.Client(orc, S.ternary_secret(rng, prm.N, prm.hamming))
@@ -42,6 +43,12 @@ def fused_inputs(prm, C_a, H, W, c_in, c_mid, level, std, seed):
         pl = CV.encode_ra_weights(orc, g_ra, w2[l * C_a:(l + 1) * C_a], level - 2, float(q[level - 2]))
         for j in range(g_ra.n_in):
             p_ra[l][j] = pl[j]
+    if all_ras_multiples:
+        base = g_ca.H * g_ca.W * g_ca.R
+        for i in range(1, C_a):
+            if base * i not in evks:
+                evks[base * i] = cl.rotation_key(orc.galois_elt(base * i), S.uniform_limbs(rng, prm.moduli, N, prm.dnum),
+                                                 S.gaussian_error(rng, N, prm.sigma, prm.dnum))
     return dict(orc=orc, cl=cl, g_ca=g_ca, g_ra=g_ra, x=x, w1=w1, w2=w2, evks=evks, rlk=rlk, cts=cts, k_in=k_in,
                 s_out=s_out, p_ca=p_ca, p_ra=p_ra, n_ca=n_ca)
 
@@ -78,3 +85,18 @@ def test_fused_block_matches_float(c_in, deferred):
         flat_ra = np.stack([d["p_ra"][0][j] for j in range(2)])
         want, _ = OB.ca_square_ra(d["orc"], d["g_ca"], d["g_ra"], d["cts"][0], level, flat_ca, flat_ra, d["evks"], d["rlk"], d["k_in"])
         assert (outs[0] == want).all()
+
+
+def test_block_with_hoisted_rotate_and_sum_matches_float():
+    """The block with RaS over C_a as one hoisted sum of rotations per intermediate: same values as the stepwise
+    form (conv(conv(x)^2) within the tolerance), other bits."""
+    prm = toy_params(logN=9, q_bits=40, nq=5, p_bits=41, np_=2, dnum=3, scale=2.0 ** 30, hamming=32, seed=97)
+    level = 4
+    d = fused_inputs(prm, 4, 4, 4, 4, 8, level, 0.2, 97, all_ras_multiples=True)
+    a = OB.ca_ra_block(d["orc"], d["g_ca"], d["g_ra"], d["cts"], level, d["p_ca"], d["p_ra"], d["evks"], d["rlk"], d["k_in"],
+                       deferred=True, hoisted_ras=True)
+    b = OB.ca_ra_block(d["orc"], d["g_ca"], d["g_ra"], d["cts"], level, d["p_ca"], d["p_ra"], d["evks"], d["rlk"], d["k_in"],
+                       deferred=True)
+    check_fused_output(d, a, level)
+    assert any((u != v).any() for u, v in zip(a, b))
+
