@@ -148,9 +148,6 @@ struct ModDownEpilogue {
     // (polynomial, Galois element, key) terms, a sum of rotations brought down by one ModDown; raised/own/evk/g
     // are then indexed by term, c0[0] must be null (the rotated c0 parts arrive summed through self0[0]).
     uint32_t n_terms;
-    // hoisted != 0 (with n_terms > 0): several outputs per launch again, every output the sum of the SAME n_terms
-    // (Galois element, key) terms applied to its own polynomial: raised/own are indexed by job, evk/g by term.
-    uint32_t hoisted;
     const u64* raised[HE_MAX_KS_JOBS];  // [beta][R][N]
     const u64* own[HE_MAX_KS_JOBS];     // [L1][N]
     const u64* evk[HE_MAX_KS_JOBS];     // [dnum][2][M][N]
@@ -165,7 +162,6 @@ struct IpPrologue {
     uint32_t g[HE_MAX_KS_JOBS];
     uint32_t beta, R, M, L1, k, nq;
     uint32_t n_terms;                   // as in ModDownEpilogue: > 0 = one output, arrays indexed by term
-    uint32_t hoisted;                   // as in ModDownEpilogue: raised indexed by job, evk/g by term
 };
 
 // One batched transform launch (both passes).  Limb i is read at seg[src_seg[i]] + src_limb[i]*N

@@ -861,8 +861,8 @@ int32_t ks_rotate_sum_deferred(he_ctx* c, uint32_t level, const KsSumTerm* terms
 // C_a, Section 2.2, evaluated as the sum of its C_a - 1 rotations of the input instead of log2 C_a dependent steps):
 //   A_j   = sum_t sum_i sigma_{g_t}(ModUp(c1_j)_i) * evk_t,i
 //   out_j = ( sum_t sigma_{g_t}(c0_j) + ModDown(A_j,0) + s0_j , ModDown(A_j,1) + s1_j )     (s0_j, s1_j: addends or null)
-// The T keys are shared by all J ciphertexts; at N = 2^16 the inner products run inside the ModDown transforms with
-// several ciphertexts per launch, elsewhere one ciphertext at a time through ks_rotate_sum_deferred.
+// The T keys are shared by all J ciphertexts: the inner products of up to 8 ciphertexts run in one register-tiled kernel
+// into stored accumulators, which the ModDown then reads.
 
 // grid (N/256, L1, J): s0_j[r][n] = sum_t c0_j[r][sigma_t-source of n] (+ add_j[r][n])
 struct HoistC0 {
@@ -951,21 +951,104 @@ __global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_kernel(HoistIp a, u
     }
 }
 
-// Which of the two forms the inner products of a hoisted sum over `nb` ciphertexts take.  The register-tiled kernel
-// reuses every key value nb times but gathers, for each term, other rows of all nb*beta digit limbs of the raised-basis
-// limb it works on: that set (nb*beta*N*8 bytes) has to stay in an XCD's 4 MiB L2, or the gathers stream from memory
-// (measured at N = 2^16: 8 ciphertexts x 1 digit 0.26 ms against 0.61 ms fused; 8 x 3 digits 1.96 ms against 1.44 ms).
-// Otherwise, at N = 2^16, the sums run inside the ModDown transforms, one work group per (ciphertext, component),
-// whose digits (beta*N*8 bytes) do stay in L2.
-static bool hoisted_sum_fused(const he_ctx* c, uint32_t level, uint32_t T, uint32_t nb) {
-    const uint32_t beta = num_digits(c, level);
-    return c->logN == 16 && beta <= 8 && T >= 1 && T <= HE_MAX_KS_JOBS && (size_t)nb * beta * c->N * sizeof(u64) > ((size_t)4 << 20);
+// The same sums when every Galois element of the list is 1 modulo 2^(logN-3): such a map moves a value only inside its
+// aligned block of 16 positions (the low logN-4 bits of the exponent index g*k + (g-1)/2 are those of k), which is
+// the case for rotations by multiples of N/32 slots - the rotate-and-sum amounts over up to 16 channel blocks.  Then a
+// work group's 256 points need exactly their own 256 values of every digit, for every term: they are loaded once
+// into LDS and each term reads them back permuted, so that the only global loads left per (term, digit) are the two key
+// values.  LDS: J*beta*2 KiB.  grid (N/256, R).
+#define HSL_MAX_TILES 24      // J * beta digit tiles of 2 KiB: 48 KiB of LDS
+__global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_local_kernel(HoistIp a, u64* __restrict__ acc, const ModConst* mc,
+                                                                          uint32_t logN, uint32_t R, uint32_t beta, uint32_t M,
+                                                                          uint32_t level, uint32_t nq, uint32_t alpha, uint32_t init) {
+    __shared__ u64 dig[HSL_MAX_TILES * KS_THREADS];
+    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y;
+    const uint32_t mi = r <= level ? r : nq + (r - level - 1);
+    const ModConst m = mc[mi];
+    const size_t ro = ((size_t)r << logN) + n, cstride = (size_t)R << logN;
+    for (uint32_t j = 0; j < beta; j++) {
+        const bool own_digit = r <= level && r / alpha == j;
+        const size_t doff = own_digit ? ro : ((size_t)(j * R + r) << logN) + n;
+#pragma unroll
+        for (int i = 0; i < HS_JOBS; i++)
+            if ((uint32_t)i < a.J) dig[(j * a.J + i) * KS_THREADS + threadIdx.x] = (own_digit ? a.own[i] : a.raised[i])[doff];
+    }
+    u128 s0[HS_JOBS], s1[HS_JOBS];
+    u64 t0[HS_JOBS], t1[HS_JOBS];
+#pragma unroll
+    for (int i = 0; i < HS_JOBS; i++) {
+        s0[i] = s1[i] = 0;
+        t0[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i) * cstride + ro] : 0;
+        t1[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i + 1) * cstride + ro] : 0;
+    }
+    __syncthreads();
+    // one flat loop over (term, digit) with the next pair's key values requested before the current products
+    const uint32_t total = a.T * beta;
+    const size_t kstride = (size_t)M << logN, koff = ((size_t)mi << logN) + n;
+    u64 kb = 0, ka = 0;
+    if (total) { kb = a.evk[0][koff]; ka = a.evk[0][kstride + koff]; }
+    uint32_t pending = 0, t = 0, j = 0, lsrc = 0;
+    for (uint32_t it = 0; it < total; it++) {
+        if (j == 0) {
+            const uint32_t g = a.g[t];
+            lsrc = (threadIdx.x & ~15u) | ((g == 1 ? n : galois_src_ks(n, g, logN)) & 15u);
+        }
+        uint32_t tn = t, jn = j + 1;
+        if (jn == beta) { jn = 0; tn = t + 1; }
+        u64 kbn = 0, kan = 0;
+        if (it + 1 < total) {
+            const u64* e = a.evk[tn] + (size_t)(2 * jn) * kstride + koff;
+            kbn = e[0]; kan = e[kstride];
+        }
+        if (pending == 8) {
+#pragma unroll
+            for (int i = 0; i < HS_JOBS; i++) {
+                t0[i] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
+                t1[i] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
+                s0[i] = s1[i] = 0;
+            }
+            pending = 0;
+        }
+#pragma unroll
+        for (int i = 0; i < HS_JOBS; i++) {
+            if ((uint32_t)i < a.J) {
+                const u64 d = dig[(j * a.J + i) * KS_THREADS + lsrc];
+                s0[i] += (u128)d * kb;
+                s1[i] += (u128)d * ka;
+            }
+        }
+        pending++;
+        kb = kbn; ka = kan; t = tn; j = jn;
+    }
+#pragma unroll
+    for (int i = 0; i < HS_JOBS; i++) {
+        if ((uint32_t)i < a.J) {
+            acc[(size_t)(2 * i) * cstride + ro] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
+            acc[(size_t)(2 * i + 1) * cstride + ro] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
+        }
+    }
 }
 
+// Whether the Galois elements of a hoisted sum only move values inside aligned blocks of 16 positions (see
+// hoisted_sum_ip_local_kernel).  Otherwise the register-tiled kernel gathers from memory: for each term it reads other
+// rows of all nb*beta digit limbs of the raised-basis limb it works on, and that set (nb*beta*N*8 bytes) should stay in
+// an XCD's 4 MiB L2 (measured at N = 2^16 with 8 ciphertexts: one digit 0.26 ms, three digits 1.96 ms for 15 terms).
+static bool hoisted_sum_local(const he_ctx* c, uint32_t level, const uint32_t* gs, uint32_t T) {
+    if (c->logN < 8 || num_digits(c, level) > HSL_MAX_TILES) return false;
+    const uint32_t mask = (1u << (c->logN - 3)) - 1;
+    for (uint32_t t = 0; t < T; t++)
+        if ((gs[t] & mask) != 1u) return false;
+    return true;
+}
+
+// ciphertexts per launch set: the engine's limits, the kernel's register tile, and for the LDS form its digit tiles
 static uint32_t hoisted_sum_jb(const he_ctx* c, uint32_t level, uint32_t J) {
     uint32_t cb, jb;
     engine_shape(c, level, J, J, cb, jb);
-    return std::min<uint32_t>(jb, HS_JOBS);
+    jb = std::min<uint32_t>(jb, HS_JOBS);
+    const uint32_t beta = num_digits(c, level);
+    if (beta <= HSL_MAX_TILES) jb = std::min<uint32_t>(jb, HSL_MAX_TILES / beta);
+    return jb;
 }
 
 size_t ks_hoisted_sum_ws_elems(const he_ctx* c, uint32_t level, uint32_t J, uint32_t T) {
@@ -996,7 +1079,7 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
     u64* conv = tmp_dn + (size_t)jb * 2 * k * N;
     for (uint32_t j0 = 0; j0 < J; j0 += jb) {
         const uint32_t nb = std::min(jb, J - j0);
-        const bool fused = hoisted_sum_fused(c, level, T, nb);
+        const bool local = hoisted_sum_local(c, level, gs, T);
         for (uint32_t t0 = 0; t0 < nb; t0 += cb) {
             int32_t rc = modup_batch(c, srcs + j0 + t0, std::min(cb, nb - t0), level, raised + (size_t)t0 * beta * R * N, tmp_up);
             if (rc != HE_OK) return rc;
@@ -1012,38 +1095,31 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
             HE_HIP(c, hipGetLastError());
         }
         c->cnt.automorph += (uint64_t)nb * T * L1;
-        IpPrologue ip = {};
         ModDownEpilogue ep = {};
         ep.acc = acc; ep.pinv = c->d_pinv; ep.pinv_sh = c->d_pinv_sh; ep.R = R; ep.L1 = L1;
-        ep.fused = fused ? 1u : 0u; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M;
+        ep.fused = 0; ep.beta = beta; ep.alpha = c->alpha; ep.M = c->M;
         for (uint32_t j = 0; j < nb; j++) {
             ep.c0[j] = nullptr; ep.g[j] = 1;
             ep.self0[j] = s0 + (size_t)j * L1 * N;
             ep.self1[j] = srcs[j0 + j].s1;
             ep.out0[j] = out0[j0 + j]; ep.out1[j] = out1[j0 + j];
         }
-        if (fused) {
-            ep.n_terms = T; ep.hoisted = 1;
-            ip.beta = beta; ip.R = R; ip.M = c->M; ip.L1 = L1; ip.k = k; ip.nq = c->nq; ip.n_terms = T; ip.hoisted = 1;
-            for (uint32_t t = 0; t < T; t++) { ip.evk[t] = ep.evk[t] = evks[t]; ip.g[t] = ep.g[t] = gs[t]; }
-            for (uint32_t j = 0; j < nb; j++) {
-                ip.raised[j] = ep.raised[j] = raised + (size_t)j * beta * R * N;
-                ep.own[j] = srcs[j0 + j].c1;
-            }
-        } else {
-            // the inner products of all the chunk's ciphertexts, register-tiled, into stored accumulators
-            for (uint32_t t0 = 0; t0 < T; t0 += HS_TERMS) {
-                HoistIp hi = {};
-                hi.J = nb; hi.T = std::min<uint32_t>(HS_TERMS, T - t0);
-                for (uint32_t t = 0; t < hi.T; t++) { hi.evk[t] = evks[t0 + t]; hi.g[t] = gs[t0 + t]; }
-                for (uint32_t j = 0; j < nb; j++) { hi.raised[j] = raised + (size_t)j * beta * R * N; hi.own[j] = srcs[j0 + j].c1; }
+        // the inner products of all the chunk's ciphertexts, register-tiled, into stored accumulators
+        for (uint32_t t0 = 0; t0 < T; t0 += HS_TERMS) {
+            HoistIp hi = {};
+            hi.J = nb; hi.T = std::min<uint32_t>(HS_TERMS, T - t0);
+            for (uint32_t t = 0; t < hi.T; t++) { hi.evk[t] = evks[t0 + t]; hi.g[t] = gs[t0 + t]; }
+            for (uint32_t j = 0; j < nb; j++) { hi.raised[j] = raised + (size_t)j * beta * R * N; hi.own[j] = srcs[j0 + j].c1; }
+            if (local)
+                hipLaunchKernelGGL(hoisted_sum_ip_local_kernel, dim3(N / KS_THREADS, R), dim3(KS_THREADS), 0, c->stream, hi, acc, c->d_mc,
+                                   c->logN, R, beta, c->M, level, c->nq, c->alpha, t0 == 0 ? 1u : 0u);
+            else
                 hipLaunchKernelGGL(hoisted_sum_ip_kernel, dim3(N / KS_THREADS, R), dim3(KS_THREADS), 0, c->stream, hi, acc, c->d_mc, c->logN, R,
                                    beta, c->M, level, c->nq, c->alpha, t0 == 0 ? 1u : 0u);
-                HE_HIP(c, hipGetLastError());
-            }
+            HE_HIP(c, hipGetLastError());
         }
         if (c->prof_on) c->prof_key_limbs += (uint64_t)T * 2 * beta * R;
-        int32_t rc = moddown_chain(c, level, nb, acc, tmp_dn, conv, fused ? &ip : nullptr, ep);
+        int32_t rc = moddown_chain(c, level, nb, acc, tmp_dn, conv, nullptr, ep);
         if (rc != HE_OK) return rc;
         c->cnt.keyswitch += (uint64_t)nb * T;
     }

@@ -293,10 +293,9 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
             u128 sum[4] = {0, 0, 0, 0};
             uint32_t pending = 0;
             for (uint32_t term = 0; term < n_terms; term++) {
-                const uint32_t idx = ep.n_terms ? term : job;          // key and Galois element
-                const uint32_t si = ep.hoisted ? job : idx;            // polynomial and its raised digits
-                const u64* own = ep.own[si] + ((size_t)r << 16);
-                const u64* raised = ep.raised[si] + ((size_t)r << 16);
+                const uint32_t idx = ep.n_terms ? term : job;
+                const u64* own = ep.own[idx] + ((size_t)r << 16);
+                const u64* raised = ep.raised[idx] + ((size_t)r << 16);
                 const u64* key = ep.evk[idx] + ((size_t)(comp * ep.M + r) << 16) + (size_t)b * 256;
                 if (term) {
                     const uint32_t gt = ep.g[idx];
@@ -416,7 +415,7 @@ __global__ __launch_bounds__(T16_THREADS) void ntt16_inv_b_kernel(Ntt16Args a, L
             for (uint32_t term = 0; term < n_terms; term++) {
                 const uint32_t idx = ip.n_terms ? term : job;
                 const uint32_t g = ip.g[idx];
-                const u64* raised = ip.raised[ip.hoisted ? job : idx] + ((size_t)(ip.L1 + tp) << 16);
+                const u64* raised = ip.raised[idx] + ((size_t)(ip.L1 + tp) << 16);
                 const u64* key = ip.evk[idx] + ((size_t)(comp * ip.M + ip.nq + tp) << 16) + (size_t)b * 256;
                 uint32_t src[4];
 #pragma unroll

@@ -1,7 +1,8 @@
 """GPU parity for the rotate-and-sum of he_conv2d evaluated as one hoisted sum of rotations per output
 (hoisted_ras: one ModUp and one ModDown per output, keys shared by the outputs): bit-exact against the oracle on a
-small ring (generic path, one output at a time), on a two-pass ring, at N = 2^16 at level 5 (single digit) and on the
-ResNet-20 layer at level 23 (three digits, eight outputs batched in one launch set), with operation counts; and
+small ring, on a two-pass ring, with 32 channel blocks (the form that gathers from memory), at N = 2^16 at level 5
+(single digit) and on the ResNet-20 layer at level 23 (three digits, eight outputs in one launch set), with operation
+counts; and
 he_rotate_sum on one ciphertext repeated (terms that rotate the same polynomial share its ModUp)."""
 import sys
 
@@ -68,6 +69,13 @@ def test_small_ring_generic_path():
 def test_two_pass_ring_with_deferred_taps():
     prm = toy_params(logN=13, q_bits=40, nq=4, p_bits=50, np_=2, dnum=2, scale=2.0 ** 30, hamming=32, seed=82)
     _run(prm, C_a=8, H=4, W=8, c_out=32, level=3, w_std=0.1, tol=1e-3, deferred_taps=True)
+
+
+def test_thirty_two_channel_blocks_gathered_form():
+    # C_a = 32: rotations by multiples of N/64 slots leave the aligned blocks of 16, so the inner products gather from
+    # memory instead of from LDS; 31 terms take two launches of at most 16 (the second continues the accumulators)
+    prm = toy_params(logN=12, q_bits=40, nq=4, p_bits=41, np_=2, dnum=2, scale=2.0 ** 30, hamming=32, seed=83)
+    _run(prm, C_a=32, H=4, W=4, c_out=8, level=3, w_std=0.1, tol=1e-3)
 
 
 def test_n65536_level5_single_digit():
