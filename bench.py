@@ -443,8 +443,16 @@ def main():
             blk.downsampling_block(ctx, 16, 32, 32, 2, level, cts[0], w3, w1, masks, masks, 8192, [3 << 53, 3 << 55], 1 << 17)
 
         ms_blk = timed(run_block, reps=10)
-        blk.use_pool(None)
         extras["downsampling_block_ms"] = round(ms_blk, 3)
+        ctx.he_ws_reserve(ctx.he_ws_query_conv2d(16, 32, 32, 2, 3, level, 16, hoisted_ras=True))
+
+        def run_block_h():
+            blk.use_pool(pool)
+            blk.downsampling_block(ctx, 16, 32, 32, 2, level, cts[0], w3, w1, masks, masks, 8192, [3 << 53, 3 << 55], 1 << 17,
+                                   hoisted_ras=True)
+
+        extras["downsampling_block_hoisted_ras_ms"] = round(timed(run_block_h, reps=10), 3)
+        blk.use_pool(None)
         del pool
         del w3, w1, masks
 

@@ -58,10 +58,11 @@ def activation_step(orc, u, level, k3, rlk):
     return orc.rescale(orc.mulct(orc.drop_level(u, level), w, level - 1, rlk), level - 1)
 
 
-def downsampling_block(orc, g3, g1, ct, level, p3, p1, m_main, m_short, evks, rlk, k_in, k3, k_short, progress=None):
+def downsampling_block(orc, g3, g1, ct, level, p3, p1, m_main, m_short, evks, rlk, k_in, k3, k_short, progress=None,
+                       hoisted_ras=False):
     """Returns every stage: conv3, conv1 (lists), merged, u, a1, a2, short, out."""
-    st = {"conv3": CV.caconv(orc, g3, ct, level, p3, evks, progress=progress)}
-    st["conv1"] = CV.caconv(orc, g1, ct, level, p1, evks)
+    st = {"conv3": CV.caconv(orc, g3, ct, level, p3, evks, progress=progress, hoisted_ras=hoisted_ras)}
+    st["conv1"] = CV.caconv(orc, g1, ct, level, p1, evks, hoisted_ras=hoisted_ras)
     lv = level - 2
     st["merged"] = merge(orc, st["conv3"], m_main, level - 1)
     st["u"] = orc.affine(st["merged"], lv, [k_in] * (lv + 1), [0] * (lv + 1))

@@ -79,16 +79,17 @@ def activation_step(ctx, u, level, k3):
 
 
 def downsampling_block(ctx, C_a, H, W, R, level, ct_in, w3, w1, masks_main, masks_short, k_in, k3, k_short,
-                       keep=False):
+                       keep=False, hoisted_ras=False):
     """ct_in at `level` -> block output at level-6.
 
     w3 / w1: n_out*9 / n_out weight plaintexts at `level`; masks_*: n_out one-hot plaintexts at level-1;
     k_in: integer that lifts the merged main path to the activation's working scale; k3: the two
     constants of the activation steps; k_short: integer that lifts the merged shortcut to the scale
-    of the activation's output.  With keep=True returns (out, dict of every intermediate)."""
+    of the activation's output.  With keep=True returns (out, dict of every intermediate).  hoisted_ras: the
+    rotate-and-sum of both convolutions as one hoisted sum of rotations per output (see he_conv2d)."""
     N, n_out = ctx.N, len(masks_main)
-    conv3 = ctx.he_conv2d(C_a, H, W, R, 3, level, w3, ct_in, [_ct(level - 1, N) for _ in range(n_out)])
-    conv1 = ctx.he_conv2d(C_a, H, W, R, 1, level, w1, ct_in, [_ct(level - 1, N) for _ in range(n_out)])
+    conv3 = ctx.he_conv2d(C_a, H, W, R, 3, level, w3, ct_in, [_ct(level - 1, N) for _ in range(n_out)], hoisted_ras=hoisted_ras)
+    conv1 = ctx.he_conv2d(C_a, H, W, R, 1, level, w1, ct_in, [_ct(level - 1, N) for _ in range(n_out)], hoisted_ras=hoisted_ras)
     lv = level - 2
     merged = merge_outputs(ctx, conv3, masks_main, level - 1)
     u = ctx.he_affine(merged, lv, [k_in] * (lv + 1), [0] * (lv + 1), _ct(lv, N))

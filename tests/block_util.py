@@ -7,8 +7,9 @@ from oracle import ckks_client as K
 from oracle.he_oracle import Oracle
 
 
-def block_inputs(prm, C_a, H, W, c_out, level, std3, std1):
-    """Everything both sides consume: keys, the encrypted image, weight and merge plaintexts, constants."""
+def block_inputs(prm, C_a, H, W, c_out, level, std3, std1, all_ras_multiples=False):
+    """Everything both sides consume: keys, the encrypted image, weight and merge plaintexts, constants.
+    all_ras_multiples: also the keys of every multiple of H*W*R below C_a (hoisted rotate-and-sum), drawn last."""
     from oracle import block as OB
     from oracle import conv2d as CV
     rng = S.make_rng(prm.seed)
@@ -33,6 +34,12 @@ def block_inputs(prm, C_a, H, W, c_out, level, std3, std1):
              p1=CV.encode_weights(orc, g1, w1, level, float(q[level])),
              m_main=OB.one_hot_masks(orc, g3, g3.n_out, level - 1, float(q[level - 1])),
              m_short=OB.one_hot_masks(orc, g3, g3.n_out, level - 1, ms_short))
+    if all_ras_multiples:
+        base = g3.H * g3.W * g3.R
+        for i in range(1, C_a):
+            if base * i not in evks:
+                evks[base * i] = cl.rotation_key(orc.galois_elt(base * i), S.uniform_limbs(rng, prm.moduli, N, prm.dnum),
+                                                 S.gaussian_error(rng, N, prm.sigma, prm.dnum))
     return d
 
 

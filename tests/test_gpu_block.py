@@ -106,7 +106,7 @@ def test_strided_and_pointwise_conv_small_ring():
     _conv_case(prm, C_a=4, H=4, W=4, c_out=8, f=1, stride=1, level=1, w_std=0.1, tol=1e-3)
 
 
-def _block_case(prm, C_a, H, W, c_out, level, std3, std1):
+def _block_case(prm, C_a, H, W, c_out, level, std3, std1, hoisted_ras=False):
     """3x3 stride-2 CAConv -> merge -> p(p(u)), plus the 1x1 stride-2 shortcut -> merge, added: every stage
     bit-exact against the same sequence on the oracle, the decrypted result against float64."""
     from gpu_util import dev, host
@@ -114,11 +114,11 @@ def _block_case(prm, C_a, H, W, c_out, level, std3, std1):
     from block_util import block_inputs, check_block_output
     from paper_2302_02407_amd import block as B
     from paper_2302_02407_amd.binding import HEContext
-    d = block_inputs(prm, C_a, H, W, c_out, level, std3, std1)
+    d = block_inputs(prm, C_a, H, W, c_out, level, std3, std1, all_ras_multiples=hoisted_ras)
     ctx, g3, n_out = HEContext.from_params(prm), d["g3"], d["g3"].n_out
     _say("block: running the oracle (%d + %d output ciphertexts)" % (n_out, n_out))
     want = OB.downsampling_block(d["orc"], g3, d["g1"], d["ct"], level, d["p3"], d["p1"], d["m_main"], d["m_short"],
-                                 d["evks"], d["rlk"], d["k_in"], d["k3"], d["k_short"], progress=_say)
+                                 d["evks"], d["rlk"], d["k_in"], d["k3"], d["k_short"], progress=_say, hoisted_ras=hoisted_ras)
     _say("block: oracle done, running the GPU path")
     for st, k in d["evks"].items():
         ctx.he_evk_register(ctx.galois_elt(st), dev(k))
@@ -126,7 +126,7 @@ def _block_case(prm, C_a, H, W, c_out, level, std3, std1):
     d3 = [dev(d["p3"][o, t]) for o in range(n_out) for t in range(9)]
     d1 = [dev(d["p1"][o, 0]) for o in range(n_out)]
     out, got = B.downsampling_block(ctx, C_a, H, W, g3.R, level, dev(d["ct"]), d3, d1, [dev(m) for m in d["m_main"]],
-                                    [dev(m) for m in d["m_short"]], d["k_in"], d["k3"], d["k_short"], keep=True)
+                                    [dev(m) for m in d["m_short"]], d["k_in"], d["k3"], d["k_short"], keep=True, hoisted_ras=hoisted_ras)
     got["out"] = out
     for name in ("conv3", "conv1"):
         for o in range(n_out):
@@ -139,6 +139,11 @@ def _block_case(prm, C_a, H, W, c_out, level, std3, std1):
 def test_downsampling_block_small_ring():
     prm = toy_params(logN=10, q_bits=40, nq=8, p_bits=41, np_=3, dnum=3, scale=2.0 ** 30, hamming=32, seed=93)
     _block_case(prm, C_a=4, H=4, W=4, c_out=16, level=7, std3=0.1, std1=0.3)
+
+
+def test_downsampling_block_hoisted_rotate_and_sum_small_ring():
+    prm = toy_params(logN=10, q_bits=40, nq=8, p_bits=41, np_=3, dnum=3, scale=2.0 ** 30, hamming=32, seed=93)
+    _block_case(prm, C_a=4, H=4, W=4, c_out=16, level=7, std3=0.1, std1=0.3, hoisted_ras=True)
 
 
 @pytest.mark.timeout(1100)
