@@ -156,9 +156,17 @@ def ras_hoisted(orc: Oracle, geo: ConvGeometry, cur, level, evks):
     itself, the rotations sharing one ModUp (they rotate the same ciphertext) and one ModDown (rotate_sum_deferred):
     the same sum as the log2(C_a) rotate-and-add steps, with one ModDown rounding instead of log2(C_a)."""
     base = geo.H * geo.W * geo.R
-    steps = [base * i for i in range(1, geo.C_a)]
-    gs = [1] + [orc.galois_elt(st) for st in steps]
-    return orc.rotate_sum_deferred([cur] * geo.C_a, level, gs, [None] + [evks[st] for st in steps])
+    rm, qm = orc.raised_moduli(level), list(range(level + 1))
+    raised = orc.modup(cur[1], level)                       # shared by all the rotations: they rotate the same ciphertext
+    acc = rot0 = None
+    for i in range(1, geo.C_a):
+        g = orc.galois_elt(base * i)
+        ip = orc.inner_product(orc.automorph_ntt(raised, g), level, evks[base * i])
+        acc = ip if acc is None else orc.add_limbs(acc, ip, rm + rm)
+        r0 = orc.automorph_ntt(cur[0], g)
+        rot0 = r0 if rot0 is None else orc.add_limbs(rot0, r0, qm)
+    out = np.stack([orc.add_limbs(orc.moddown(acc[0], level), rot0, qm), orc.moddown(acc[1], level)])
+    return orc.add(out, cur, level)
 
 
 def caconv(orc: Oracle, geo: ConvGeometry, ct, level, pts, evks, keep=False, progress=None, deferred_taps=False,

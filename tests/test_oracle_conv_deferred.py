@@ -181,3 +181,21 @@ def test_hoisted_rotate_and_sum_is_the_same_sum():
     assert max(np.max(np.abs(np.asarray(u) - np.asarray(v))) for u, v in zip(da, db)) < 1e-3
     assert any((u != v).any() for u, v in zip(a, b))
 
+
+def test_hoisted_rotate_and_sum_is_the_pinned_rotation_sum():
+    """ras_hoisted writes the sum out with its single ModUp; it must be, bit for bit, rotate_sum_deferred (the function
+    pinned in exact integers) applied to the ciphertext repeated C_a times with the Galois elements 1, g, g^2, ..."""
+    prm = toy_params(logN=8, q_bits=40, nq=3, p_bits=41, np_=1, dnum=3, scale=2.0 ** 30, hamming=16, seed=57)
+    rng = S.make_rng(57)
+    o = Oracle.from_params(prm)
+    cl = K.Client(o, S.ternary_secret(rng, prm.N, prm.hamming))
+    geo = CV.ConvGeometry(prm.N, 8, 2, 2, 4)
+    base = geo.H * geo.W * geo.R
+    steps = [base * i for i in range(1, geo.C_a)]
+    evks = _keys(o, cl, prm, rng, steps)
+    for level in (2, 1):
+        cur = np.stack([S.uniform_limbs(rng, prm.q[:level + 1], prm.N)[0] for _ in range(2)])
+        a = CV.ras_hoisted(o, geo, cur, level, evks)
+        b = o.rotate_sum_deferred([cur] * geo.C_a, level, [1] + [o.galois_elt(s) for s in steps], [None] + [evks[s] for s in steps])
+        assert (a == b).all()
+
