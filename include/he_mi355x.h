@@ -227,7 +227,8 @@ int32_t he_ws_query_rotate_batch(const he_ctx* ctx, uint32_t level, uint32_t n_c
  * deferred != 0: the rotations share ONE ModDown - each term's raised digits are multiplied into its key, the
  * products are summed over q_0..q_level,p_*, and the sum is brought down once; out0 also gets the sum of the rotated c0
  * parts.  The result encrypts the same sum with one ModDown's rounding instead of one per rotation, and differs in
- * bits from the deferred == 0 result.  Grows the workspace with n_ct (all raised digits are live at once). */
+ * bits from the deferred == 0 result.  Terms that rotate the same ciphertext (the same pointer) share its ModUp.
+ * Grows the workspace with n_ct (all raised digits are live at once). */
 int32_t he_rotate_sum(he_ctx* ctx, const uint64_t* const* h_d_ct, uint32_t n_ct, uint32_t level, const int32_t* h_steps,
                       uint64_t* d_out, int32_t deferred);
 /* CRot(ct; step): identical bits to he_rotate_hoisted with n_steps = 1. */
