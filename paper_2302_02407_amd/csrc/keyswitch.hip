@@ -239,15 +239,11 @@ int32_t launch_moddown_final(he_ctx* c, const u64* conv, uint32_t n_jobs, const 
 }
 
 // ---------------------------------------------------------------- rescale kernels
-struct RescaleBatch {
-    const u64* ct[HE_MAX_KS_JOBS];   // [2][level+1][N]
-    u64* out[HE_MAX_KS_JOBS];        // [2][level][N]
-};
-
 // grid: (N/256, level, 2*n).  t = coefficient-form limb `level` of (job, comp) (tmp[job*2+comp][N]);
-// delta[job][comp][r] = (h mod q_r) - ((t + h mod q_l) mod q_r), h = floor(q_l/2).
+// delta[job][comp][r] = (h mod q_r) - ((t + h mod q_l) mod q_r), h = floor(q_l/2); negate != 0 stores -delta (for the
+// forward transform whose epilogue subtracts what it transformed).
 __global__ __launch_bounds__(KS_THREADS) void rescale_delta_kernel(const u64* __restrict__ tmp, u64* __restrict__ delta,
-                                                                   const ModConst* mc, uint32_t logN, uint32_t level) {
+                                                                   const ModConst* mc, uint32_t logN, uint32_t level, uint32_t negate) {
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
     const uint32_t r = blockIdx.y, jc = blockIdx.z;
     const ModConst ml = mc[level], mr = mc[r];
@@ -255,19 +251,7 @@ __global__ __launch_bounds__(KS_THREADS) void rescale_delta_kernel(const u64* __
     u64 t = addmod(tmp[((size_t)jc << logN) + n], h, ml.q);
     u64 tr = barrett64(t, mr.q, mr.mu, mr.bits);
     u64 hr = barrett64(h, mr.q, mr.mu, mr.bits);
-    delta[((size_t)(jc * level + r) << logN) + n] = submod(hr, tr, mr.q);
-}
-
-// grid: (N/256, level, 2*n).  out[comp][r] = (ct[comp][r] + delta[job][comp][r]) * q_l^-1 mod q_r.
-__global__ __launch_bounds__(KS_THREADS) void rescale_final_kernel(RescaleBatch rb, const u64* __restrict__ delta,
-                                                                   const ModConst* mc, const u64* qlinv, const u64* qlinv_sh,
-                                                                   uint32_t logN, uint32_t level) {
-    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x;
-    const uint32_t r = blockIdx.y, jc = blockIdx.z, job = jc >> 1, comp = jc & 1u;
-    const u64 q = mc[r].q;
-    u64 a = rb.ct[job][((size_t)(comp * (level + 1) + r) << logN) + n];
-    u64 d = delta[((size_t)(jc * level + r) << logN) + n];
-    rb.out[job][((size_t)(comp * level + r) << logN) + n] = shoup_mul(addmod(a, d, q), qlinv[r], qlinv_sh[r], q);
+    delta[((size_t)(jc * level + r) << logN) + n] = negate ? submod(tr, hr, mr.q) : submod(hr, tr, mr.q);
 }
 
 // ---------------------------------------------------------------- host: tables
@@ -1204,18 +1188,19 @@ size_t rescale_ws_elems(const he_ctx* c, uint32_t level, uint32_t n) {
 int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint32_t n, uint32_t level, u64* ws) {
     const uint32_t N = ctx->N, L1 = level + 1;
     if (ctx->logN <= 12) return sr_rescale(ctx, cts, outs, n, level);   // limb fits LDS: one launch, no scratch
-    for (uint32_t b0 = 0; b0 < n; b0 += HE_MAX_KS_JOBS) {
-        const uint32_t nb = std::min<uint32_t>(HE_MAX_KS_JOBS, n - b0);
+    // ciphertexts per launch set: the launch-list limit, and (for the fused last step) inputs that lie one after the other
+    const uint32_t cap = std::max<uint32_t>(1, std::min<uint32_t>(HE_MAX_KS_JOBS, HE_MAX_LAUNCH_LIMBS / (2 * level)));
+    for (uint32_t b0 = 0; b0 < n;) {
+        uint32_t nb = 1;
+        while (nb < cap && b0 + nb < n && cts[b0 + nb] == cts[b0] + (size_t)nb * 2 * L1 * N) nb++;
         u64* tmp = ws;
         u64* delta = tmp + (size_t)2 * nb * N;
-        RescaleBatch rb;
         std::vector<uint32_t> mods(2 * nb, level);
         std::vector<uint8_t> seg(2 * nb);
         std::vector<uint16_t> lim(2 * nb);
         TransformDesc t = {};
         t.fwd = false; t.n_seg = nb; t.dst = tmp; t.n = 2 * nb;
         for (uint32_t i = 0; i < nb; i++) {
-            rb.ct[i] = cts[b0 + i]; rb.out[i] = outs[b0 + i];
             t.seg[i] = cts[b0 + i];
             seg[2 * i] = seg[2 * i + 1] = (uint8_t)i;
             lim[2 * i] = (uint16_t)level; lim[2 * i + 1] = (uint16_t)(L1 + level);
@@ -1224,20 +1209,28 @@ int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint
         int32_t rc = launch_transform(ctx, t);
         if (rc != HE_OK) return rc;
         dim3 grid(N / KS_THREADS, level, 2 * nb), block(KS_THREADS);
-        hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level);
+        hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level, 1u);
         HE_HIP(ctx, hipGetLastError());
+        // forward transform of -delta whose epilogue writes (c - (-delta)) * q_l^-1: the input limb plays the stored
+        // accumulator (component stride level+1 limbs), q_l^-1 mod q_r the constant of the final product
         const uint32_t total = 2 * nb * level;
         std::vector<uint32_t> dm(total);
         for (uint32_t i = 0; i < total; i++) dm[i] = i % level;
-        for (uint32_t o = 0; o < total; o += HE_MAX_LAUNCH_LIMBS) {
-            uint32_t cnt = std::min<uint32_t>(HE_MAX_LAUNCH_LIMBS, total - o);
-            rc = launch_ntt(ctx, delta + (size_t)o * N, dm.data() + o, cnt);
-            if (rc != HE_OK) return rc;
+        ModDownEpilogue ep = {};
+        ep.acc = cts[b0]; ep.R = L1; ep.L1 = level;
+        ep.pinv = ctx->d_qlinv + (size_t)level * ctx->nq; ep.pinv_sh = ctx->d_qlinv_sh + (size_t)level * ctx->nq;
+        ep.fused = 0; ep.beta = 1; ep.alpha = ctx->alpha; ep.M = ctx->M;
+        for (uint32_t i = 0; i < nb; i++) {
+            ep.c0[i] = nullptr; ep.self0[i] = nullptr; ep.self1[i] = nullptr; ep.g[i] = 1;
+            ep.out0[i] = outs[b0 + i]; ep.out1[i] = outs[b0 + i] + (size_t)level * N;
         }
-        hipLaunchKernelGGL(rescale_final_kernel, grid, block, 0, ctx->stream, rb, delta, ctx->d_mc,
-                           ctx->d_qlinv + (size_t)level * ctx->nq, ctx->d_qlinv_sh + (size_t)level * ctx->nq, ctx->logN, level);
-        HE_HIP(ctx, hipGetLastError());
+        TransformDesc f = {};
+        f.fwd = true; f.seg[0] = delta; f.n_seg = 1; f.dst = delta; f.n = total; f.mod_idx = dm.data(); f.ep = &ep;
+        f.lazy_out = true;
+        rc = launch_transform(ctx, f);
+        if (rc != HE_OK) return rc;
         ctx->cnt.rescale += nb;
+        b0 += nb;
     }
     return HE_OK;
 }
