@@ -20,6 +20,7 @@
 #include <algorithm>
 
 #include "modarith.h"
+#include "ntt_blocks.h"
 
 #define KS_THREADS 256
 #define CONV_MAX_JOBS 8
@@ -856,13 +857,23 @@ struct HoistC0 {
     uint32_t g[HE_MAX_KS_JOBS];
     uint32_t T;
 };
+// LOCAL: every Galois element moves values only inside aligned blocks of 16 positions (see hoisted_sum_ip_local_kernel):
+// the work group's 256 values are read once into LDS and gathered from there.
+template <bool LOCAL>
 __global__ __launch_bounds__(KS_THREADS) void hoist_c0_sum_kernel(HoistC0 a, const ModConst* mc, uint32_t logN) {
+    __shared__ u64 tile[LOCAL ? KS_THREADS : 1];
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y, j = blockIdx.z;
     const u64 q = mc[r].q;
     const size_t o = ((size_t)r << logN) + n;
     const u64* c0 = a.c0[j] + ((size_t)r << logN);
     u64 v = a.add[j] ? a.add[j][o] : 0;
-    for (uint32_t t = 0; t < a.T; t++) v = addmod(v, c0[galois_src_ks(n, a.g[t], logN)], q);
+    if (LOCAL) {
+        tile[threadIdx.x] = c0[n];
+        __syncthreads();
+        for (uint32_t t = 0; t < a.T; t++) v = addmod(v, tile[(threadIdx.x & ~15u) | (galois_src_ks(n, a.g[t], logN) & 15u)], q);
+    } else {
+        for (uint32_t t = 0; t < a.T; t++) v = addmod(v, c0[galois_src_ks(n, a.g[t], logN)], q);
+    }
     a.s0[j][o] = v;
 }
 
@@ -940,75 +951,159 @@ __global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_kernel(HoistIp a, u
 // the case for rotations by multiples of N/32 slots - the rotate-and-sum amounts over up to 16 channel blocks.  Then a
 // work group's 256 points need exactly their own 256 values of every digit, for every term: they are loaded once
 // into LDS and each term reads them back permuted, so that the only global loads left per (term, digit) are the two key
-// values.  LDS: J*beta*2 KiB.  grid (N/256, R).
+// values.  LDS: J*beta*2 KiB.  grid (N/256, number of limbs in sel).
+//
+// Products are taken in halves, three multiplications each.  The 32x32+64-bit multiply-add is the slow instruction here
+// (a quarter of the rate of the others), so their count is what bounds the kernel.  With h = 27 for moduli of at most 54
+// bits and h = 30 for wider ones (up to 60 bits), a canonical digit value d = d1*2^h + d0 and a canonical key value
+// k = k1*2^h + k0 give d*k = d0*k0 + (d0*k1 + d1*k0)*2^h + d1*k1*2^2h with d0*k1 + d1*k0 = (d0-d1)*(k1-k0) + d0*k0 + d1*k1.
+// Three 64-bit accumulators per output take the sums of d0*k0, of d1*k1 and (signed) of (d0-d1)*(k1-k0) directly from
+// the multiply-adds, with no carries: three instructions per product, against four multiply-adds and ten others for a
+// 128-bit accumulation.  Every partial product is below 2^2h in magnitude, so after `period` pairs (32 for h = 27, 6
+// for h = 30: (period+1)*2^2h < 2^63, and period*2^(2*bits-2h) + q < 100q) the middle sum is formed, the carries of the
+// low and middle sums move up, the high sum is reduced modulo q, and the signed accumulator is set to what keeps the
+// identity; the three sums are put together and reduced once at the end.  Digits are made canonical (the forward
+// transform may leave them below 69q) and split while they are staged into LDS, the low half in the low word.  JT = size
+// of the register tile: ciphertexts a.J..JT-1 repeat ciphertext 0 and are not stored.
 #define HSL_MAX_TILES 24      // J * beta digit tiles of 2 KiB: 48 KiB of LDS
-__global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_local_kernel(HoistIp a, u64* __restrict__ acc, const ModConst* mc,
-                                                                          uint32_t logN, uint32_t R, uint32_t beta, uint32_t M,
-                                                                          uint32_t level, uint32_t nq, uint32_t alpha, uint32_t init) {
-    __shared__ u64 dig[HSL_MAX_TILES * KS_THREADS];
-    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y;
+#define HSL_RING 2            // (term, digit) pairs whose key values are in registers or on their way
+// the raised-basis limbs one launch works on: blockIdx.y indexes this list
+struct LimbSel {
+    uint32_t r[HE_MAX_MODULI];
+};
+template <int JT>
+__global__ __launch_bounds__(KS_THREADS, 3) void hoisted_sum_ip_local_kernel(HoistIp a, LimbSel sel, u64* __restrict__ acc,
+                                                                             const ModConst* mc, uint32_t logN, uint32_t R,
+                                                                             uint32_t beta, uint32_t M, uint32_t level, uint32_t nq,
+                                                                             uint32_t alpha, uint32_t init) {
+    extern __shared__ u64 dig[];                         // a.J * beta tiles of KS_THREADS values
+    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = sel.r[blockIdx.y];
     const uint32_t mi = r <= level ? r : nq + (r - level - 1);
     const ModConst m = mc[mi];
+    const uint32_t mrec = (1u << 24) / ((uint32_t)(m.q >> (m.bits - 8)) + 1);
+    const uint32_t h = m.bits > 54 ? 30u : 27u, period = m.bits > 54 ? 6u : 32u;
+    const u64 lo_h = (1ull << h) - 1;
     const size_t ro = ((size_t)r << logN) + n, cstride = (size_t)R << logN;
     for (uint32_t j = 0; j < beta; j++) {
         const bool own_digit = r <= level && r / alpha == j;
         const size_t doff = own_digit ? ro : ((size_t)(j * R + r) << logN) + n;
 #pragma unroll
-        for (int i = 0; i < HS_JOBS; i++)
-            if ((uint32_t)i < a.J) dig[(j * a.J + i) * KS_THREADS + threadIdx.x] = (own_digit ? a.own[i] : a.raised[i])[doff];
-    }
-    u128 s0[HS_JOBS], s1[HS_JOBS];
-    u64 t0[HS_JOBS], t1[HS_JOBS];
-#pragma unroll
-    for (int i = 0; i < HS_JOBS; i++) {
-        s0[i] = s1[i] = 0;
-        t0[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i) * cstride + ro] : 0;
-        t1[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i + 1) * cstride + ro] : 0;
-    }
-    __syncthreads();
-    // one flat loop over (term, digit) with the next pair's key values requested before the current products
-    const uint32_t total = a.T * beta;
-    const size_t kstride = (size_t)M << logN, koff = ((size_t)mi << logN) + n;
-    u64 kb = 0, ka = 0;
-    if (total) { kb = a.evk[0][koff]; ka = a.evk[0][kstride + koff]; }
-    uint32_t pending = 0, t = 0, j = 0, lsrc = 0;
-    for (uint32_t it = 0; it < total; it++) {
-        if (j == 0) {
-            const uint32_t g = a.g[t];
-            lsrc = (threadIdx.x & ~15u) | ((g == 1 ? n : galois_src_ks(n, g, logN)) & 15u);
-        }
-        uint32_t tn = t, jn = j + 1;
-        if (jn == beta) { jn = 0; tn = t + 1; }
-        u64 kbn = 0, kan = 0;
-        if (it + 1 < total) {
-            const u64* e = a.evk[tn] + (size_t)(2 * jn) * kstride + koff;
-            kbn = e[0]; kan = e[kstride];
-        }
-        if (pending == 8) {
-#pragma unroll
-            for (int i = 0; i < HS_JOBS; i++) {
-                t0[i] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
-                t1[i] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
-                s0[i] = s1[i] = 0;
-            }
-            pending = 0;
-        }
-#pragma unroll
-        for (int i = 0; i < HS_JOBS; i++) {
+        for (int i = 0; i < JT; i++) {
             if ((uint32_t)i < a.J) {
-                const u64 d = dig[(j * a.J + i) * KS_THREADS + lsrc];
-                s0[i] += (u128)d * kb;
-                s1[i] += (u128)d * ka;
+                const u64 v = reduce_small((own_digit ? a.own[i] : a.raised[i])[doff], m.q, m.bits, mrec);
+                dig[(j * a.J + i) * KS_THREADS + threadIdx.x] = (v & lo_h) | ((v >> h) << 32);
             }
         }
-        pending++;
-        kb = kbn; ka = kan; t = tn; j = jn;
     }
+    // per output and component: low sum, high sum, and the signed sum bm = (middle sum) - low - high
+    u64 b0[JT], b2[JT], a0[JT], a2[JT];
+    int64_t bm[JT], am[JT];
 #pragma unroll
-    for (int i = 0; i < HS_JOBS; i++) {
+    for (int i = 0; i < JT; i++) { b0[i] = b2[i] = a0[i] = a2[i] = 0; bm[i] = am[i] = 0; }
+    __syncthreads();
+    const size_t kstride = (size_t)M << logN, koff = ((size_t)mi << logN) + n;
+    // lane t (mod 16) keeps term t's key address and Galois element: the loop then picks them with a lane read instead
+    // of a scalar load from the argument block, whose latency every step would wait for
+    uint32_t kp_lo = 0, kp_hi = 0, g_lane = 1;
+#pragma unroll
+    for (int tt = 0; tt < HS_TERMS; tt++) {
+        if ((threadIdx.x & (HS_TERMS - 1)) == (uint32_t)tt) {
+            kp_lo = (uint32_t)(uintptr_t)a.evk[tt]; kp_hi = (uint32_t)((uintptr_t)a.evk[tt] >> 32); g_lane = a.g[tt];
+        }
+    }
+    auto key_of = [&](uint32_t term) {
+        const uint32_t lo = __builtin_amdgcn_readlane(kp_lo, term), hi = __builtin_amdgcn_readlane(kp_hi, term);
+        return (const u64 __attribute__((address_space(1)))*)(((uintptr_t)hi << 32) | lo);   // a global, not a generic, address
+    };
+    // Software pipeline, pinned with scheduling barriers (left alone, the compiler issues every LDS read right before its
+    // use and waits for it).  The register tile is worked in two halves: while one half's products run, the digit values
+    // of the other half - of this pair, then of the next pair - are on their way from LDS; the key values of a pair are
+    // requested HSL_RING pairs ahead.  Past the end the last key pair is requested again and its products are switched
+    // off, so that the loop body has no branch around a load.
+    constexpr int HA = (JT + 1) / 2, HB = JT - HA;
+    u64 kb[HSL_RING], ka[HSL_RING], dA[HA], dB[HB > 0 ? HB : 1];
+    uint32_t tp = 0, jp = 0, pending = 0;
+    auto request_key = [&](u64& kbu, u64& kau) {
+        const bool more = tp < a.T;
+        const auto e = key_of(more ? tp : a.T - 1) + (size_t)(2 * (more ? jp : beta - 1)) * kstride + koff;
+        kbu = e[0]; kau = e[kstride];
+        if (more && ++jp == beta) { jp = 0; tp++; }
+    };
+    // (t, j) = the pair whose digits are read next, lsrc = where this thread's value of term t sits in its tile
+    uint32_t t = 0, j = 0;
+    auto lsrc_of = [&](uint32_t term) {
+        return (threadIdx.x & ~15u) | (galois_src_ks(n, __builtin_amdgcn_readlane(g_lane, term < a.T ? term : 0), logN) & 15u);
+    };
+    uint32_t lsrc = lsrc_of(0);
+    auto read_a = [&]() {
+        const u64* dj = dig + (size_t)j * a.J * KS_THREADS + lsrc;
+#pragma unroll
+        for (int i = 0; i < HA; i++) dA[i] = dj[((uint32_t)i < a.J ? i : 0) * KS_THREADS];
+    };
+    auto read_b = [&]() {
+        const u64* dj = dig + (size_t)j * a.J * KS_THREADS + lsrc;
+#pragma unroll
+        for (int i = 0; i < HB; i++) dB[i] = dj[((uint32_t)(HA + i) < a.J ? HA + i : 0) * KS_THREADS];
+    };
+    // the middle sum formed (it is below 2^64, so wrap-around arithmetic gives it exactly), carries moved up (low and
+    // middle sums back below 2^h), the high sum, which stays below 100q, reduced, and the signed sum set to
+    // middle - low - high again: the value of the three sums together is unchanged modulo q
+    auto fold1 = [&](u64& lo, int64_t& mid_s, u64& hi) {
+        u64 mid = (u64)mid_s + lo + hi;
+        mid += lo >> h; lo &= lo_h;
+        hi = reduce_small(hi + (mid >> h), m.q, m.bits, mrec); mid &= lo_h;
+        mid_s = (int64_t)(mid - lo - hi);
+    };
+    auto fold = [&]() {
+#pragma unroll
+        for (int i = 0; i < JT; i++) { fold1(b0[i], bm[i], b2[i]); fold1(a0[i], am[i], a2[i]); }
+        pending = 0;
+    };
+    // kbd = kb1 - kb0, kad = ka1 - ka0 (signed)
+    auto mac = [&](int i, u64 d, uint32_t kb0, uint32_t kb1, int32_t kbd, uint32_t ka0, uint32_t ka1, int32_t kad) {
+        const uint32_t d0 = (uint32_t)d, d1 = (uint32_t)(d >> 32);
+        const int32_t dd = (int32_t)(d0 - d1);
+        b0[i] += (u64)d0 * kb0; b2[i] += (u64)d1 * kb1; bm[i] += (int64_t)dd * kbd;
+        a0[i] += (u64)d0 * ka0; a2[i] += (u64)d1 * ka1; am[i] += (int64_t)dd * kad;
+    };
+    auto step = [&](u64& kbu, u64& kau, bool valid) {
+        read_b();                                                   // the second half of this pair's digits
+        __builtin_amdgcn_sched_barrier(0);
+        const u64 kbv = valid ? kbu : 0, kav = valid ? kau : 0;     // a step past the end adds nothing
+        const uint32_t kb0 = (uint32_t)(kbv & lo_h), kb1 = (uint32_t)(kbv >> h);
+        const uint32_t ka0 = (uint32_t)(kav & lo_h), ka1 = (uint32_t)(kav >> h);
+        const int32_t kbd = (int32_t)(kb1 - kb0), kad = (int32_t)(ka1 - ka0);
+#pragma unroll
+        for (int i = 0; i < HA; i++) mac(i, dA[i], kb0, kb1, kbd, ka0, ka1, kad);
+        __builtin_amdgcn_sched_barrier(0);
+        if (++j == beta) { j = 0; t++; lsrc = lsrc_of(t); }
+        read_a();                                                   // the first half of the next pair's digits
+        request_key(kbu, kau);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < HB; i++) mac(HA + i, dB[i], kb0, kb1, kbd, ka0, ka1, kad);
+        pending++;
+    };
+    const uint32_t total = a.T * beta;
+#pragma unroll
+    for (int u = 0; u < HSL_RING; u++) request_key(kb[u], ka[u]);
+    read_a();
+    for (uint32_t it = 0; it < total; it += HSL_RING) {  // HSL_RING steps per trip, none of them conditional
+        if (pending + HSL_RING > period) fold();
+#pragma unroll
+        for (int u = 0; u < HSL_RING; u++) step(kb[u], ka[u], it + u < total);
+    }
+    fold();
+#pragma unroll
+    for (int i = 0; i < JT; i++) {
         if ((uint32_t)i < a.J) {
-            acc[(size_t)(2 * i) * cstride + ro] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
-            acc[(size_t)(2 * i + 1) * cstride + ro] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
+            const u64 b1 = (u64)bm[i] + b0[i] + b2[i], a1 = (u64)am[i] + a0[i] + a2[i];
+            const u64 vb = barrett128((u128)b0[i] + ((u128)b1 << h) + ((u128)b2[i] << (2 * h)), m.q, m.mu, m.bits);
+            const u64 va = barrett128((u128)a0[i] + ((u128)a1 << h) + ((u128)a2[i] << (2 * h)), m.q, m.mu, m.bits);
+            u64* o0 = acc + (size_t)(2 * i) * cstride + ro;
+            u64* o1 = acc + (size_t)(2 * i + 1) * cstride + ro;
+            *o0 = init ? vb : addmod(vb, *o0, m.q);
+            *o1 = init ? va : addmod(va, *o1, m.q);
         }
     }
 }
@@ -1075,7 +1170,8 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
             hc.T = std::min<uint32_t>(HE_MAX_KS_JOBS, T - t0);
             for (uint32_t t = 0; t < hc.T; t++) hc.g[t] = gs[t0 + t];
             for (uint32_t j = 0; j < nb; j++) hc.add[j] = t0 == 0 ? srcs[j0 + j].s0 : hc.s0[j];
-            hipLaunchKernelGGL(hoist_c0_sum_kernel, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
+            if (local) hipLaunchKernelGGL(hoist_c0_sum_kernel<true>, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
+            else hipLaunchKernelGGL(hoist_c0_sum_kernel<false>, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
             HE_HIP(c, hipGetLastError());
         }
         c->cnt.automorph += (uint64_t)nb * T * L1;
@@ -1094,10 +1190,28 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
             hi.J = nb; hi.T = std::min<uint32_t>(HS_TERMS, T - t0);
             for (uint32_t t = 0; t < hi.T; t++) { hi.evk[t] = evks[t0 + t]; hi.g[t] = gs[t0 + t]; }
             for (uint32_t j = 0; j < nb; j++) { hi.raised[j] = raised + (size_t)j * beta * R * N; hi.own[j] = srcs[j0 + j].c1; }
-            if (local)
-                hipLaunchKernelGGL(hoisted_sum_ip_local_kernel, dim3(N / KS_THREADS, R), dim3(KS_THREADS), 0, c->stream, hi, acc, c->d_mc,
-                                   c->logN, R, beta, c->M, level, c->nq, c->alpha, t0 == 0 ? 1u : 0u);
-            else
+            if (local) {
+                // limbs of moduli wider than 54 bits (bound by arithmetic: they fold every 7 pairs) spread evenly among the
+                // others (bound by the key reads), so that both kinds are resident together
+                LimbSel sel;
+                {
+                    uint32_t wide[HE_MAX_MODULI], narrow[HE_MAX_MODULI], nw = 0, nn = 0, iw = 0, in = 0;
+                    for (uint32_t r = 0; r < R; r++) {
+                        if (c->h_mc[r <= level ? r : c->nq + (r - level - 1)].bits > 54) wide[nw++] = r; else narrow[nn++] = r;
+                    }
+                    for (uint32_t i = 0; i < R; i++) {
+                        // the i-th slot goes to a wide limb when that keeps wide limbs at nw/R of the slots so far
+                        if (iw < nw && (in == nn || (uint64_t)iw * R <= (uint64_t)i * nw)) sel.r[i] = wide[iw++];
+                        else sel.r[i] = narrow[in++];
+                    }
+                }
+                const dim3 grid(N / KS_THREADS, R), blk(KS_THREADS);
+                const uint32_t init = t0 == 0 ? 1u : 0u;
+#define HSL_LAUNCH(JT) hipLaunchKernelGGL(hoisted_sum_ip_local_kernel<JT>, grid, blk, (size_t)nb * beta * KS_THREADS * sizeof(u64), c->stream, hi, sel, acc, c->d_mc, c->logN, R, beta, \
+                                          c->M, level, c->nq, c->alpha, init)
+                if (nb <= 1) HSL_LAUNCH(1); else if (nb <= 2) HSL_LAUNCH(2); else if (nb <= 4) HSL_LAUNCH(4); else HSL_LAUNCH(8);
+#undef HSL_LAUNCH
+            } else
                 hipLaunchKernelGGL(hoisted_sum_ip_kernel, dim3(N / KS_THREADS, R), dim3(KS_THREADS), 0, c->stream, hi, acc, c->d_mc, c->logN, R,
                                    beta, c->M, level, c->nq, c->alpha, t0 == 0 ? 1u : 0u);
             HE_HIP(c, hipGetLastError());
