@@ -183,6 +183,9 @@ struct TransformDesc {
                                  // consumers' 128-bit accumulations leave room; internal buffers only
     uint32_t only_pass;          // N = 2^16 path: 0 = both passes; 1 = the first pass only (inverse: rows, reading the
                                  // sources; forward: columns); 2 = the second pass only, in place at dst
+    uint32_t rescale_from;       // N = 2^16 path, forward only: l + 1 when the sources are coefficient-form limbs of
+                                 // modulus l and limb i (modulus r) transforms ((t + h) mod q_l) mod q_r - (h mod q_r),
+                                 // h = floor(q_l / 2): the rounding term of Rescale, negated; 0 = sources as they are
 };
 
 // N = 2^16 latency path: [inverse column pass -> basis conversion -> forward column pass] of several groups in one launch.

@@ -1322,14 +1322,19 @@ int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint
         t.mod_idx = mods.data(); t.src_seg = seg.data(); t.src_limb = lim.data();
         int32_t rc = launch_transform(ctx, t);
         if (rc != HE_OK) return rc;
-        dim3 grid(N / KS_THREADS, level, 2 * nb), block(KS_THREADS);
-        hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level, 1u);
-        HE_HIP(ctx, hipGetLastError());
         // forward transform of -delta whose epilogue writes (c - (-delta)) * q_l^-1: the input limb plays the stored
-        // accumulator (component stride level+1 limbs), q_l^-1 mod q_r the constant of the final product
+        // accumulator (component stride level+1 limbs), q_l^-1 mod q_r the constant of the final product.  At N = 2^16
+        // the first pass forms -delta from the dropped limb's coefficients as it reads them; otherwise a kernel does.
         const uint32_t total = 2 * nb * level;
+        const bool fused_delta = ctx->logN == 16;
         std::vector<uint32_t> dm(total);
-        for (uint32_t i = 0; i < total; i++) dm[i] = i % level;
+        std::vector<uint16_t> dsrc(total);
+        for (uint32_t i = 0; i < total; i++) { dm[i] = i % level; dsrc[i] = (uint16_t)(i / level); }
+        if (!fused_delta) {
+            dim3 grid(N / KS_THREADS, level, 2 * nb), block(KS_THREADS);
+            hipLaunchKernelGGL(rescale_delta_kernel, grid, block, 0, ctx->stream, tmp, delta, ctx->d_mc, ctx->logN, level, 1u);
+            HE_HIP(ctx, hipGetLastError());
+        }
         ModDownEpilogue ep = {};
         ep.acc = cts[b0]; ep.R = L1; ep.L1 = level;
         ep.pinv = ctx->d_qlinv + (size_t)level * ctx->nq; ep.pinv_sh = ctx->d_qlinv_sh + (size_t)level * ctx->nq;
@@ -1341,6 +1346,7 @@ int32_t rescale_batch(he_ctx* ctx, const u64* const* cts, u64* const* outs, uint
         TransformDesc f = {};
         f.fwd = true; f.seg[0] = delta; f.n_seg = 1; f.dst = delta; f.n = total; f.mod_idx = dm.data(); f.ep = &ep;
         f.lazy_out = true;
+        if (fused_delta) { f.seg[0] = tmp; f.src_limb = dsrc.data(); f.rescale_from = level + 1; }
         rc = launch_transform(ctx, f);
         if (rc != HE_OK) return rc;
         ctx->cnt.rescale += nb;

@@ -184,6 +184,7 @@ static int32_t run_transform(he_ctx* ctx, u64* d, const uint32_t* mod_idx, uint3
 // Generic ring sizes: the first pass reads the source limbs where they are; the ModDown epilogue runs as
 // its own kernel.
 static int32_t launch_transform_generic(he_ctx* ctx, const TransformDesc& d) {
+    if (d.rescale_from) return he_fail(ctx, HE_ERR_BADARG, "transform: the Rescale rounding term is only read on the N = 2^16 path");
     TileSrc ts;
     for (uint32_t s = 0; s < HE_MAX_SEGS; s++) ts.seg[s] = s < d.n_seg ? d.seg[s] : d.seg[0];
     for (uint32_t i = 0; i < d.n; i++) {

@@ -26,6 +26,7 @@
 
 struct Ntt16Args {
     uint32_t lazy;      // forward, last pass: leave outputs unreduced where LAZY_Q_MAX allows
+    uint32_t rs_mod;    // forward, first pass reading the Rescale rounding term: modulus index of the dropped limb
     u64* dst;           // limb i is written / transformed in place at dst + i*N
     const ModConst* mc;
     const u64* tw;      // [M][N] forward or inverse twiddles
@@ -139,13 +140,20 @@ __device__ __forceinline__ void ip_accumulate(u128 (&sum)[4], const u64* __restr
 
 // ---------------------------------------------------------------- forward
 // Pass A: workgroup = 16 adjacent columns x all 256 rows of one limb; tid = t*16 + col.
-template <bool WIDE>
+// RS: the source is the coefficient form of the limb that Rescale drops (modulus ml); what is transformed is the negated
+// rounding term ((v + h) mod q_l) mod q - (h mod q), h = floor(q_l / 2), of this limb's modulus m.
+template <bool WIDE, bool RS>
 __device__ __forceinline__ void fwd_pass_a(const u64* __restrict__ src, u64* __restrict__ dst, u64* sm, const u64* tw,
-                                           const u64* tw_sh, uint32_t tile, u64 q, u64 q4) {
+                                           const u64* tw_sh, uint32_t tile, u64 q, u64 q4, const ModConst& m, const ModConst& ml) {
     const uint32_t t = threadIdx.x >> 4, cl = threadIdx.x & 15, c = tile * 16 + cl;
     u64 x[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = src[(size_t)(t + 16 * k) * 256 + c];
+    if (RS) {
+        const u64 h = ml.q >> 1, hr = barrett64(h, m.q, m.mu, m.bits);
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = submod(barrett64(addmod(x[k], h, ml.q), m.q, m.mu, m.bits), hr, q);
+    }
     fwd_block4<WIDE>(x, tw, tw_sh, 0, 0, q, q4);
     // row r of the tile sits at (r + (r >> 4)) * 16: one spare row per 16 keeps the four row groups
     // that a wavefront reads back at once on different banks
@@ -330,18 +338,20 @@ __device__ __forceinline__ void fwd_pass_b(u64* __restrict__ data, u64* sm, cons
     }
 }
 
+template <bool RS>
 __global__ __launch_bounds__(T16_THREADS) void ntt16_fwd_a_kernel(Ntt16Args a, LimbList ll, SrcList sl) {
     __shared__ u64 sm[272 * 16];
     const uint32_t limb = blockIdx.x >> 4, tile = blockIdx.x & 15;
     const uint32_t mi = ll.mod[limb];
     if (mi == 0xFFu) return;
     const ModConst m = a.mc[mi];
+    const ModConst ml = a.mc[RS ? a.rs_mod : mi];
     const u64* src = src_of(sl, limb);
     u64* dst = a.dst + ((size_t)limb << 16);
     const u64* tw = a.tw + ((size_t)mi << 16);
     const u64* tw_sh = a.tw_sh + ((size_t)mi << 16);
-    if (m.bits > 57) fwd_pass_a<true>(src, dst, sm, tw, tw_sh, tile, m.q, 2 * m.q2);
-    else fwd_pass_a<false>(src, dst, sm, tw, tw_sh, tile, m.q, 2 * m.q2);
+    if (m.bits > 57) fwd_pass_a<true, RS>(src, dst, sm, tw, tw_sh, tile, m.q, 2 * m.q2, m, ml);
+    else fwd_pass_a<false, RS>(src, dst, sm, tw, tw_sh, tile, m.q, 2 * m.q2, m, ml);
 }
 
 template <int EPI>
@@ -733,6 +743,9 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
     Ntt16Args a;
     a.dst = d.dst; a.mc = ctx->d_mc;
     a.lazy = (d.fwd && d.lazy_out) ? 1u : 0u;
+    a.rs_mod = d.rescale_from ? d.rescale_from - 1 : 0;
+    if (d.rescale_from && (!d.fwd || d.rescale_from > ctx->M || d.only_pass == 2))
+        return he_fail(ctx, HE_ERR_BADARG, "transform: the Rescale rounding term is read by the first pass of a forward transform");
     a.tw = fwd ? ctx->d_tw : ctx->d_itw;
     a.tw_sh = fwd ? ctx->d_tw_sh : ctx->d_itw_sh;
     dim3 grid(n * 16), block(T16_THREADS);
@@ -760,7 +773,8 @@ int32_t launch_transform16(he_ctx* ctx, const TransformDesc& d) {
             HE_HIP(ctx, hipEventCreate(&e1));
             HE_HIP(ctx, hipEventRecord(e0, ctx->stream));
         }
-        if (fwd && pass == 0) hipLaunchKernelGGL(ntt16_fwd_a_kernel, grid, block, 0, ctx->stream, a, ll, sl);
+        if (fwd && pass == 0 && d.rescale_from) hipLaunchKernelGGL(ntt16_fwd_a_kernel<true>, grid, block, 0, ctx->stream, a, ll, sl);
+        else if (fwd && pass == 0) hipLaunchKernelGGL(ntt16_fwd_a_kernel<false>, grid, block, 0, ctx->stream, a, ll, sl);
         else if (fwd && d.ep && d.ep->fused && d.ep->beta == 1 && d.ep->n_terms == 0)      // single digit: its own instantiation
             hipLaunchKernelGGL(ntt16_fwd_b_kernel<3>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
         else if (fwd && d.ep && d.ep->fused) hipLaunchKernelGGL(ntt16_fwd_b_kernel<2>, grid_rows, block, 0, ctx->stream, a, ll, rs, *d.ep);
