@@ -953,13 +953,13 @@ __global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_kernel(HoistIp a, u
 // into LDS and each term reads them back permuted, so that the only global loads left per (term, digit) are the two key
 // values.  LDS: J*beta*2 KiB.  grid (N/256, number of limbs in sel).
 //
-// Products are taken in halves, three multiplications each.  The 32x32+64-bit multiply-add is the slow instruction here
-// (a quarter of the rate of the others), so their count is what bounds the kernel.  With h = 27 for moduli of at most 54
-// bits and h = 30 for wider ones (up to 60 bits), a canonical digit value d = d1*2^h + d0 and a canonical key value
+// Products are taken in halves, three multiplications each: the kernel is bound by its vector instructions (measured:
+// they issue nearly all the time with three wavefronts per SIMD), so their count per product is what matters.  With
+// h = 27 for moduli of at most 54 bits and h = 30 for wider ones (up to 60 bits), a canonical digit value d = d1*2^h + d0 and a canonical key value
 // k = k1*2^h + k0 give d*k = d0*k0 + (d0*k1 + d1*k0)*2^h + d1*k1*2^2h with d0*k1 + d1*k0 = (d0-d1)*(k1-k0) + d0*k0 + d1*k1.
 // Three 64-bit accumulators per output take the sums of d0*k0, of d1*k1 and (signed) of (d0-d1)*(k1-k0) directly from
-// the multiply-adds, with no carries: three instructions per product, against four multiply-adds and ten others for a
-// 128-bit accumulation.  Every partial product is below 2^2h in magnitude, so after `period` pairs (32 for h = 27, 6
+// the 32x32+64-bit multiply-adds, with no carries: three instructions per product, against four multiply-adds and ten
+// others (carries, moves) for a 128-bit accumulation.  Every partial product is below 2^2h in magnitude, so after `period` pairs (32 for h = 27, 6
 // for h = 30: (period+1)*2^2h < 2^63, and period*2^(2*bits-2h) + q < 100q) the middle sum is formed, the carries of the
 // low and middle sums move up, the high sum is reduced modulo q, and the signed accumulator is set to what keeps the
 // identity; the three sums are put together and reduced once at the end.  Digits are made canonical (the forward

@@ -1,6 +1,7 @@
 """GPU parity for the rotate-and-sum of he_conv2d evaluated as one hoisted sum of rotations per output
 (hoisted_ras: one ModUp and one ModDown per output, keys shared by the outputs): bit-exact against the oracle on a
-small ring, on a two-pass ring, with 32 channel blocks (the form that gathers from memory), at N = 2^16 at level 5
+small ring, on a two-pass ring, with 32 channel blocks (the form that gathers from memory), with 57/59-bit moduli and a
+single output, at N = 2^16 at level 5
 (single digit) and on the ResNet-20 layer at level 23 (three digits, eight outputs in one launch set), with operation
 counts; and
 he_rotate_sum on one ciphertext repeated (terms that rotate the same polynomial share its ModUp)."""
@@ -76,6 +77,13 @@ def test_thirty_two_channel_blocks_gathered_form():
     # memory instead of from LDS; 31 terms take two launches of at most 16 (the second continues the accumulators)
     prm = toy_params(logN=12, q_bits=40, nq=4, p_bits=41, np_=2, dnum=2, scale=2.0 ** 30, hamming=32, seed=83)
     _run(prm, C_a=32, H=4, W=4, c_out=8, level=3, w_std=0.1, tol=1e-3)
+
+
+def test_moduli_of_57_and_59_bits_single_output():
+    # moduli wider than 54 bits take the 30-bit halves of the LDS-staged inner products (with their carry moves every
+    # six products); one output ciphertext is the smallest register tile
+    prm = toy_params(logN=11, q_bits=57, nq=3, p_bits=59, np_=2, dnum=2, scale=2.0 ** 45, hamming=32, seed=86)
+    _run(prm, C_a=16, H=4, W=4, c_out=4, level=2, w_std=0.1, tol=1e-3)
 
 
 def test_n65536_level5_single_digit():
