@@ -188,9 +188,10 @@ int32_t he_automorph(he_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, const u
 
 /* Register the evaluation key that switches sigma_g(s) -> s (galois_elt = g) or s^2 -> s
  * (galois_elt = 0).  d_evk: [dnum][2][nq+np][N] NTT form, component 0 = b, 1 = a, limb order
- * q_0..q_L, p_0..p_{k-1}; digit j carries P*s' on the q-limbs j*alpha..(j+1)*alpha-1.  The
- * caller keeps the buffer alive and unchanged while it is registered; registering again
- * replaces the pointer. */
+ * q_0..q_L, p_0..p_{k-1}; digit j carries P*s' on the q-limbs j*alpha..(j+1)*alpha-1.  Every
+ * residue must be canonical (below its modulus): the inner products split key values in halves
+ * and do not reduce them first; the buffer is not checked.  The caller keeps the buffer alive
+ * and unchanged while it is registered; registering again replaces the pointer. */
 int32_t he_evk_register(he_ctx* ctx, uint32_t galois_elt, const uint64_t* d_evk);
 
 /* Hybrid key switching of one polynomial (the inner step of CRot and of relinearisation;
