@@ -376,45 +376,44 @@ struct RaMac {
     uint32_t n_in, n_taps, init;
 };
 
-// MulFilter&Sum_ci for up to 9 taps: every input coefficient is loaded once and multiplied into the
-// accumulator of each tap; 128-bit sums, one Barrett step per 8 inputs.  init = 0 continues from
-// the accumulators' current (canonical) contents.  grid: (N/256, L1).
+// MulFilter&Sum_ci for up to 9 taps: the coefficients of the (at most NI) inputs are loaded once and kept in registers;
+// each tap's accumulator is then their sum of products with that tap's plaintexts, in 128 bits with one Barrett step
+// per 8 inputs, so that only two sums are live at a time.  init = 0 continues from the accumulators' current
+// (canonical) contents.  grid: (N/256, L1).
+template <int NI>
 __global__ __launch_bounds__(CV_THREADS) void ra_mac9_kernel(RaMac a, const ModConst* mc, uint32_t logN, uint32_t L1) {
     const uint32_t n = blockIdx.x * CV_THREADS + threadIdx.x;
     const uint32_t limb = blockIdx.y;
     const ModConst m = mc[limb];
     const size_t o0 = ((size_t)limb << logN) + n, o1 = ((size_t)(limb + L1) << logN) + n;
-    u128 s0[9], s1[9];
+    u64 c0[NI], c1[NI];
 #pragma unroll
-    for (uint32_t t = 0; t < 9; t++) {
-        s0[t] = (!a.init && t < a.n_taps) ? a.acc[t][o0] : 0;
-        s1[t] = (!a.init && t < a.n_taps) ? a.acc[t][o1] : 0;
+    for (int i = 0; i < NI; i++) {
+        c0[i] = (uint32_t)i < a.n_in ? a.ct[i][o0] : 0;
+        c1[i] = (uint32_t)i < a.n_in ? a.ct[i][o1] : 0;
     }
-    for (uint32_t i = 0; i < a.n_in; i++) {
-        if (i && (i & 7u) == 0) {
+    for (uint32_t t = 0; t < a.n_taps; t++) {
+        u128 s0 = a.init ? 0 : a.acc[t][o0], s1 = a.init ? 0 : a.acc[t][o1];
 #pragma unroll
-            for (uint32_t t = 0; t < 9; t++) {
-                s0[t] = barrett128(s0[t], m.q, m.mu, m.bits);
-                s1[t] = barrett128(s1[t], m.q, m.mu, m.bits);
+        for (int i = 0; i < NI; i++) {
+            if (i == 8) {
+                s0 = barrett128(s0, m.q, m.mu, m.bits);
+                s1 = barrett128(s1, m.q, m.mu, m.bits);
             }
-        }
-        const u64 c0 = a.ct[i][o0], c1 = a.ct[i][o1];
-#pragma unroll
-        for (uint32_t t = 0; t < 9; t++) {
-            if (t < a.n_taps) {
+            if ((uint32_t)i < a.n_in) {
                 const u64 p = a.pt[i * 9 + t][o0];
-                s0[t] += (u128)c0 * p;
-                s1[t] += (u128)c1 * p;
+                s0 += (u128)c0[i] * p;
+                s1 += (u128)c1[i] * p;
             }
         }
+        a.acc[t][o0] = barrett128(s0, m.q, m.mu, m.bits);
+        a.acc[t][o1] = barrett128(s1, m.q, m.mu, m.bits);
     }
-#pragma unroll
-    for (uint32_t t = 0; t < 9; t++) {
-        if (t < a.n_taps) {
-            a.acc[t][o0] = barrett128(s0[t], m.q, m.mu, m.bits);
-            a.acc[t][o1] = barrett128(s1[t], m.q, m.mu, m.bits);
-        }
-    }
+}
+
+static void launch_ra_mac9(he_ctx* ctx, const RaMac& a, dim3 grid, dim3 block, uint32_t L1) {
+    if (a.n_in <= 8) hipLaunchKernelGGL(ra_mac9_kernel<8>, grid, block, 0, ctx->stream, a, ctx->d_mc, ctx->logN, L1);
+    else hipLaunchKernelGGL(ra_mac9_kernel<RA_IN_PER_LAUNCH>, grid, block, 0, ctx->stream, a, ctx->d_mc, ctx->logN, L1);
 }
 
 struct SumList {
@@ -578,7 +577,7 @@ extern "C" int32_t he_raconv(he_ctx* ctx, const he_raconv_plan* plan, const uint
                     a.ct[i] = (const u64*)h_d_ct_in[i0 + i];
                     for (uint32_t t = 0; t < a.n_taps; t++) a.pt[i * 9 + t] = (const u64*)plan->h_d_weights[(size_t)(i0 + i) * taps + t0 + t];
                 }
-                hipLaunchKernelGGL(ra_mac9_kernel, grid, block, 0, ctx->stream, a, ctx->d_mc, ctx->logN, L1);
+                launch_ra_mac9(ctx, a, grid, block, L1);
                 HE_HIP(ctx, hipGetLastError());
             }
         }
@@ -837,7 +836,7 @@ extern "C" int32_t he_ca_ra_block(he_ctx* ctx, const he_block_plan* plan, const 
                             for (uint32_t t = 0; t < a.n_taps; t++)
                                 a.pt[i * 9 + t] = (const u64*)plan->h_d_w_ra[((size_t)l * n_ra + j0 + i0 + i) * taps + t0 + t];
                         }
-                        hipLaunchKernelGGL(ra_mac9_kernel, grid, block, 0, ctx->stream, a, ctx->d_mc, ctx->logN, lo + 1);
+                        launch_ra_mac9(ctx, a, grid, block, lo + 1);
                         HE_HIP(ctx, hipGetLastError());
                     }
             ctx->cnt.mac += (uint64_t)g * n_ca * taps;
