@@ -383,7 +383,20 @@ def main():
         ctx.he_ws_reserve(ctx.he_ws_query_conv2d(16, 32, 32, 2, 3, level, 8, hoisted_ras=True))
         extras["conv2d_hoisted_ras_ms"] = round(
             timed(lambda: ctx.he_conv2d(16, 32, 32, 2, 3, level, weights, cts[0], conv_out, hoisted_ras=True), reps=3), 3)
-        # the same layer on a 6-limb ciphertext (level 5, where the paper's networks run their convolutions)
+        # the 32 -> 32 channel layer on 16x16 images of ResNet-20's second stage (C_a = 32, R = 4, 8 output
+        # ciphertexts): 5 rotate-and-sum rounds in the paper's order, or one hoisted sum of 31 rotations per output
+        # (two launches of the inner products: 16 + 15 terms)
+        steps32 = sorted(set(((dy * 16 + dx) * 4) % (N // 2) for dy in (-1, 0, 1) for dx in (-1, 0, 1)) - {0}
+                         | {1024 * i for i in range(1, 32)})
+        for s in steps32:
+            if s not in keys:
+                keys[s] = uniform_dev(torch, gen, prm.moduli, N, lead=(prm.dnum, 2))
+                ctx.he_evk_register(ctx.galois_elt(s), keys[s])
+        ctx.he_ws_reserve(ctx.he_ws_query_conv2d(32, 16, 16, 4, 3, level, 8, hoisted_ras=True))
+        extras["conv2d_32ch_ms"] = round(timed(lambda: ctx.he_conv2d(32, 16, 16, 4, 3, level, weights, cts[0], conv_out), reps=2), 3)
+        extras["conv2d_32ch_hoisted_ras_ms"] = round(
+            timed(lambda: ctx.he_conv2d(32, 16, 16, 4, 3, level, weights, cts[0], conv_out, hoisted_ras=True), reps=3), 3)
+        # the 16 -> 16 layer on a 6-limb ciphertext (level 5, where the paper's networks run their convolutions)
         lo_w = [w[:6] for w in weights]
         lo_in = cts[0][:, :6, :].contiguous()
         lo_outs = [torch.empty((2, 5, N), dtype=torch.uint64, device="cuda") for _ in range(8)]

@@ -857,32 +857,25 @@ struct HoistC0 {
     uint32_t g[HE_MAX_KS_JOBS];
     uint32_t T;
 };
-// LOCAL: every Galois element moves values only inside aligned blocks of 16 positions (see hoisted_sum_ip_local_kernel):
-// the work group's 256 values are read once into LDS and gathered from there.
-template <bool LOCAL>
+// Every Galois element moves values only inside aligned blocks of 256 positions (see hoisted_sum_ip_local_kernel): the
+// work group's 256 values are read once into LDS and gathered from there.
 __global__ __launch_bounds__(KS_THREADS) void hoist_c0_sum_kernel(HoistC0 a, const ModConst* mc, uint32_t logN) {
-    __shared__ u64 tile[LOCAL ? KS_THREADS : 1];
+    __shared__ u64 tile[KS_THREADS];
     const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y, j = blockIdx.z;
     const u64 q = mc[r].q;
     const size_t o = ((size_t)r << logN) + n;
     const u64* c0 = a.c0[j] + ((size_t)r << logN);
     u64 v = a.add[j] ? a.add[j][o] : 0;
-    if (LOCAL) {
-        tile[threadIdx.x] = c0[n];
-        __syncthreads();
-        for (uint32_t t = 0; t < a.T; t++) v = addmod(v, tile[(threadIdx.x & ~15u) | (galois_src_ks(n, a.g[t], logN) & 15u)], q);
-    } else {
-        for (uint32_t t = 0; t < a.T; t++) v = addmod(v, c0[galois_src_ks(n, a.g[t], logN)], q);
-    }
+    tile[threadIdx.x] = c0[n];
+    __syncthreads();
+    for (uint32_t t = 0; t < a.T; t++) v = addmod(v, tile[galois_src_ks(n, a.g[t], logN) & (KS_THREADS - 1)], q);
     a.s0[j][o] = v;
 }
 
 // Inner products of a hoisted sum for up to HS_JOBS ciphertexts at once, register-tiled: a thread owns one point of
 // one raised-basis limb for all the ciphertexts and both components; per (term, digit) it loads the two key values
-// once and one gathered digit value per ciphertext, and feeds 2*J multiply-accumulates.  Against one work group per
-// (ciphertext, component) that is J/(J+2)... the loads per product fall from 2 to (J+2)/(2J), which is what bounds
-// these sums (they are L2-bandwidth-bound: every term gathers other rows of the digits).
-// acc [J][2][R][N] (canonical); init = 0 continues from its contents (more than HS_TERMS terms).  grid (N/256, R).
+// once and one digit value per ciphertext, and feeds 2*J multiply-accumulates.
+// acc [J][2][R][N] (canonical); init = 0 continues from its contents (more than HS_TERMS terms).
 #define HS_JOBS 8
 #define HS_TERMS 16
 struct HoistIp {
@@ -892,66 +885,14 @@ struct HoistIp {
     uint32_t g[HS_TERMS];
     uint32_t J, T;
 };
-__global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_kernel(HoistIp a, u64* __restrict__ acc, const ModConst* mc, uint32_t logN,
-                                                                    uint32_t R, uint32_t beta, uint32_t M, uint32_t level, uint32_t nq,
-                                                                    uint32_t alpha, uint32_t init) {
-    const uint32_t n = blockIdx.x * KS_THREADS + threadIdx.x, r = blockIdx.y;
-    const uint32_t mi = r <= level ? r : nq + (r - level - 1);
-    const ModConst m = mc[mi];
-    const size_t ro = ((size_t)r << logN) + n, cstride = (size_t)R << logN;
-    u128 s0[HS_JOBS], s1[HS_JOBS];
-    u64 t0[HS_JOBS], t1[HS_JOBS];
-#pragma unroll
-    for (int i = 0; i < HS_JOBS; i++) {
-        s0[i] = s1[i] = 0;
-        t0[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i) * cstride + ro] : 0;
-        t1[i] = (!init && (uint32_t)i < a.J) ? acc[(size_t)(2 * i + 1) * cstride + ro] : 0;
-    }
-    uint32_t pending = 0;
-    for (uint32_t t = 0; t < a.T; t++) {
-        const uint32_t g = a.g[t];
-        const uint32_t src = g == 1 ? n : galois_src_ks(n, g, logN);
-        const u64* evk = a.evk[t];
-        for (uint32_t j = 0; j < beta; j++) {
-            if (pending == 8) {          // eight products of (possibly unreduced) digits are what 128 bits hold
-#pragma unroll
-                for (int i = 0; i < HS_JOBS; i++) {
-                    t0[i] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
-                    t1[i] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
-                    s0[i] = s1[i] = 0;
-                }
-                pending = 0;
-            }
-            const u64 kb = evk[((size_t)((j * 2 + 0) * M + mi) << logN) + n];
-            const u64 ka = evk[((size_t)((j * 2 + 1) * M + mi) << logN) + n];
-            const bool own_digit = r <= level && r / alpha == j;
-            const size_t doff = own_digit ? ((size_t)r << logN) + src : ((size_t)(j * R + r) << logN) + src;
-#pragma unroll
-            for (int i = 0; i < HS_JOBS; i++) {
-                if ((uint32_t)i < a.J) {
-                    const u64 d = (own_digit ? a.own[i] : a.raised[i])[doff];
-                    s0[i] += (u128)d * kb;
-                    s1[i] += (u128)d * ka;
-                }
-            }
-            pending++;
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < HS_JOBS; i++) {
-        if ((uint32_t)i < a.J) {
-            acc[(size_t)(2 * i) * cstride + ro] = addmod(t0[i], barrett128(s0[i], m.q, m.mu, m.bits), m.q);
-            acc[(size_t)(2 * i + 1) * cstride + ro] = addmod(t1[i], barrett128(s1[i], m.q, m.mu, m.bits), m.q);
-        }
-    }
-}
 
-// The same sums when every Galois element of the list is 1 modulo 2^(logN-3): such a map moves a value only inside its
-// aligned block of 16 positions (the low logN-4 bits of the exponent index g*k + (g-1)/2 are those of k), which is
-// the case for rotations by multiples of N/32 slots - the rotate-and-sum amounts over up to 16 channel blocks.  Then a
-// work group's 256 points need exactly their own 256 values of every digit, for every term: they are loaded once
-// into LDS and each term reads them back permuted, so that the only global loads left per (term, digit) are the two key
-// values.  LDS: J*beta*2 KiB.  grid (N/256, number of limbs in sel).
+// Every Galois element of the list must be 1 modulo 2^(logN-7): such a map moves a value only inside its aligned block
+// of 256 positions (the low logN-8 bits of the exponent index g*k + (g-1)/2 are those of k, i.e. the high bits of the
+// position stay), which is the case for rotations by multiples of N/512 slots - the rotate-and-sum amounts over up to
+// 256 channel blocks (over up to 16 of them the values even stay inside aligned blocks of 16, and the LDS reads below are
+// free of bank conflicts).  Then a work group's 256 points need exactly their own 256 values of every digit, for
+// every term: they are loaded once into LDS and each term reads them back permuted, so that the only global loads left
+// per (term, digit) are the two key values.  LDS: J*beta*2 KiB.  grid (N/256, number of limbs in sel).
 //
 // Products are taken in halves, three multiplications each: the kernel is bound by its vector instructions (measured:
 // they issue nearly all the time with three wavefronts per SIMD), so their count per product is what matters.  With
@@ -960,8 +901,8 @@ __global__ __launch_bounds__(KS_THREADS) void hoisted_sum_ip_kernel(HoistIp a, u
 // Three 64-bit accumulators per output take the sums of d0*k0, of d1*k1 and (signed) of (d0-d1)*(k1-k0) directly from
 // the 32x32+64-bit multiply-adds, with no carries: three instructions per product, against four multiply-adds and ten
 // others (carries, moves) for a 128-bit accumulation.  Every partial product is below 2^2h in magnitude, so after `period` pairs (32 for h = 27, 6
-// for h = 30: (period+1)*2^2h < 2^63, and period*2^(2*bits-2h) + q < 100q) the middle sum is formed, the carries of the
-// low and middle sums move up, the high sum is reduced modulo q, and the signed accumulator is set to what keeps the
+// for h = 30: (period+3)*2^2h < 2^64, and period*2^(2*bits-2h) + 3q < 100q) the middle sum is formed, the carries of the
+// low and middle sums move up, the high sum is brought below 3q, and the signed accumulator is set to what keeps the
 // identity; the three sums are put together and reduced once at the end.  Digits are made canonical (the forward
 // transform may leave them below 69q) and split while they are staged into LDS, the low half in the low word.  JT = size
 // of the register tile: ciphertexts a.J..JT-1 repeat ciphertext 0 and are not stored.
@@ -996,10 +937,10 @@ __global__ __launch_bounds__(KS_THREADS, 3) void hoisted_sum_ip_local_kernel(Hoi
         }
     }
     // per output and component: low sum, high sum, and the signed sum bm = (middle sum) - low - high
-    u64 b0[JT], b2[JT], a0[JT], a2[JT];
-    int64_t bm[JT], am[JT];
+    // (bm is kept modulo 2^64: the middle sum it stands for is below 2^64, so wrap-around arithmetic recovers it)
+    u64 b0[JT], b2[JT], a0[JT], a2[JT], bm[JT], am[JT];
 #pragma unroll
-    for (int i = 0; i < JT; i++) { b0[i] = b2[i] = a0[i] = a2[i] = 0; bm[i] = am[i] = 0; }
+    for (int i = 0; i < JT; i++) b0[i] = b2[i] = a0[i] = a2[i] = bm[i] = am[i] = 0;
     __syncthreads();
     const size_t kstride = (size_t)M << logN, koff = ((size_t)mi << logN) + n;
     // lane t (mod 16) keeps term t's key address and Galois element: the loop then picks them with a lane read instead
@@ -1032,7 +973,7 @@ __global__ __launch_bounds__(KS_THREADS, 3) void hoisted_sum_ip_local_kernel(Hoi
     // (t, j) = the pair whose digits are read next, lsrc = where this thread's value of term t sits in its tile
     uint32_t t = 0, j = 0;
     auto lsrc_of = [&](uint32_t term) {
-        return (threadIdx.x & ~15u) | (galois_src_ks(n, __builtin_amdgcn_readlane(g_lane, term < a.T ? term : 0), logN) & 15u);
+        return galois_src_ks(n, __builtin_amdgcn_readlane(g_lane, term < a.T ? term : 0), logN) & (KS_THREADS - 1);
     };
     uint32_t lsrc = lsrc_of(0);
     auto read_a = [&]() {
@@ -1046,13 +987,13 @@ __global__ __launch_bounds__(KS_THREADS, 3) void hoisted_sum_ip_local_kernel(Hoi
         for (int i = 0; i < HB; i++) dB[i] = dj[((uint32_t)(HA + i) < a.J ? HA + i : 0) * KS_THREADS];
     };
     // the middle sum formed (it is below 2^64, so wrap-around arithmetic gives it exactly), carries moved up (low and
-    // middle sums back below 2^h), the high sum, which stays below 100q, reduced, and the signed sum set to
+    // middle sums back below 2^h), the high sum, which stays below 100q, brought below 3q, and the signed sum set to
     // middle - low - high again: the value of the three sums together is unchanged modulo q
-    auto fold1 = [&](u64& lo, int64_t& mid_s, u64& hi) {
-        u64 mid = (u64)mid_s + lo + hi;
+    auto fold1 = [&](u64& lo, u64& mid_s, u64& hi) {
+        u64 mid = mid_s + lo + hi;
         mid += lo >> h; lo &= lo_h;
-        hi = reduce_small(hi + (mid >> h), m.q, m.bits, mrec); mid &= lo_h;
-        mid_s = (int64_t)(mid - lo - hi);
+        hi = reduce_small_lazy(hi + (mid >> h), m.q, m.bits, mrec); mid &= lo_h;
+        mid_s = mid - lo - hi;
     };
     auto fold = [&]() {
 #pragma unroll
@@ -1063,8 +1004,8 @@ __global__ __launch_bounds__(KS_THREADS, 3) void hoisted_sum_ip_local_kernel(Hoi
     auto mac = [&](int i, u64 d, uint32_t kb0, uint32_t kb1, int32_t kbd, uint32_t ka0, uint32_t ka1, int32_t kad) {
         const uint32_t d0 = (uint32_t)d, d1 = (uint32_t)(d >> 32);
         const int32_t dd = (int32_t)(d0 - d1);
-        b0[i] += (u64)d0 * kb0; b2[i] += (u64)d1 * kb1; bm[i] += (int64_t)dd * kbd;
-        a0[i] += (u64)d0 * ka0; a2[i] += (u64)d1 * ka1; am[i] += (int64_t)dd * kad;
+        b0[i] += (u64)d0 * kb0; b2[i] += (u64)d1 * kb1; bm[i] += (u64)((int64_t)dd * kbd);
+        a0[i] += (u64)d0 * ka0; a2[i] += (u64)d1 * ka1; am[i] += (u64)((int64_t)dd * kad);
     };
     auto step = [&](u64& kbu, u64& kau, bool valid) {
         read_b();                                                   // the second half of this pair's digits
@@ -1097,7 +1038,7 @@ __global__ __launch_bounds__(KS_THREADS, 3) void hoisted_sum_ip_local_kernel(Hoi
 #pragma unroll
     for (int i = 0; i < JT; i++) {
         if ((uint32_t)i < a.J) {
-            const u64 b1 = (u64)bm[i] + b0[i] + b2[i], a1 = (u64)am[i] + a0[i] + a2[i];
+            const u64 b1 = bm[i] + b0[i] + b2[i], a1 = am[i] + a0[i] + a2[i];
             const u64 vb = barrett128((u128)b0[i] + ((u128)b1 << h) + ((u128)b2[i] << (2 * h)), m.q, m.mu, m.bits);
             const u64 va = barrett128((u128)a0[i] + ((u128)a1 << h) + ((u128)a2[i] << (2 * h)), m.q, m.mu, m.bits);
             u64* o0 = acc + (size_t)(2 * i) * cstride + ro;
@@ -1108,13 +1049,11 @@ __global__ __launch_bounds__(KS_THREADS, 3) void hoisted_sum_ip_local_kernel(Hoi
     }
 }
 
-// Whether the Galois elements of a hoisted sum only move values inside aligned blocks of 16 positions (see
-// hoisted_sum_ip_local_kernel).  Otherwise the register-tiled kernel gathers from memory: for each term it reads other
-// rows of all nb*beta digit limbs of the raised-basis limb it works on, and that set (nb*beta*N*8 bytes) should stay in
-// an XCD's 4 MiB L2 (measured at N = 2^16 with 8 ciphertexts: one digit 0.26 ms, three digits 1.96 ms for 15 terms).
+// Whether the Galois elements of a hoisted sum only move values inside aligned blocks of 256 positions, the tile of a
+// work group of hoisted_sum_ip_local_kernel.
 static bool hoisted_sum_local(const he_ctx* c, uint32_t level, const uint32_t* gs, uint32_t T) {
     if (c->logN < 8 || num_digits(c, level) > HSL_MAX_TILES) return false;
-    const uint32_t mask = (1u << (c->logN - 3)) - 1;
+    const uint32_t mask = (1u << (c->logN - 7)) - 1;
     for (uint32_t t = 0; t < T; t++)
         if ((gs[t] & mask) != 1u) return false;
     return true;
@@ -1147,6 +1086,9 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
     for (uint32_t t = 0; t < T; t++)
         if (gs[t] == 1 || !evks[t]) return he_fail(c, HE_ERR_BADARG, "hoisted rotation sum: term %u does not rotate or has no key", t);
     if (2 * k > HE_MAX_MODULI) return he_fail(c, HE_ERR_BADARG, "key switch: more than %d special primes", HE_MAX_MODULI / 2);
+    if (!hoisted_sum_local(c, level, gs, T))
+        return he_fail(c, HE_ERR_BADARG, "hoisted rotation sum: a rotation is not by a multiple of N/512 slots, or more than %d digits",
+                       HSL_MAX_TILES);
     uint32_t cb, jb;
     engine_shape(c, level, J, J, cb, jb);
     jb = hoisted_sum_jb(c, level, J);
@@ -1158,7 +1100,6 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
     u64* conv = tmp_dn + (size_t)jb * 2 * k * N;
     for (uint32_t j0 = 0; j0 < J; j0 += jb) {
         const uint32_t nb = std::min(jb, J - j0);
-        const bool local = hoisted_sum_local(c, level, gs, T);
         for (uint32_t t0 = 0; t0 < nb; t0 += cb) {
             int32_t rc = modup_batch(c, srcs + j0 + t0, std::min(cb, nb - t0), level, raised + (size_t)t0 * beta * R * N, tmp_up);
             if (rc != HE_OK) return rc;
@@ -1170,8 +1111,7 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
             hc.T = std::min<uint32_t>(HE_MAX_KS_JOBS, T - t0);
             for (uint32_t t = 0; t < hc.T; t++) hc.g[t] = gs[t0 + t];
             for (uint32_t j = 0; j < nb; j++) hc.add[j] = t0 == 0 ? srcs[j0 + j].s0 : hc.s0[j];
-            if (local) hipLaunchKernelGGL(hoist_c0_sum_kernel<true>, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
-            else hipLaunchKernelGGL(hoist_c0_sum_kernel<false>, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
+            hipLaunchKernelGGL(hoist_c0_sum_kernel, dim3(N / KS_THREADS, L1, nb), dim3(KS_THREADS), 0, c->stream, hc, c->d_mc, c->logN);
             HE_HIP(c, hipGetLastError());
         }
         c->cnt.automorph += (uint64_t)nb * T * L1;
@@ -1190,9 +1130,9 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
             hi.J = nb; hi.T = std::min<uint32_t>(HS_TERMS, T - t0);
             for (uint32_t t = 0; t < hi.T; t++) { hi.evk[t] = evks[t0 + t]; hi.g[t] = gs[t0 + t]; }
             for (uint32_t j = 0; j < nb; j++) { hi.raised[j] = raised + (size_t)j * beta * R * N; hi.own[j] = srcs[j0 + j].c1; }
-            if (local) {
-                // limbs of moduli wider than 54 bits (bound by arithmetic: they fold every 7 pairs) spread evenly among the
-                // others (bound by the key reads), so that both kinds are resident together
+            {
+                // limbs of moduli wider than 54 bits (they move carries every 6 pairs) spread evenly among the others, so
+                // that both kinds are resident together
                 LimbSel sel;
                 {
                     uint32_t wide[HE_MAX_MODULI], narrow[HE_MAX_MODULI], nw = 0, nn = 0, iw = 0, in = 0;
@@ -1211,9 +1151,7 @@ int32_t ks_hoisted_sum(he_ctx* c, uint32_t level, const KsSrc* srcs, uint32_t J,
                                           c->M, level, c->nq, c->alpha, init)
                 if (nb <= 1) HSL_LAUNCH(1); else if (nb <= 2) HSL_LAUNCH(2); else if (nb <= 4) HSL_LAUNCH(4); else HSL_LAUNCH(8);
 #undef HSL_LAUNCH
-            } else
-                hipLaunchKernelGGL(hoisted_sum_ip_kernel, dim3(N / KS_THREADS, R), dim3(KS_THREADS), 0, c->stream, hi, acc, c->d_mc, c->logN, R,
-                                   beta, c->M, level, c->nq, c->alpha, t0 == 0 ? 1u : 0u);
+            }
             HE_HIP(c, hipGetLastError());
         }
         if (c->prof_on) c->prof_key_limbs += (uint64_t)T * 2 * beta * R;

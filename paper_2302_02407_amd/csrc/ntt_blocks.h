@@ -102,12 +102,15 @@ __device__ __forceinline__ void inv_block2_r(u64 (&x)[4], const u64 (&r)[6], u64
 }
 
 // v mod q for v < 100q: a 7-bit quotient estimated from the top bits (never too large, at most 2
-// too small), then two conditional subtractions.
-__device__ __forceinline__ u64 reduce_small(u64 v, u64 q, uint32_t bits, uint32_t mrec) {
+// too small), then two conditional subtractions.  The lazy form stops before them: a value below 3q congruent to v.
+__device__ __forceinline__ u64 reduce_small_lazy(u64 v, u64 q, uint32_t bits, uint32_t mrec) {
     const uint32_t sh = bits - 8;                       // q >> sh in [128, 256)
     uint32_t v1 = (uint32_t)(v >> sh);                  // < 100 * 256
     uint32_t qh = (v1 * mrec) >> 24;                    // mrec = floor(2^24 / ((q >> sh) + 1))
-    u64 r = v - (u64)qh * q;
+    return v - (u64)qh * q;
+}
+__device__ __forceinline__ u64 reduce_small(u64 v, u64 q, uint32_t bits, uint32_t mrec) {
+    u64 r = reduce_small_lazy(v, q, bits, mrec);
     r = csub(r, 2 * q);
     return csub(r, q);
 }

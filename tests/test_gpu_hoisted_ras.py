@@ -1,6 +1,6 @@
 """GPU parity for the rotate-and-sum of he_conv2d evaluated as one hoisted sum of rotations per output
 (hoisted_ras: one ModUp and one ModDown per output, keys shared by the outputs): bit-exact against the oracle on a
-small ring, on a two-pass ring, with 32 channel blocks (the form that gathers from memory), with 57/59-bit moduli and a
+small ring, on a two-pass ring, with 32 channel blocks (31 terms: two launches of the inner products), with 57/59-bit moduli and a
 single output, at N = 2^16 at level 5
 (single digit) and on the ResNet-20 layer at level 23 (three digits, eight outputs in one launch set), with operation
 counts; and
@@ -72,9 +72,10 @@ def test_two_pass_ring_with_deferred_taps():
     _run(prm, C_a=8, H=4, W=8, c_out=32, level=3, w_std=0.1, tol=1e-3, deferred_taps=True)
 
 
-def test_thirty_two_channel_blocks_gathered_form():
-    # C_a = 32: rotations by multiples of N/64 slots leave the aligned blocks of 16, so the inner products gather from
-    # memory instead of from LDS; 31 terms take two launches of at most 16 (the second continues the accumulators)
+def test_thirty_two_channel_blocks_two_launches():
+    # C_a = 32: rotations by multiples of N/64 slots leave the aligned blocks of 16 positions but stay inside the
+    # 256-position tiles the inner products stage in LDS; 31 terms take two launches of at most 16 (the second continues
+    # the stored accumulators)
     prm = toy_params(logN=12, q_bits=40, nq=4, p_bits=41, np_=2, dnum=2, scale=2.0 ** 30, hamming=32, seed=83)
     _run(prm, C_a=32, H=4, W=4, c_out=8, level=3, w_std=0.1, tol=1e-3)
 

@@ -57,3 +57,26 @@ def test_forms_agree_n65536():
     a = S.uniform_limbs(rng, [prm.moduli[i] for i in mods], prm.N)[0]
     g = o.galois_elt(1 << 14)
     assert (o.ntt(o.automorph_coef(a, mods, g), mods) == o.automorph_ntt(o.ntt(a, mods), g)).all()
+
+
+@pytest.mark.parametrize("logN", [9, 12, 16])
+def test_rotations_by_multiples_of_n_over_512_stay_inside_blocks_of_256_positions(logN):
+    """The layout fact that the LDS-staged hoisted sums rest on: in NTT form (bit-reversed evaluation order) a
+    rotation by a multiple of N/2^(b+1) slots permutes every aligned block of 2^b positions within itself - b = 8 is a
+    work group's tile, b = 4 holds for the rotate-and-sum amounts over up to 16 channel blocks - and a rotation by half
+    that amount does not."""
+    prm = toy_params(logN=logN, nq=1, np_=1) if logN < 16 else config_params(1)
+    o = Oracle.from_params(prm)
+    N = prm.N
+    pos = np.arange(N, dtype=np.uint64)                     # out[n] = pos[src(n)] = src(n)
+    for b in (8, 4):
+        if N >> (b + 1) == 0:
+            continue
+        unit = N >> (b + 1)
+        for mult in (1, 2, 3, (1 << b) - 1):
+            src = o.automorph_ntt(pos, o.galois_elt(unit * mult)).astype(np.int64)
+            assert sorted(src.tolist()) == list(range(N))
+            assert ((src >> b) == (np.arange(N) >> b)).all(), (logN, b, mult)
+        if unit >= 2:
+            src = o.automorph_ntt(pos, o.galois_elt(unit // 2)).astype(np.int64)
+            assert not ((src >> b) == (np.arange(N) >> b)).all()
